@@ -1,0 +1,247 @@
+#!/usr/bin/env python3
+"""Benchmark of the AASD hot path on one MI355X.
+
+One "step" is one pass of the whole hot path over one batch of synthetic input of the chosen
+workload, with all inputs resident in HBM before the timed region starts:
+    aasd_align_sample   over all prefill rows,
+    aasd_retrieve_drafts over the token buffers of every decode step,
+    aasd_verify         over the verify logits of every decode step
+(for the single-stream workloads the decode steps are processed as one batch, which is the
+throughput form; the sequential per-step latency is reported beside it).
+The metric is logit rows per second (prefill rows sampled + verify rows verified); the roofline
+block gives the achieved HBM bandwidth of the dominant kernel, the fused row sweep.
+
+Prints ONE JSON line.  `--gpus N` with N > 1 is refused: this build is single-GPU.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama3_single",
+                    choices=["tiny", "llama3_single", "long_context", "batched_serving", "stress_tree"])
+    ap.add_argument("--decode-steps", type=int, default=None, help="override the workload's number of decode steps")
+    ap.add_argument("--prefill-rows", type=int, default=None, help="cap on prefill rows held in HBM")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-latency", action="store_true")
+    ap.add_argument("--traffic-json", default=None, help="JSON file with measured HBM bytes per launch (from rocprofv3 --pmc)")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print(f"bench.py: this build runs on ONE GPU; --gpus {args.gpus} is not supported "
+              "(no collectives or sharding are part of it).", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2505_13204_amd as aasd
+    from paper_2505_13204_amd import _lib, harness, synth
+
+    _lib.load()  # no CPU fallback: fail loudly if the HIP library is missing
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    w = synth.WORKLOADS[args.workload]
+    if args.decode_steps:
+        w = synth.scaled(w, steps=args.decode_steps)
+    elt = 2 if w.dtype == "bf16" else 4
+
+    # ---------------------------------------------------------------- setup (untimed)
+    t_setup = time.time()
+    n_prefill_seq = w.B
+    prefill_rows = w.B * w.L
+    if args.prefill_rows and prefill_rows > args.prefill_rows:
+        n_prefill_seq = max(1, args.prefill_rows // w.L)
+        prefill_rows = n_prefill_seq * w.L
+    prefill = torch.empty((prefill_rows, w.V), dtype=w.torch_dtype, device=dev)
+    next_tok = np.empty(prefill_rows, dtype=np.int32)
+    for b in range(n_prefill_seq):
+        g, copied = synth.token_stream(w, b)
+        synth.prefill_logits(w, b, g, copied, dev, out=prefill[b * w.L:(b + 1) * w.L])
+        next_tok[b * w.L:(b + 1) * w.L] = synth.next_tokens(w, g)
+    next_tok_d = torch.from_numpy(next_tok).to(dev)
+    align_out = aasd.align_sample(prefill, next_tok_d, m=w.m, c=w.c, mode=aasd.EXTRAS_TOP, seed=w.seed)
+
+    # run the synthetic decode loop once on the HIP path to obtain every step's inputs
+    class Recorder(harness.Backend):
+        def __init__(self):
+            self.logits = []
+
+        def _d(self, a, dt):
+            return torch.as_tensor(np.ascontiguousarray(a), device=dev).to(dt)
+
+        def retrieve(self, tokens, length, prompt_len, w_, extras, n_extras):
+            out = aasd.retrieve_drafts(self._d(tokens, torch.int32), self._d(length, torch.int32),
+                                       self._d(prompt_len, torch.int32), w_.n_min, w_.n_max, w_.k, w_.C)
+            return {k: (v.cpu().numpy() if v is not None else None) for k, v in out.items()}
+
+        def make_logits(self, w_, step, gs, copieds, length, drafts, draft_len, peaked):
+            z = synth.verify_logits(w_, step, gs, copieds, length, drafts, draft_len, dev)
+            self.logits.append(z)
+            return z
+
+        def verify(self, logits, drafts, draft_len, strict, w_):
+            out = aasd.verify(logits, self._d(drafts, torch.int32), self._d(draft_len, torch.int32),
+                              self._d(strict, torch.uint8), alpha=w_.alpha, beta=w_.beta, want_rows=False,
+                              want_tokens=False, want_near=False)
+            return {k: v.cpu().numpy() for k, v in out.items() if v is not None and k != "workspace"}
+
+    # hold at most ~24 GiB of verify logits: later steps reuse the buffers of earlier ones in rotation
+    step_bytes = w.B * w.R * w.V * elt
+    max_steps_resident = max(1, min(w.steps, int(24 * 2 ** 30 // step_bytes)))
+    rec = Recorder()
+    trace = harness.decode(synth.scaled(w, steps=max_steps_resident), rec)
+    S = len(trace.steps)
+    BB = S * w.B  # decode steps x sequences, processed as one batch
+    verify_logits = torch.stack(rec.logits).view(BB, w.R, w.V)
+    rec.logits = None
+    tok_cap = trace.tokens.shape[1]
+    tokens_b = torch.from_numpy(np.tile(trace.tokens, (S, 1))).to(dev).contiguous()          # [S*B, cap]
+    len_b = torch.from_numpy(np.concatenate([s.length for s in trace.steps]).astype(np.int32)).to(dev)
+    plen_b = torch.full((BB,), w.L, dtype=torch.int32, device=dev)
+    r_out = aasd.retrieve_drafts(tokens_b, len_b, plen_b, w.n_min, w.n_max, w.k, w.C)
+    ws = torch.empty(max(16, aasd.verify_workspace_bytes(BB, w.C, w.k)), dtype=torch.uint8, device=dev)
+    v_out = aasd.verify(verify_logits, r_out["drafts"], r_out["draft_len"], r_out["strict"], alpha=w.alpha, beta=w.beta,
+                        workspace=ws, want_rows=False, want_tokens=False)
+    torch.cuda.synchronize()
+    # the batched pass must reproduce the sequential loop it stands for
+    seq_accept = np.concatenate([s.verified["accept_len"] for s in trace.steps])
+    assert (v_out["accept_len"].cpu().numpy() == seq_accept).all(), "batched verify differs from the decode loop"
+    setup_s = time.time() - t_setup
+
+    verify_rows = BB * w.R
+    rows_per_step = prefill_rows + verify_rows
+
+    def one_pass():
+        aasd.align_sample(prefill, next_tok_d, m=w.m, c=w.c, mode=aasd.EXTRAS_TOP, seed=w.seed, out=align_out)
+        aasd.retrieve_drafts(tokens_b, len_b, plen_b, w.n_min, w.n_max, w.k, w.C, out=r_out)
+        aasd.verify(verify_logits, r_out["drafts"], r_out["draft_len"], r_out["strict"], alpha=w.alpha, beta=w.beta,
+                    workspace=ws, want_rows=False, want_tokens=False, out=v_out)
+
+    for _ in range(args.warmup):
+        one_pass()
+    torch.cuda.synchronize()
+
+    # ---------------------------------------------------------------- timed region: exactly K steps
+    K = args.steps
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(K)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):
+        ev[i][0].record()
+        aasd.align_sample(prefill, next_tok_d, m=w.m, c=w.c, mode=aasd.EXTRAS_TOP, seed=w.seed, out=align_out)
+        ev[i][1].record()
+        aasd.retrieve_drafts(tokens_b, len_b, plen_b, w.n_min, w.n_max, w.k, w.C, out=r_out)
+        ev[i][2].record()
+        aasd.verify(verify_logits, r_out["drafts"], r_out["draft_len"], r_out["strict"], alpha=w.alpha, beta=w.beta,
+                    workspace=ws, want_rows=False, want_tokens=False, out=v_out)
+        ev[i][3].record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / K
+    value = rows_per_step / (ms_per_step * 1e-3)
+    align_ms = float(np.mean([ev[i][0].elapsed_time(ev[i][1]) for i in range(K)]))
+    retr_ms = float(np.mean([ev[i][1].elapsed_time(ev[i][2]) for i in range(K)]))
+    verify_ms = float(np.mean([ev[i][2].elapsed_time(ev[i][3]) for i in range(K)]))
+
+    row_bytes = w.V * elt
+    align_gbs = prefill_rows * row_bytes / (align_ms * 1e-3) / 1e9
+    verify_gbs = verify_rows * row_bytes / (verify_ms * 1e-3) / 1e9
+    traffic = None
+    if args.traffic_json and os.path.exists(args.traffic_json):
+        traffic = json.load(open(args.traffic_json))
+    # the dominant kernel is the row sweep; its verify instantiation moves the most bytes per step here
+    dom = "verify" if verify_ms >= align_ms else "align"
+    roofline = {
+        "bound": "hbm", "kernel": f"row_sweep_kernel ({dom} instantiation)",
+        "achieved": round(verify_gbs if dom == "verify" else align_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": round((verify_gbs if dom == "verify" else align_gbs) / HBM_PEAK_GBS, 4),
+        "traffic": traffic,
+        "bytes_per_launch": (verify_rows if dom == "verify" else prefill_rows) * row_bytes,
+        "avg_launch_ms": round(verify_ms if dom == "verify" else align_ms, 4),
+        "align_sample": {"rows": prefill_rows, "ms": round(align_ms, 4), "GB/s": round(align_gbs, 1),
+                         "frac": round(align_gbs / HBM_PEAK_GBS, 4)},
+        "verify": {"rows": verify_rows, "ms": round(verify_ms, 4), "GB/s": round(verify_gbs, 1),
+                   "frac": round(verify_gbs / HBM_PEAK_GBS, 4),
+                   "note": "events bracket the sweep and the per-sequence accept-scan kernel"},
+        "retrieve_drafts": {"sequences": BB, "ms": round(retr_ms, 4)},
+    }
+
+    # ---------------------------------------------------------------- sequential per-step latency (context)
+    latency = None
+    if not args.no_latency and w.B * w.R <= 512:
+        n_lat = min(S, 256)
+        outs_r = aasd.retrieve_drafts(tokens_b[:w.B], len_b[:w.B], plen_b[:w.B], w.n_min, w.n_max, w.k, w.C)
+        ws1 = torch.empty(max(16, aasd.verify_workspace_bytes(w.B, w.C, w.k)), dtype=torch.uint8, device=dev)
+        outs_v = aasd.verify(verify_logits[:w.B], outs_r["drafts"], outs_r["draft_len"], outs_r["strict"],
+                             workspace=ws1, want_rows=False, want_tokens=False)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for s in range(n_lat):
+            sl = slice(s * w.B, (s + 1) * w.B)
+            aasd.retrieve_drafts(tokens_b[sl], len_b[sl], plen_b[sl], w.n_min, w.n_max, w.k, w.C, out=outs_r)
+            aasd.verify(verify_logits[sl], outs_r["drafts"], outs_r["draft_len"], outs_r["strict"], alpha=w.alpha,
+                        beta=w.beta, workspace=ws1, want_rows=False, want_tokens=False, out=outs_v)
+        e1.record()
+        torch.cuda.synchronize()
+        latency = {"decode_steps": n_lat, "rows_per_step": w.B * w.R,
+                   "us_per_decode_step": round(e0.elapsed_time(e1) * 1e3 / n_lat, 2),
+                   "note": "retrieve + verify launched back to back per decode step, no host sync"}
+
+    # ---------------------------------------------------------------- CPU oracle on a bounded sample (context)
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        n_a = min(prefill_rows, 1024)
+        n_s = max(1, min(S, 1152 // (w.B * w.R)))
+        nb = n_s * w.B
+        bits_a = synth.to_host_bits(prefill[:n_a])
+        bits_v = synth.to_host_bits(verify_logits[:nb])
+        tok_h = tokens_b[:nb].cpu().numpy()
+        len_h = len_b[:nb].cpu().numpy()
+        plen_h = plen_b[:nb].cpu().numpy()
+        tc = time.perf_counter()
+        oracle.align_sample(bits_a, next_tok[:n_a], m_x=w.m, c=w.c)
+        r = oracle.retrieve_drafts(tok_h, len_h, plen_h, w.n_min, w.n_max, w.k, w.C)
+        oracle.verify(bits_v, r["drafts"], r["draft_len"], r["strict"], alpha=float(np.float32(w.alpha)),
+                      beta=float(np.float32(w.beta)))
+        dt = time.perf_counter() - tc
+        cpu = {"value": round((n_a + nb * w.R) / dt, 1), "unit": "rows/s", "cores": 1, "kind": "oracle",
+               "sample": f"first {n_a} prefill rows + first {n_s} decode steps ({nb * w.R} verify rows) of the same "
+                         f"workload, {dt:.1f} s", "host_cores_present": os.cpu_count()}
+
+    out = {
+        "metric": "logit rows/sec verified+sampled at V=%d %s" % (w.V, w.dtype),
+        "value": round(value, 1), "unit": "rows/s", "n_gpus": 1, "steps": K, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "prompt_len": w.L, "V": w.V, "logits_dtype": w.dtype, "k": w.k, "C": w.C,
+                   "n_gram": [w.n_min, w.n_max], "decode_steps": S, "prefill_rows": prefill_rows,
+                   "verify_rows": verify_rows, "rows_per_step": rows_per_step,
+                   "form": "all decode steps verified as one batch"},
+        "roofline": roofline, "cpu_baseline": cpu, "latency": latency,
+        "tokens_per_decode_step": round(trace.mean_accept_len, 3), "setup_s": round(setup_s, 1),
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

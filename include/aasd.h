@@ -1,0 +1,181 @@
+/*
+ * aasd.h - C ABI of the MI355X (gfx950) hot path of Alignment-Augmented
+ * Speculative Decoding: alignment sampling over prefill logits, n-gram draft
+ * retrieval over the token buffer, and conditional verification of draft
+ * candidates against the target model's logits.
+ *
+ * Conventions shared by every entry point
+ *   - Pointers named in "DEVICE" lists are device (HBM) pointers owned by the
+ *     caller; the library never allocates, frees or retains them.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls only enqueue work; outputs are valid once the caller has
+ *     synchronised the stream.  There is no host synchronisation inside.
+ *   - Return value: AASD_OK (0) or a negative aasd_status.  On an error nothing
+ *     is enqueued.  aasd_last_error() returns a thread-local message for the
+ *     last failing call on the calling thread.  No exception crosses the ABI.
+ *   - A call with zero rows / zero sequences succeeds and enqueues nothing.
+ *   - Logits must be finite or -inf, with at least one finite value per row;
+ *     NaN or +inf logits give unspecified numbers (never a fault).
+ *   - All reductions have a fixed order and no floating-point atomics are
+ *     used: the same inputs give byte-identical outputs on every run.
+ */
+#ifndef AASD_H
+#define AASD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    AASD_OK = 0,
+    AASD_ERR_INVALID_ARG = -1, /* null required pointer, size or parameter out of range */
+    AASD_ERR_UNSUPPORTED = -2, /* valid request this build cannot serve (e.g. misaligned base pointer) */
+    AASD_ERR_WORKSPACE = -3,   /* workspace missing or too small */
+    AASD_ERR_LAUNCH = -4       /* the HIP runtime refused a launch */
+} aasd_status;
+
+typedef enum { AASD_F32 = 0, AASD_BF16 = 1 } aasd_dtype;
+
+/* how the extra draft tokens of a misaligned position are chosen */
+typedef enum {
+    AASD_EXTRAS_TOP = 0,   /* best-ranked first (Fig. 2: the rank-1 and rank-2 tokens) */
+    AASD_EXTRAS_SAMPLE = 1 /* seeded draws without replacement, proportional to probability */
+} aasd_extras_mode;
+
+/* aasd_verify flags */
+#define AASD_VERIFY_NO_CLAMP 1u /* threshold alpha*H+beta without the min with Delta (Eq. 3 when alpha = 0) */
+
+/* limits */
+#define AASD_MAX_EXTRAS 4      /* m */
+#define AASD_MAX_CANDSET 8     /* c */
+#define AASD_MAX_KEY 8         /* n_max */
+#define AASD_MAX_DRAFT 16      /* k */
+#define AASD_MAX_CANDIDATES 32 /* C */
+
+const char *aasd_version(void);
+const char *aasd_last_error(void);
+
+/*
+ * Alignment sampling over the prefill logits (Sec. 2.3 for aligned/misaligned
+ * positions; Sec. 3.2 and the caption of Fig. 2 for the extra tokens; Sec. 4.1
+ * for the cap of two extras per position).
+ *
+ * For every row r of logits[rows, V] (row-major, consecutive rows `row_stride`
+ * elements apart, temperature-1 softmax):
+ *   argmax[r]     smallest token id that attains the row maximum (the greedy pick)
+ *   entropy[r]    H = -sum_v p_v ln p_v in nats
+ *   p_max[r]      max_v p_v
+ *   and, when next_tok[r] is a token id (the prompt token that follows row r):
+ *   rank[r]       number of tokens with a strictly larger logit than next_tok[r]
+ *   misaligned[r] 1 iff rank[r] > 0, i.e. the prompt's next token is not a greedy pick
+ *   p_next[r]     probability of next_tok[r]
+ *   extras[r,:]   for misaligned rows, up to m of the tokens that are strictly more likely
+ *                 than next_tok[r], taken from the c best tokens of the row (logit descending,
+ *                 id ascending): in TOP mode the best min(m, .) of them in rank order; in
+ *                 SAMPLE mode, if more than m qualify, m draws without replacement with
+ *                 probability proportional to p.  Draw j of row r uses the first word of
+ *                 Philox4x32-10(counter = (lo32(id), hi32(id), j, 0x41415344),
+ *                 key = (lo32(seed), hi32(seed))), id = row_id_base + r, as u = (word >> 8) / 2^24
+ *                 and picks the first remaining candidate whose running weight sum exceeds
+ *                 u * (total remaining weight).  Unused slots hold -1.
+ *   n_extras[r]   number of valid entries in extras[r,:]
+ *   Rows with next_tok[r] < 0 (or >= V) get misaligned = 0, p_next = 0, rank = -1, no extras.
+ *
+ * DEVICE in : logits (dtype dt; base pointer aligned to the element size), next_tok[rows]
+ *             (NULL = no row has a next token)
+ * DEVICE out: argmax[rows] i32, misaligned[rows] u8, entropy[rows] f32, p_next[rows] f32,
+ *             p_max[rows] f32 (all required); rank[rows] i32 (NULL = not wanted);
+ *             extras[rows, m] i32 and n_extras[rows] u8 (required when m > 0);
+ *             near_count: one u32 that is INCREMENTED by the number of SAMPLE draws that fell
+ *             within 1e-6 (relative to the total weight) of a boundary between two picks
+ *             (NULL = not wanted; the caller zeroes it).
+ * Parameters: 0 <= m <= 4, max(m,1) <= c <= 8, rows >= 0, V >= 1, row_stride >= V.
+ */
+int aasd_align_sample(const void *logits, int32_t dt, int64_t rows, int32_t V, int64_t row_stride,
+                      const int32_t *next_tok, int32_t m, int32_t c, int32_t mode, uint64_t seed,
+                      uint64_t row_id_base, int32_t *argmax, uint8_t *misaligned, float *entropy,
+                      float *p_next, float *p_max, int32_t *rank, int32_t *extras,
+                      uint8_t *n_extras, uint32_t *near_count, void *stream);
+
+/*
+ * n-gram draft retrieval (Sec. 3.1; Algorithm 1: draft-pool initialisation and the
+ * longest-key-first lookup).  Stateless: instead of keeping the dictionary, each call
+ * scans the token buffer and returns the positions the dictionary would hold.
+ *
+ * For every sequence b with context tokens[b, 0 .. len[b]):
+ *   for n = n_max down to n_min, the hits of key length n are the positions p in
+ *   [n, len-1] whose n preceding tokens equal the last n tokens of the context; the
+ *   first n with at least one hit wins (key_len[b] = n, 0 if none).  The candidates are
+ *   the hits in descending p (latest occurrence first), at most C of them (n_cand[b]).
+ *   Candidate c copies draft_len[b,c] = min(k, len - p) tokens tokens[p ..] into
+ *   drafts[b,c,:] (-1 padded), records p in src_pos[b,c] (-1 if absent), and marks
+ *   strict[b,c,j] = 1 iff the j-th token was copied from generated context
+ *   (p + j >= prompt_len[b]); such tokens are to be verified strictly (Sec. 3.3).
+ *   With an alignment table (extras/n_extras from aasd_align_sample, row
+ *   b*extras_stride + i = prefill row i of sequence b), draft_extras[b,c,j,:] holds
+ *   the extra tokens of the prefill row that predicted position p + j (row p+j-1,
+ *   only when p + j <= prompt_len - 1), else -1.
+ *
+ * DEVICE in : tokens[B, tok_stride] i32, len[B] i32 (0 <= len <= tok_stride; other
+ *             values are treated as an empty context), prompt_len[B] i32,
+ *             extras / n_extras (both NULL, or both given with 1 <= m <= 4)
+ * DEVICE out: drafts[B,C,k] i32, draft_len[B,C] i32, src_pos[B,C] i32, n_cand[B] i32,
+ *             key_len[B] i32, strict[B,C,k] u8 (all required);
+ *             draft_extras[B,C,k,m] i32 (NULL = not wanted; needs the table)
+ * Parameters: 1 <= n_min <= n_max <= 8, 1 <= k <= 16, 1 <= C <= 32, B >= 0, tok_stride >= 1.
+ */
+int aasd_retrieve_drafts(const int32_t *tokens, int64_t tok_stride, const int32_t *len,
+                         const int32_t *prompt_len, int32_t B, int32_t n_min, int32_t n_max,
+                         int32_t k, int32_t C, const int32_t *extras, const uint8_t *n_extras,
+                         int32_t m, int64_t extras_stride, int32_t *drafts, int32_t *draft_len,
+                         int32_t *src_pos, int32_t *n_cand, int32_t *key_len,
+                         int32_t *draft_extras, uint8_t *strict, void *stream);
+
+/* Bytes of device workspace aasd_verify needs for B sequences of C candidates of k tokens
+ * (0 on invalid arguments). */
+size_t aasd_verify_workspace_bytes(int32_t B, int32_t C, int32_t k);
+
+/*
+ * Conditional verification (Sec. 3.3, Eq. 4-6; the cascade rule of Sec. 2.1; "the longest
+ * draft candidate that passes" of Sec. 3.3).
+ *
+ * logits[B, R, V] with R = 1 + C*k rows per sequence: row 0 is the distribution after the
+ * last committed token, row 1 + c*k + (j-1) the distribution after the j-th (1-based)
+ * draft token of candidate c.  Element (b, r, v) is at b*seq_stride + r*row_stride + v.
+ * The j-th token t of candidate c is verified by row rho = 0 (j = 1) or 1 + c*k + (j-2):
+ *   p     = softmax(row rho)[t]
+ *   Delta = max_v softmax(row rho)[v]                                  (Eq. 6)
+ *   delta = min(alpha * H(row rho) + beta, Delta), H in nats           (Eq. 5)
+ *           (strict token: delta = Delta; AASD_VERIFY_NO_CLAMP: delta = alpha*H + beta)
+ *   pass  = p >= delta, and a token whose logit equals the row maximum always
+ *           passes (not under AASD_VERIFY_NO_CLAMP)                    (Eq. 4)
+ * A token id outside [0, V) fails.  accept_len[b] is the largest number of leading passes
+ * over the candidates (at most draft_len), best_cand[b] the lowest candidate index that
+ * reaches it, next_token[b] the greedy pick of the row after the last accepted token
+ * (row 0 if nothing was accepted).
+ *
+ * DEVICE in : logits, drafts[B,C,k] i32, draft_len[B,C] i32 (clamped to [0,k]),
+ *             strict[B,C,k] u8 (NULL = no token is strict)
+ * DEVICE out: accept_len[B], best_cand[B], next_token[B] i32 (required);
+ *             row_entropy[B,R] f32, row_pmax[B,R] f32, row_argmax[B,R] i32 (each NULL = not wanted);
+ *             tok_p[B,C,k], tok_delta[B,C,k] f32 (0 beyond draft_len; NULL = not wanted);
+ *             near_count[B] u32 = number of evaluated tokens (up to and including each
+ *             candidate's first failure) with |p - delta| < 1e-6 (NULL = not wanted)
+ * workspace : DEVICE scratch of at least aasd_verify_workspace_bytes(B, C, k) bytes, 16-byte aligned
+ * Parameters: 1 <= k <= 16, 1 <= C <= 32, V >= 1, row_stride >= V, seq_stride >= R*row_stride.
+ */
+int aasd_verify(const void *logits, int32_t dt, int32_t B, int32_t C, int32_t k, int32_t V,
+                int64_t row_stride, int64_t seq_stride, const int32_t *drafts,
+                const int32_t *draft_len, const uint8_t *strict, float alpha, float beta,
+                uint32_t flags, int32_t *accept_len, int32_t *best_cand, int32_t *next_token,
+                float *row_entropy, float *row_pmax, int32_t *row_argmax, float *tok_p,
+                float *tok_delta, uint32_t *near_count, void *workspace, size_t workspace_bytes,
+                void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AASD_H */

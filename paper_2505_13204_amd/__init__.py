@@ -1,0 +1,190 @@
+"""MI355X-native hot path of Alignment-Augmented Speculative Decoding (AASD).
+
+Thin Python binding over the C ABI in ``include/aasd.h``: argument marshalling only.
+Every step of the path (alignment sampling, n-gram draft retrieval, conditional
+verification) runs in the hand-written HIP kernels of ``libaasd.so``; PyTorch is used
+for device memory and streams, nothing else.  There is no CPU fallback.
+"""
+from __future__ import annotations
+
+from typing import Optional
+
+import torch
+
+from . import _lib
+
+F32, BF16 = 0, 1
+EXTRAS_TOP, EXTRAS_SAMPLE = 0, 1
+VERIFY_NO_CLAMP = 1
+
+MAX_EXTRAS, MAX_CANDSET, MAX_KEY, MAX_DRAFT, MAX_CANDIDATES = 4, 8, 8, 16, 32
+HASH_BASE = 0x9E3779B1  # multiplier of the retrieval kernel's window hash (mod 2^32)
+
+
+class AasdError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"aasd error {code}: {message}")
+        self.code = code
+
+
+def version() -> str:
+    return _lib.load().aasd_version().decode()
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise AasdError(rc, _lib.load().aasd_last_error().decode())
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"logits must be float32 or bfloat16, got {t.dtype}")
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else t.data_ptr()
+
+
+def _stream(device) -> int:
+    return torch.cuda.current_stream(device).cuda_stream
+
+
+def _dev_check(*tensors):
+    for t in tensors:
+        if t is not None and not t.is_cuda:
+            raise ValueError("all tensors must live on the GPU")
+
+
+def align_sample(logits: torch.Tensor, next_tok: Optional[torch.Tensor], m: int = 2, c: int = 4,
+                 mode: int = EXTRAS_TOP, seed: int = 0, row_id_base: int = 0, V: Optional[int] = None,
+                 want_rank: bool = True, near_count: Optional[torch.Tensor] = None, out: Optional[dict] = None):
+    """aasd_align_sample over logits[rows, row_stride] (fp32 or bf16, rows contiguous in memory).
+
+    Returns a dict of device tensors: argmax, misaligned, entropy, p_next, p_max, rank (or None),
+    extras [rows, m], n_extras.  ``out`` may carry preallocated tensors of the same names."""
+    _dev_check(logits, next_tok, near_count)
+    assert logits.dim() == 2 and logits.stride(1) == 1
+    rows, row_stride = logits.shape[0], logits.stride(0) if logits.shape[0] > 1 else logits.shape[1]
+    V = logits.shape[1] if V is None else V
+    dev = logits.device
+    if out is None:
+        out = {}
+    o = dict(
+        argmax=out.get("argmax", None), misaligned=out.get("misaligned", None), entropy=out.get("entropy", None),
+        p_next=out.get("p_next", None), p_max=out.get("p_max", None), rank=out.get("rank", None),
+        extras=out.get("extras", None), n_extras=out.get("n_extras", None))
+    if o["argmax"] is None: o["argmax"] = torch.empty(rows, dtype=torch.int32, device=dev)
+    if o["misaligned"] is None: o["misaligned"] = torch.empty(rows, dtype=torch.uint8, device=dev)
+    if o["entropy"] is None: o["entropy"] = torch.empty(rows, dtype=torch.float32, device=dev)
+    if o["p_next"] is None: o["p_next"] = torch.empty(rows, dtype=torch.float32, device=dev)
+    if o["p_max"] is None: o["p_max"] = torch.empty(rows, dtype=torch.float32, device=dev)
+    if o["rank"] is None and want_rank: o["rank"] = torch.empty(rows, dtype=torch.int32, device=dev)
+    if o["extras"] is None: o["extras"] = torch.empty((rows, m), dtype=torch.int32, device=dev)
+    if o["n_extras"] is None: o["n_extras"] = torch.empty(rows, dtype=torch.uint8, device=dev)
+    if next_tok is not None:
+        assert next_tok.dtype == torch.int32 and next_tok.is_contiguous() and next_tok.numel() == rows
+    rc = _lib.load().aasd_align_sample(
+        logits.data_ptr(), _dtype_code(logits), rows, V, row_stride, _ptr(next_tok), m, c, mode,
+        seed & 0xFFFFFFFFFFFFFFFF, row_id_base & 0xFFFFFFFFFFFFFFFF,
+        o["argmax"].data_ptr(), o["misaligned"].data_ptr(), o["entropy"].data_ptr(), o["p_next"].data_ptr(),
+        o["p_max"].data_ptr(), _ptr(o["rank"]), o["extras"].data_ptr(), o["n_extras"].data_ptr(),
+        _ptr(near_count), _stream(dev))
+    _check(rc)
+    return o
+
+
+def retrieve_drafts(tokens: torch.Tensor, length: torch.Tensor, prompt_len: torch.Tensor, n_min: int, n_max: int,
+                    k: int, C: int, extras: Optional[torch.Tensor] = None, n_extras: Optional[torch.Tensor] = None,
+                    m: int = 0, extras_stride: int = 0, want_draft_extras: Optional[bool] = None,
+                    out: Optional[dict] = None):
+    """aasd_retrieve_drafts over tokens[B, tok_stride] (int32).  Returns a dict of device tensors:
+    drafts [B,C,k], draft_len [B,C], src_pos [B,C], n_cand [B], key_len [B], strict [B,C,k],
+    draft_extras [B,C,k,m] or None."""
+    _dev_check(tokens, length, prompt_len, extras, n_extras)
+    assert tokens.dim() == 2 and tokens.dtype == torch.int32 and tokens.stride(1) == 1
+    B = tokens.shape[0]
+    tok_stride = tokens.stride(0) if B > 1 else tokens.shape[1]
+    assert length.dtype == torch.int32 and prompt_len.dtype == torch.int32
+    dev = tokens.device
+    have_table = extras is not None
+    if want_draft_extras is None:
+        want_draft_extras = have_table
+    if out is None:
+        out = {}
+    o = dict(out)
+    def need(name, shape, dtype):
+        if o.get(name) is None:
+            o[name] = torch.empty(shape, dtype=dtype, device=dev)
+    need("drafts", (B, C, k), torch.int32)
+    need("draft_len", (B, C), torch.int32)
+    need("src_pos", (B, C), torch.int32)
+    need("n_cand", (B,), torch.int32)
+    need("key_len", (B,), torch.int32)
+    need("strict", (B, C, k), torch.uint8)
+    if want_draft_extras:
+        need("draft_extras", (B, C, k, m), torch.int32)
+    else:
+        o["draft_extras"] = None
+    rc = _lib.load().aasd_retrieve_drafts(
+        tokens.data_ptr(), tok_stride, length.data_ptr(), prompt_len.data_ptr(), B, n_min, n_max, k, C,
+        _ptr(extras), _ptr(n_extras), m, extras_stride,
+        o["drafts"].data_ptr(), o["draft_len"].data_ptr(), o["src_pos"].data_ptr(), o["n_cand"].data_ptr(),
+        o["key_len"].data_ptr(), _ptr(o["draft_extras"]), o["strict"].data_ptr(), _stream(dev))
+    _check(rc)
+    return o
+
+
+def verify_workspace_bytes(B: int, C: int, k: int) -> int:
+    return int(_lib.load().aasd_verify_workspace_bytes(B, C, k))
+
+
+def verify(logits: torch.Tensor, drafts: torch.Tensor, draft_len: torch.Tensor, strict: Optional[torch.Tensor] = None,
+           alpha: float = 0.1, beta: float = 0.1, flags: int = 0, V: Optional[int] = None,
+           want_rows: bool = True, want_tokens: bool = True, want_near: bool = True,
+           workspace: Optional[torch.Tensor] = None, out: Optional[dict] = None):
+    """aasd_verify over logits[B, R, row_stride], R = 1 + C*k, drafts [B,C,k], draft_len [B,C].
+
+    Returns a dict of device tensors: accept_len, best_cand, next_token [B]; row_entropy, row_pmax,
+    row_argmax [B,R]; tok_p, tok_delta [B,C,k]; near_count [B] (the optional ones may be None)."""
+    _dev_check(logits, drafts, draft_len, strict, workspace)
+    assert logits.dim() == 3 and logits.stride(2) == 1
+    B, R = logits.shape[0], logits.shape[1]
+    assert drafts.dtype == torch.int32 and drafts.is_contiguous() and draft_len.dtype == torch.int32
+    _, C, k = drafts.shape
+    assert R == 1 + C * k, (R, C, k)
+    row_stride = logits.stride(1)
+    seq_stride = logits.stride(0) if B > 1 else R * row_stride
+    V = logits.shape[2] if V is None else V
+    dev = logits.device
+    if out is None:
+        out = {}
+    o = dict(out)
+    def need(name, shape, dtype, wanted=True):
+        if not wanted:
+            o[name] = None
+        elif o.get(name) is None:
+            o[name] = torch.empty(shape, dtype=dtype, device=dev)
+    need("accept_len", (B,), torch.int32)
+    need("best_cand", (B,), torch.int32)
+    need("next_token", (B,), torch.int32)
+    need("row_entropy", (B, R), torch.float32, want_rows)
+    need("row_pmax", (B, R), torch.float32, want_rows)
+    need("row_argmax", (B, R), torch.int32, want_rows)
+    need("tok_p", (B, C, k), torch.float32, want_tokens)
+    need("tok_delta", (B, C, k), torch.float32, want_tokens)
+    need("near_count", (B,), torch.int32, want_near)
+    ws_bytes = verify_workspace_bytes(B, C, k)
+    if workspace is None:
+        workspace = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
+    rc = _lib.load().aasd_verify(
+        logits.data_ptr(), _dtype_code(logits), B, C, k, V, row_stride, seq_stride,
+        drafts.data_ptr(), draft_len.data_ptr(), _ptr(strict), float(alpha), float(beta), flags,
+        o["accept_len"].data_ptr(), o["best_cand"].data_ptr(), o["next_token"].data_ptr(),
+        _ptr(o["row_entropy"]), _ptr(o["row_pmax"]), _ptr(o["row_argmax"]), _ptr(o["tok_p"]), _ptr(o["tok_delta"]),
+        _ptr(o["near_count"]), workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream(dev))
+    _check(rc)
+    o["workspace"] = workspace
+    return o

@@ -1,0 +1,110 @@
+// Device helpers shared by the AASD kernels (gfx950, wave64).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "aasd.h"
+
+namespace aasd {
+
+constexpr int kWave = 64;
+constexpr float kLog2e = 1.4426950408889634f;   // fp32(log2 e); every exponent below uses this one value
+constexpr double kLn2 = 0.69314718055994530942;
+constexpr float kNegHuge = -1.0e30f;             // finite stand-in for -inf in the clamped sweep
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+template <int DT> struct Elt;
+template <> struct Elt<AASD_BF16> {
+    static constexpr int kBytes = 2;
+    static constexpr int kPerVec = 8;  // elements in one 16-byte load
+};
+template <> struct Elt<AASD_F32> {
+    static constexpr int kBytes = 4;
+    static constexpr int kPerVec = 4;
+};
+
+__device__ __forceinline__ float bits_to_float(uint32_t b) { return __uint_as_float(b); }
+
+// One element of a row, widened exactly to fp32.
+template <int DT>
+__device__ __forceinline__ float load_elt(const void* row, int64_t idx)
+{
+    if constexpr (DT == AASD_BF16) {
+        return bits_to_float((uint32_t)((const uint16_t*)row)[idx] << 16);
+    } else {
+        return ((const float*)row)[idx];
+    }
+}
+
+// The elements of one 16-byte vector in memory order.
+template <int DT>
+__device__ __forceinline__ void unpack(const u32x4& v, float (&z)[Elt<DT>::kPerVec])
+{
+    if constexpr (DT == AASD_BF16) {
+        // bf16 is the upper half of an fp32: the low element of each dword moves up, the high one is masked
+        z[0] = bits_to_float(v.x << 16); z[1] = bits_to_float(v.x & 0xffff0000u);
+        z[2] = bits_to_float(v.y << 16); z[3] = bits_to_float(v.y & 0xffff0000u);
+        z[4] = bits_to_float(v.z << 16); z[5] = bits_to_float(v.z & 0xffff0000u);
+        z[6] = bits_to_float(v.w << 16); z[7] = bits_to_float(v.w & 0xffff0000u);
+    } else {
+        z[0] = bits_to_float(v.x); z[1] = bits_to_float(v.y);
+        z[2] = bits_to_float(v.z); z[3] = bits_to_float(v.w);
+    }
+}
+
+// Butterfly reductions over the 64 lanes of a wave; every lane ends with the result and the
+// combination order is fixed, so sums are reproducible.
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+__device__ __forceinline__ unsigned wave_sum(unsigned v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+__device__ __forceinline__ int wave_min(int v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = min(v, __shfl_xor(v, o));
+    return v;
+}
+
+// Total order used for "best token": larger logit first, then smaller id.
+__device__ __forceinline__ bool better(float za, int ia, float zb, int ib)
+{
+    return za > zb || (za == zb && ia < ib);
+}
+__device__ __forceinline__ void wave_best(float& z, int& i)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        float oz = __shfl_xor(z, o);
+        int oi = __shfl_xor(i, o);
+        if (better(oz, oi, z, i)) { z = oz; i = oi; }
+    }
+}
+
+// Philox4x32 with 10 rounds (Salmon et al., SC'11): counter-based, integer only.
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                              uint32_t k0, uint32_t k1, uint32_t (&out)[4])
+{
+    constexpr uint32_t kMul0 = 0xD2511F53u, kMul1 = 0xCD9E8D57u;
+    constexpr uint32_t kWeyl0 = 0x9E3779B9u, kWeyl1 = 0xBB67AE85u;
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint32_t hi0 = __umulhi(kMul0, c0), lo0 = kMul0 * c0;
+        const uint32_t hi1 = __umulhi(kMul1, c2), lo1 = kMul1 * c2;
+        const uint32_t n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
+        c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+        k0 += kWeyl0; k1 += kWeyl1;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+}  // namespace aasd

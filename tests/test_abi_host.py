@@ -1,0 +1,97 @@
+"""Host-side checks of the C ABI: the library loads without a GPU, exports every symbol the
+header declares, and rejects invalid arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2505_13204_amd import _lib, build
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+INVALID, UNSUPPORTED, WORKSPACE = -1, -2, -3
+FAKE = 0x10000  # a non-null, 16-byte aligned address that is never dereferenced on the host
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(_lib.LIB_PATH):
+        build.build(verbose=False)
+    return _lib.load()
+
+
+def test_exports_every_declared_symbol(lib):
+    header = open(os.path.join(ROOT, "include", "aasd.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = set(re.findall(r"\b(aasd_[a-z_]+)\s*\(", header))
+    assert {"aasd_version", "aasd_last_error", "aasd_align_sample", "aasd_retrieve_drafts",
+            "aasd_verify_workspace_bytes", "aasd_verify"} <= names
+    for n in names:
+        assert hasattr(lib, n), n
+    assert b"gfx950" in lib.aasd_version()
+
+
+def _align(lib, **kw):
+    a = dict(logits=FAKE, dt=1, rows=4, V=100, row_stride=100, next_tok=FAKE, m=2, c=4, mode=0, seed=0, base=0,
+             argmax=FAKE, mis=FAKE, ent=FAKE, pn=FAKE, pm=FAKE, rank=FAKE, extras=FAKE, nx=FAKE, near=None, stream=None)
+    a.update(kw)
+    return lib.aasd_align_sample(a["logits"], a["dt"], a["rows"], a["V"], a["row_stride"], a["next_tok"], a["m"], a["c"],
+                                 a["mode"], a["seed"], a["base"], a["argmax"], a["mis"], a["ent"], a["pn"], a["pm"],
+                                 a["rank"], a["extras"], a["nx"], a["near"], a["stream"])
+
+
+def test_align_sample_rejects_invalid_arguments(lib):
+    for kw in [dict(dt=7), dict(rows=-1), dict(V=0), dict(row_stride=99), dict(m=5), dict(m=-1), dict(c=1), dict(c=9),
+               dict(m=0, c=0), dict(mode=2), dict(logits=None), dict(argmax=None), dict(ent=None), dict(extras=None),
+               dict(nx=None)]:
+        assert _align(lib, **kw) == INVALID, kw
+        assert lib.aasd_last_error() != b""
+    assert _align(lib, logits=FAKE + 1) == UNSUPPORTED
+    assert _align(lib, rows=0, logits=None) == 0  # empty call is a successful no-op
+
+
+def _retrieve(lib, **kw):
+    a = dict(tokens=FAKE, stride=64, len=FAKE, plen=FAKE, B=2, n_min=2, n_max=4, k=8, C=4, extras=None, nx=None, m=0,
+             xs=0, drafts=FAKE, dl=FAKE, sp=FAKE, nc=FAKE, kl=FAKE, dx=None, strict=FAKE, stream=None)
+    a.update(kw)
+    return lib.aasd_retrieve_drafts(a["tokens"], a["stride"], a["len"], a["plen"], a["B"], a["n_min"], a["n_max"], a["k"],
+                                    a["C"], a["extras"], a["nx"], a["m"], a["xs"], a["drafts"], a["dl"], a["sp"], a["nc"],
+                                    a["kl"], a["dx"], a["strict"], a["stream"])
+
+
+def test_retrieve_drafts_rejects_invalid_arguments(lib):
+    for kw in [dict(B=-1), dict(stride=0), dict(n_min=0), dict(n_min=5), dict(n_max=9), dict(k=0), dict(k=17), dict(C=0),
+               dict(C=33), dict(tokens=None), dict(len=None), dict(drafts=None), dict(strict=None),
+               dict(extras=FAKE), dict(extras=FAKE, nx=FAKE, m=0), dict(extras=FAKE, nx=FAKE, m=5), dict(dx=FAKE)]:
+        assert _retrieve(lib, **kw) == INVALID, kw
+    assert _retrieve(lib, B=0, tokens=None) == 0
+
+
+def _verify(lib, **kw):
+    a = dict(logits=FAKE, dt=1, B=2, C=2, k=4, V=100, rs=100, ss=900, drafts=FAKE, dl=FAKE, strict=None, alpha=0.1,
+             beta=0.1, flags=0, al=FAKE, bc=FAKE, nt=FAKE, re=None, rp=None, ra=None, tp=None, td=None, near=None,
+             ws=FAKE, wsb=1 << 20, stream=None)
+    a.update(kw)
+    return lib.aasd_verify(a["logits"], a["dt"], a["B"], a["C"], a["k"], a["V"], a["rs"], a["ss"], a["drafts"], a["dl"],
+                           a["strict"], a["alpha"], a["beta"], a["flags"], a["al"], a["bc"], a["nt"], a["re"], a["rp"],
+                           a["ra"], a["tp"], a["td"], a["near"], a["ws"], a["wsb"], a["stream"])
+
+
+def test_verify_rejects_invalid_arguments(lib):
+    for kw in [dict(dt=-1), dict(B=-1), dict(C=0), dict(C=33), dict(k=0), dict(k=17), dict(V=0), dict(rs=99), dict(ss=899),
+               dict(flags=2), dict(logits=None), dict(drafts=None), dict(dl=None), dict(al=None), dict(nt=None)]:
+        assert _verify(lib, **kw) == INVALID, kw
+    assert _verify(lib, logits=FAKE + 1) == UNSUPPORTED
+    assert _verify(lib, ws=None) == WORKSPACE
+    assert _verify(lib, wsb=2 * 9 * 16 - 1) == WORKSPACE
+    assert _verify(lib, ws=FAKE + 4) == WORKSPACE
+    assert b"workspace" in lib.aasd_last_error()
+    assert _verify(lib, B=0) == 0
+
+
+def test_workspace_query(lib):
+    assert lib.aasd_verify_workspace_bytes(2, 2, 4) == 2 * 9 * 16
+    assert lib.aasd_verify_workspace_bytes(64, 16, 8) == 64 * 129 * 16
+    assert lib.aasd_verify_workspace_bytes(1, 0, 4) == 0
+    assert lib.aasd_verify_workspace_bytes(1, 4, 17) == 0
+    assert lib.aasd_verify_workspace_bytes(0, 1, 1) == 0

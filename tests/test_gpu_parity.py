@@ -1,0 +1,321 @@
+"""Parity of the HIP path with the CPU oracle, element by element, on the same seeded inputs.
+
+Bar: integers, bytes and indices bit-exact (decisions whose oracle margin is below 1e-6 are
+counted instead); probabilities and entropies within 1e-5 relative (fp32 accumulation).
+All calls go through the Python binding, i.e. through the C ABI of libaasd.so.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2505_13204_amd as aasd
+from paper_2505_13204_amd import harness, synth
+from tests import backends as bk
+from tests.util import to_bf16_bits
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _dev_logits(z: np.ndarray, dtype: str):
+    t = torch.from_numpy(np.ascontiguousarray(z, dtype=np.float32)).to(DEV)
+    return t.to(torch.bfloat16) if dtype == "bf16" else t
+
+
+def _random_rows(rng, rows, V, dtype, sigma=1.7, coarse=False):
+    z = rng.standard_normal((rows, V)).astype(np.float32) * sigma
+    if coarse:
+        z = np.round(z * 2) / 2  # many exact ties
+    return _dev_logits(z, dtype)
+
+
+# --------------------------------------------------------------------------- alignment sampling
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("V", [1, 5, 8, 9, 63, 1000, 4099, 32000])
+def test_align_shapes_and_tails(dtype, V):
+    rng = np.random.default_rng(V)
+    rows = 37
+    z = _random_rows(rng, rows, V, dtype)
+    nt = rng.integers(-1, V, size=rows).astype(np.int32)
+    tally = bk.Tally()
+    for mode in (oracle.EXTRAS_TOP, oracle.EXTRAS_SAMPLE):
+        got = bk.hip_align(z, nt, 2, 4, mode, seed=5, row_id_base=77)
+        ref = bk.oracle_align(z, nt, 2, 4, mode, seed=5, row_id_base=77)
+        bk.compare_align(got, ref, tally, mode)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("pad", [1, 3, 8, 13])
+def test_align_unaligned_row_stride(dtype, pad):
+    """row_stride != V: rows start at every 16-byte phase, so head and tail scalars are exercised."""
+    rng = np.random.default_rng(pad)
+    rows, V = 41, 5003
+    full = _random_rows(rng, rows, V + pad, dtype)
+    nt = rng.integers(0, V, size=rows).astype(np.int32)
+    got = bk.hip_align(full, nt, 2, 4, oracle.EXTRAS_TOP, V=V)
+    ref = oracle.align_sample(synth.to_host_bits(full), nt, m_x=2, c=4, V=V)
+    bk.compare_align(got, ref, bk.Tally(), oracle.EXTRAS_TOP)
+
+
+@pytest.mark.parametrize("m,c", [(0, 1), (1, 1), (1, 2), (2, 2), (2, 4), (3, 5), (4, 4), (4, 8)])
+def test_align_extras_parameters_with_ties(m, c):
+    rng = np.random.default_rng(100 * m + c)
+    rows, V = 300, 777
+    z = _random_rows(rng, rows, V, "bf16", coarse=True)
+    nt = rng.integers(0, V, size=rows).astype(np.int32)
+    for mode in (oracle.EXTRAS_TOP, oracle.EXTRAS_SAMPLE):
+        got = bk.hip_align(z, nt, m, c, mode, seed=9)
+        ref = bk.oracle_align(z, nt, m, c, mode, seed=9)
+        bk.compare_align(got, ref, bk.Tally(), mode)
+
+
+def test_align_no_next_tokens_and_no_rank():
+    rng = np.random.default_rng(1)
+    z = _random_rows(rng, 20, 3000, "bf16")
+    got = bk.hip_align(z, None, 2, 4, oracle.EXTRAS_TOP, want_rank=False)
+    ref = bk.oracle_align(z, None, 2, 4, oracle.EXTRAS_TOP)
+    assert got["rank"] is None
+    bk.compare_align(got, ref, bk.Tally(), oracle.EXTRAS_TOP)
+    assert (got["n_extras"] == 0).all() and (got["extras"] == -1).all()
+
+
+def test_align_degenerate_rows():
+    V = 4096
+    z = np.zeros((6, V), np.float32)
+    z[1, :] = -3.0                      # uniform
+    z[2, :] = -1.0e4; z[2, 1234] = 0.0  # one-hot limit
+    z[3, :] = -np.inf; z[3, [5, 4000]] = [1.0, 1.0]   # -inf logits (masked vocabulary)
+    z[4, :] = np.linspace(-40, 40, V)   # wide dynamic range, maximum at the end
+    z[5, :] = np.linspace(60, -60, V)   # maximum at the start
+    nt = np.array([7, 9, 1234, 4000, 0, 0], np.int32)
+    for dtype in ("f32", "bf16"):
+        zd = _dev_logits(z, dtype)
+        got = bk.hip_align(zd, nt, 2, 4, oracle.EXTRAS_TOP)
+        ref = bk.oracle_align(zd, nt, 2, 4, oracle.EXTRAS_TOP)
+        bk.compare_align(got, ref, bk.Tally(), oracle.EXTRAS_TOP)
+        assert abs(got["entropy"][0] - math.log(V)) < 1e-4 and got["misaligned"][0] == 0
+        assert got["entropy"][2] == 0.0 and abs(got["p_max"][2] - 1.0) < 1e-6
+        assert abs(got["entropy"][3] - math.log(2)) < 1e-5
+
+
+def test_align_many_ties_above_next_token_overflows_candidate_buffer():
+    """More than 256 tokens tied above the prompt token: the exact fallback selection runs."""
+    V = 6000
+    z = np.full((3, V), -2.0, np.float32)
+    z[0, 100:700] = 3.0                 # 600-way tie at the top
+    z[1, 100:700] = 3.0; z[1, 5555] = 4.0; z[1, 17] = 3.5
+    z[2, ::2] = 1.0                     # 3000-way tie
+    nt = np.array([0, 1, 1], np.int32)
+    for dtype in ("f32", "bf16"):
+        zd = _dev_logits(z, dtype)
+        for (m, c) in [(2, 4), (4, 8)]:
+            for mode in (oracle.EXTRAS_TOP, oracle.EXTRAS_SAMPLE):
+                got = bk.hip_align(zd, nt, m, c, mode, seed=3)
+                ref = bk.oracle_align(zd, nt, m, c, mode, seed=3)
+                bk.compare_align(got, ref, bk.Tally(), mode)
+    assert got["extras"][1].tolist()[:2] == ref["extras"][1].tolist()[:2]
+
+
+def test_align_row_id_base_partition_and_determinism():
+    rng = np.random.default_rng(8)
+    z = _random_rows(rng, 64, 2048, "bf16")
+    nt = rng.integers(0, 2048, size=64).astype(np.int32)
+    full = bk.hip_align(z, nt, 2, 4, oracle.EXTRAS_SAMPLE, seed=11, row_id_base=500)
+    again = bk.hip_align(z, nt, 2, 4, oracle.EXTRAS_SAMPLE, seed=11, row_id_base=500)
+    for name in full:
+        if full[name] is not None:
+            assert full[name].tobytes() == again[name].tobytes(), name  # byte-identical reruns
+    lo = bk.hip_align(z[:32], nt[:32], 2, 4, oracle.EXTRAS_SAMPLE, seed=11, row_id_base=500)
+    hi = bk.hip_align(z[32:], nt[32:], 2, 4, oracle.EXTRAS_SAMPLE, seed=11, row_id_base=532)
+    np.testing.assert_array_equal(full["extras"], np.concatenate([lo["extras"], hi["extras"]]))
+
+
+def test_align_sample_frequencies_on_device():
+    rows = 20000
+    z = torch.tensor([2.0, 1.0, 0.5, 0.0, -3.0, -9.0], device=DEV).repeat(rows, 1).contiguous()
+    nt = np.full(rows, 4, np.int32)
+    got = bk.hip_align(z, nt, 1, 4, oracle.EXTRAS_SAMPLE, seed=99)
+    ref = bk.oracle_align(z, nt, 1, 4, oracle.EXTRAS_SAMPLE, seed=99)
+    bk.compare_align(got, ref, bk.Tally(), oracle.EXTRAS_SAMPLE)
+    w = np.exp(np.array([2.0, 1.0, 0.5, 0.0])); p = w / w.sum()
+    counts = np.bincount(got["extras"][:, 0], minlength=4)[:4]
+    assert np.all(np.abs(counts - rows * p) < 4 * np.sqrt(rows * p * (1 - p)))
+
+
+# --------------------------------------------------------------------------- retrieval
+def _retrieve_both(tokens, lens, plens, n_min, n_max, k, C, extras=None, n_extras=None, m=0, xs=0):
+    ref = oracle.retrieve_drafts(tokens, lens, plens, n_min, n_max, k, C, extras=extras, n_extras=n_extras, m_x=m,
+                                 extras_stride=xs)
+    t = lambda a, dt: torch.as_tensor(np.ascontiguousarray(a), device=DEV).to(dt)
+    out = aasd.retrieve_drafts(t(tokens, torch.int32), t(lens, torch.int32), t(plens, torch.int32), n_min, n_max, k, C,
+                               extras=None if extras is None else t(extras, torch.int32),
+                               n_extras=None if extras is None else t(n_extras, torch.uint8), m=m, extras_stride=xs)
+    torch.cuda.synchronize()
+    bk.compare_retrieve(bk.to_np(out), ref)
+    return ref
+
+
+@pytest.mark.parametrize("n_min,n_max,k,C", [(1, 1, 1, 1), (1, 6, 6, 4), (3, 3, 4, 2), (2, 4, 8, 16), (1, 8, 16, 32)])
+@pytest.mark.parametrize("cap", [1, 90, 1500, 12000, 30011])
+def test_retrieve_random_small_alphabet(n_min, n_max, k, C, cap):
+    rng = np.random.default_rng(cap + n_max)
+    B = 24
+    alphabet = 3 if cap < 2000 else 40
+    toks = rng.integers(0, alphabet, size=(B, cap)).astype(np.int32)
+    lens = rng.integers(0, cap + 1, size=B).astype(np.int32)
+    lens[0], lens[1] = cap, 0
+    plens = np.minimum(lens, rng.integers(0, cap + 1, size=B)).astype(np.int32)
+    ref = _retrieve_both(toks, lens, plens, n_min, n_max, k, C)
+    if cap >= 1500:
+        assert (ref["n_cand"] > 0).any()
+
+
+def test_retrieve_planted_spans_multi_tile_and_extras():
+    """A 20000-token context (two LDS tiles) with spans repeated across the tile boundary, plus
+    gathering of the alignment extras."""
+    rng = np.random.default_rng(4)
+    L, V, m = 20000, 50000, 2
+    B = 3
+    toks = rng.integers(0, V, size=(B, L + 64)).astype(np.int32)
+    for b in range(B):
+        span = toks[b, 100:140].copy()
+        for dst in (5000, 11200, 11264 - 5, 19000):  # 11264 = tile size for this capacity
+            toks[b, dst:dst + 40] = span
+        toks[b, L - 6:L] = span[10:16]  # the context ends inside the span
+    lens = np.full(B, L, np.int32)
+    plens = np.array([L, 12000, 0], np.int32)
+    extras = rng.integers(0, V, size=(B * L, m)).astype(np.int32)
+    n_extras = rng.integers(0, m + 1, size=B * L).astype(np.uint8)
+    extras[np.arange(m)[None, :] >= n_extras[:, None]] = -1
+    ref = _retrieve_both(toks, lens, plens, 2, 6, 8, 8, extras=extras, n_extras=n_extras, m=m, xs=L)
+    assert (ref["key_len"] == 6).all() and (ref["n_cand"] == 5).all()
+    assert ref["src_pos"][0].tolist()[:5] == [19016, 11264 - 5 + 16, 11200 + 16, 5016, 116]
+
+
+def test_retrieve_hash_collision_is_not_a_hit():
+    """Two different bigrams with the same polynomial window hash: only the exact one is returned."""
+    step = (1 << 32) - aasd.HASH_BASE  # (a+1)*B + (b+step) == a*B + b  (mod 2^32)
+    a, b = 1000, 2000
+    toks = np.array([[5, a + 1, b + step, 77, 6, a, b, 88, 9, a, b]], np.int32)
+    assert ((a + 1) * aasd.HASH_BASE + (b + step)) % (1 << 32) == (a * aasd.HASH_BASE + b) % (1 << 32)
+    ref = _retrieve_both(toks, [11], [11], 2, 2, 3, 4)
+    assert ref["src_pos"][0].tolist() == [7, -1, -1, -1]
+
+
+# --------------------------------------------------------------------------- verification
+def _verify_case(rng, B, C, k, V, dtype, peaked=True):
+    R = 1 + C * k
+    z = rng.standard_normal((B, R, V)).astype(np.float32) * 1.5
+    drafts = np.empty((B, C, k), np.int32)
+    for b in range(B):
+        for r in range(R):
+            if peaked:
+                top = rng.choice(V, 4, replace=False)
+                z[b, r, top] = [24.0, 23.0, 22.0, 21.0]
+    order = np.argsort(-z, axis=2)[:, :, :6]
+    for b in range(B):
+        for c in range(C):
+            for j in range(k):
+                rho = 0 if j == 0 else 1 + c * k + (j - 1)
+                pick = rng.choice(6, p=[0.55, 0.25, 0.08, 0.06, 0.03, 0.03])
+                drafts[b, c, j] = order[b, rho, pick]
+    drafts[rng.random((B, C, k)) < 0.02] = V + 5       # out-of-vocabulary ids fail
+    dl = rng.integers(0, k + 1, size=(B, C)).astype(np.int32)
+    strict = (rng.random((B, C, k)) < 0.3).astype(np.uint8)
+    return _dev_logits(z.reshape(B * R, V), dtype).view(B, R, V), drafts, dl, strict
+
+
+def _verify_both(zd, drafts, dl, strict, alpha, beta, flags, tally):
+    ref = oracle.verify(synth.to_host_bits(zd), drafts, dl, strict, alpha=bk.f32(alpha), beta=bk.f32(beta), flags=flags)
+    t = lambda a, dt: None if a is None else torch.as_tensor(np.ascontiguousarray(a), device=DEV).to(dt)
+    out = aasd.verify(zd, t(drafts, torch.int32), t(dl, torch.int32), t(strict, torch.uint8), alpha=alpha, beta=beta,
+                      flags=flags)
+    torch.cuda.synchronize()
+    bk.compare_verify(bk.to_np(out), ref, tally)
+    return ref
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("B,C,k,V", [(1, 1, 1, 50), (3, 1, 4, 32000), (2, 3, 5, 4099), (5, 16, 8, 1000), (2, 32, 16, 300)])
+def test_verify_random_cases(dtype, B, C, k, V):
+    rng = np.random.default_rng(B * 1000 + C * 10 + k)
+    tally = bk.Tally()
+    for peaked in (True, False):
+        zd, drafts, dl, strict = _verify_case(rng, B, C, k, V, dtype, peaked)
+        for alpha, beta, flags, st in [(0.1, 0.1, 0, strict), (0.2, 0.1, 0, None), (0.0, 0.1, aasd.VERIFY_NO_CLAMP, None),
+                                       (0.0, 0.0, 0, None), (0.0, 1.0, 0, strict)]:
+            _verify_both(zd, drafts, dl, st, alpha, beta, flags, tally)
+    print("verify", dtype, B, C, k, V, tally)
+
+
+def test_verify_strided_sequences_and_determinism():
+    rng = np.random.default_rng(12)
+    B, C, k, V = 3, 2, 4, 2000
+    R = 1 + C * k
+    zd, drafts, dl, strict = _verify_case(rng, B, C, k, V, "bf16")
+    big = torch.zeros((B, R + 2, V + 24), dtype=torch.bfloat16, device=DEV)
+    big[:, :R, :V] = zd
+    view = big[:, :R, :V]
+    t = lambda a, dt: torch.as_tensor(np.ascontiguousarray(a), device=DEV).to(dt)
+    a = bk.to_np(aasd.verify(zd, t(drafts, torch.int32), t(dl, torch.int32), t(strict, torch.uint8)))
+    b = bk.to_np(aasd.verify(view, t(drafts, torch.int32), t(dl, torch.int32), t(strict, torch.uint8)))
+    torch.cuda.synchronize()
+    for name in a:
+        if a[name] is not None:
+            assert a[name].tobytes() == b[name].tobytes(), name
+
+
+# --------------------------------------------------------------------------- the five workloads
+def _align_workload(w, b, rows, tally, peaked=False, mode=oracle.EXTRAS_TOP):
+    g, copied = synth.token_stream(w, b)
+    z = synth.prefill_logits(w, b, g, copied, DEV, rows=rows, peaked=peaked)
+    nt = synth.next_tokens(w, g)[rows]
+    base = b * w.L + (rows.start or 0)
+    got = bk.hip_align(z, nt, w.m, w.c, mode, seed=w.seed, row_id_base=base)
+    ref = bk.oracle_align(z, nt, w.m, w.c, mode, seed=w.seed, row_id_base=base)
+    bk.compare_align(got, ref, tally, mode)
+    return got
+
+
+def test_workload_tiny_full():
+    """Config 1 in full: all 256 prefill rows (both modes) and the 64-step decode loop."""
+    w = synth.WORKLOADS["tiny"]
+    tally = bk.Tally()
+    got = _align_workload(w, 0, slice(0, w.L), tally, mode=oracle.EXTRAS_TOP)
+    _align_workload(w, 0, slice(0, w.L), tally, mode=oracle.EXTRAS_SAMPLE)
+    assert 0.2 < got["misaligned"].mean() < 0.8
+    pb = bk.ParityBackend(DEV)
+    trace = harness.decode(w, pb)
+    assert len(trace.steps) == w.steps
+    print("tiny", tally, pb.tally, "tokens/step", trace.mean_accept_len)
+    # LLM-like rows (exercise the unclamped alpha*H + beta branch) over a context dense in repeats, with
+    # the alignment extras gathered along the drafts: drafts are found and accepted
+    wd = synth.scaled(w, coverage=0.9, spans=0)
+    g, copied = synth.token_stream(wd, 0)
+    z = synth.prefill_logits(wd, 0, g, copied, DEV, peaked=True)
+    al = bk.hip_align(z, synth.next_tokens(wd, g), wd.m, wd.c, oracle.EXTRAS_TOP)
+    pb2 = bk.ParityBackend(DEV)
+    tr2 = harness.decode(wd, pb2, peaked=True, extras=al["extras"], n_extras=al["n_extras"])
+    hits = sum(int(s.retrieved["n_cand"][0] > 0) for s in tr2.steps)
+    print("tiny dense/peaked", pb2.tally, "tokens/step", tr2.mean_accept_len, "steps with drafts", hits)
+    assert hits > 5 and tr2.mean_accept_len > 1.2
+
+
+@pytest.mark.parametrize("name,rows_n,steps", [("llama3_single", 192, 24), ("long_context", 128, 12),
+                                               ("batched_serving", 64, 6), ("stress_tree", 64, 3)])
+def test_workloads_scaled(name, rows_n, steps):
+    """Configs 2-5 at full vocabulary and full per-step shape, with fewer rows and steps."""
+    w0 = synth.WORKLOADS[name]
+    tally = bk.Tally()
+    _align_workload(w0, 0, slice(0, rows_n), tally, mode=oracle.EXTRAS_TOP)
+    _align_workload(w0, w0.B - 1, slice(w0.L - rows_n, w0.L), tally, mode=oracle.EXTRAS_SAMPLE)
+    _align_workload(w0, 0, slice(0, 32), tally, peaked=True)
+    w = synth.scaled(w0, B=min(w0.B, 4), steps=steps)
+    pb = bk.ParityBackend(DEV)
+    trace = harness.decode(w, pb)
+    pb2 = bk.ParityBackend(DEV)
+    harness.decode(synth.scaled(w, steps=2), pb2, peaked=True)
+    print(name, tally, pb.tally, pb2.tally, "MAL", trace.mean_accept_len)
