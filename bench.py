@@ -210,8 +210,8 @@ def main():
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
-        n_a = min(prefill_rows, 1024)
-        n_s = max(1, min(S, 1152 // (w.B * w.R)))
+        n_a = min(prefill_rows, 8192)
+        n_s = max(1, min(S, 9216 // (w.B * w.R)))
         nb = n_s * w.B
         bits_a = synth.to_host_bits(prefill[:n_a])
         bits_v = synth.to_host_bits(verify_logits[:nb])

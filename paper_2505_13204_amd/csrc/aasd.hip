@@ -29,13 +29,16 @@ int fail(int code, const char* fmt, ...)
 bool valid_dtype(int32_t dt) { return dt == AASD_F32 || dt == AASD_BF16; }
 size_t elt_size(int32_t dt) { return dt == AASD_F32 ? 4 : 2; }
 
-// Launch shape of the row sweep.  The default suits rows of 10^5 elements; the environment
-// variable AASD_SWEEP_CONFIG="block,unroll" is a developer knob for tuning runs.
+// Launch shape of the row sweep (threads per row, 16-byte loads in flight per lane and buffer).
+// Measured on MI355X at V = 128256 bf16: without the LDS chunk-maximum array (verification) 1024
+// threads x 2 loads is fastest at every row count; with it (alignment sampling) occupancy is
+// LDS-bound and 256 x 4 wins.  The environment variable
+// AASD_SWEEP_CONFIG="block,unroll" overrides the choice (developer knob for tuning and tests).
 struct SweepConfig { int block, unroll; };
 
-SweepConfig sweep_config(int64_t rows)
+SweepConfig sweep_config(bool align, int64_t rows)
 {
-    SweepConfig cfg{256, 4};
+    SweepConfig cfg = align ? SweepConfig{256, 4} : SweepConfig{1024, 2};
     (void)rows;
     if (const char* e = getenv("AASD_SWEEP_CONFIG")) {
         int b = 0, u = 0;
@@ -63,12 +66,15 @@ hipError_t launch_sweep_one(const aasd::SweepParams& p, int64_t rows, size_t dyn
 template <int DT, bool ALIGN, bool COUNT>
 int launch_sweep(const aasd::SweepParams& p, int64_t rows, size_t dyn_lds, hipStream_t stream)
 {
-    const SweepConfig cfg = sweep_config(rows);
+    const SweepConfig cfg = sweep_config(ALIGN, rows);
     hipError_t e;
     if (cfg.block == 256 && cfg.unroll == 4) e = launch_sweep_one<DT, ALIGN, COUNT, 256, 4>(p, rows, dyn_lds, stream);
     else if (cfg.block == 256 && cfg.unroll == 2) e = launch_sweep_one<DT, ALIGN, COUNT, 256, 2>(p, rows, dyn_lds, stream);
     else if (cfg.block == 512 && cfg.unroll == 4) e = launch_sweep_one<DT, ALIGN, COUNT, 512, 4>(p, rows, dyn_lds, stream);
     else if (cfg.block == 512 && cfg.unroll == 2) e = launch_sweep_one<DT, ALIGN, COUNT, 512, 2>(p, rows, dyn_lds, stream);
+    else if (cfg.block == 256 && cfg.unroll == 8) e = launch_sweep_one<DT, ALIGN, COUNT, 256, 8>(p, rows, dyn_lds, stream);
+    else if (cfg.block == 512 && cfg.unroll == 8) e = launch_sweep_one<DT, ALIGN, COUNT, 512, 8>(p, rows, dyn_lds, stream);
+    else if (cfg.block == 1024 && cfg.unroll == 4) e = launch_sweep_one<DT, ALIGN, COUNT, 1024, 4>(p, rows, dyn_lds, stream);
     else if (cfg.block == 1024 && cfg.unroll == 2) e = launch_sweep_one<DT, ALIGN, COUNT, 1024, 2>(p, rows, dyn_lds, stream);
     else if (cfg.block == 1024 && cfg.unroll == 1) e = launch_sweep_one<DT, ALIGN, COUNT, 1024, 1>(p, rows, dyn_lds, stream);
     else return fail(AASD_ERR_UNSUPPORTED, "AASD_SWEEP_CONFIG=%d,%d is not a compiled launch shape", cfg.block, cfg.unroll);

@@ -80,7 +80,8 @@ __device__ __forceinline__ float accumulate(LaneAcc& a, const float (&z)[N], int
     float cmax = z[0];
 #pragma unroll
     for (int e = 1; e < N; ++e) cmax = fmaxf(cmax, z[e]);
-    if (cmax > a.vmax) { a.vmax = cmax; a.code = idx0; }
+    a.code = cmax > a.vmax ? idx0 : a.code;
+    a.vmax = fmaxf(a.vmax, cmax);
     if (cmax > a.rlim) {  // rare: first chunk of the lane, or a jump of more than kRefSlack nats
         float nr2 = cmax * kLog2e;
         if (CLAMP) nr2 = fmaxf(nr2, kNegHuge);
@@ -160,33 +161,40 @@ __device__ __forceinline__ void sweep_lane(LaneAcc& a, const RowShape& rs, int V
         accumulate<1, CLAMP, COUNT, false>(a, z1, tid, zcmp);
     }
 
+    // Full batches of BLOCK*U vectors.  Two register buffers alternate: while one batch is folded
+    // in, the loads of the next are in flight, and no buffer is ever copied.  The batch base is
+    // uniform (scalar registers), the lane offset a 32-bit byte offset.
     constexpr int kPerSuper = BLOCK * U;
+    constexpr unsigned kBatchBytes = (unsigned)kPerSuper * 16u;
     const int nsuper = rs.nvec / kPerSuper;
-    u32x4 cur[U];
-    if (nsuper > 0) {
+    const char* const sbase = (const char*)rs.vbase;
+    const unsigned voff = (unsigned)tid * 16u;
+    auto load_batch = [&](u32x4 (&buf)[U], int it) {
+        const char* b = sbase + (size_t)it * kBatchBytes;
 #pragma unroll
-        for (int u = 0; u < U; ++u) cur[u] = rs.vbase[u * BLOCK + tid];
-    }
-    for (int it = 0; it < nsuper; ++it) {
-        u32x4 nxt[U];
-        const bool more = it + 1 < nsuper;
-        if (more) {
-#pragma unroll
-            for (int u = 0; u < U; ++u) nxt[u] = rs.vbase[((it + 1) * U + u) * BLOCK + tid];
-        }
+        for (int u = 0; u < U; ++u) buf[u] = *(const u32x4*)(b + (voff + (unsigned)u * (BLOCK * 16u)));
+    };
+    auto fold_batch = [&](const u32x4 (&buf)[U], int it) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             float z[EPV];
-            unpack<DT>(cur[u], z);
+            unpack<DT>(buf[u], z);
             const int vec = (it * U + u) * BLOCK + tid;
             const float cmax = accumulate<EPV, CLAMP, COUNT, true>(a, z, rs.head + vec * EPV, zcmp);
             if (store_cm) cm_store<DT>(cm, vec, cmax);
         }
-        if (more) {
-#pragma unroll
-            for (int u = 0; u < U; ++u) cur[u] = nxt[u];
-        }
+    };
+    u32x4 bufA[U], bufB[U];
+    int it = 0;
+    if (nsuper > 0) load_batch(bufA, 0);
+    while (it + 1 < nsuper) {
+        load_batch(bufB, it + 1);
+        fold_batch(bufA, it);
+        if (it + 2 < nsuper) load_batch(bufA, it + 2);
+        fold_batch(bufB, it + 1);
+        it += 2;
     }
+    if (it < nsuper) fold_batch(bufA, it);
     {   // fewer than BLOCK*U vectors remain
         const int vec0 = nsuper * kPerSuper + tid;
         u32x4 rem[U];
@@ -313,29 +321,29 @@ __device__ __forceinline__ void choose_extras(const SweepParams& p, int64_t row,
     if (p.mode == AASD_EXTRAS_TOP || nK <= p.m_x) {
         for (int i = 0; i < nK && i < p.m_x; ++i) chosen[n_chosen++] = ki[i];
     } else {
-        double w[AASD_MAX_CANDSET];
+        float w[AASD_MAX_CANDSET];
         int id[AASD_MAX_CANDSET];
         int n_rem = nK;
-        for (int i = 0; i < nK; ++i) { w[i] = exp((double)kz[i] - (double)m); id[i] = ki[i]; }
+        for (int i = 0; i < nK; ++i) { w[i] = expf(kz[i] - m); id[i] = ki[i]; }
         const uint64_t row_id = p.row_id_base + (uint64_t)row;
         unsigned near = 0;
         for (int j = 0; j < p.m_x; ++j) {
             uint32_t rnd[4];
             philox4x32_10((uint32_t)row_id, (uint32_t)(row_id >> 32), (uint32_t)j, 0x41415344u,
                           (uint32_t)p.seed, (uint32_t)(p.seed >> 32), rnd);
-            const double u = (double)(rnd[0] >> 8) * (1.0 / 16777216.0);
-            double W = 0.0;
+            const float u = (float)(rnd[0] >> 8) * (1.0f / 16777216.0f);  // 24 bits: exact in fp32
+            float W = 0.f;
             for (int i = 0; i < n_rem; ++i) W += w[i];
-            const double target = u * W;
-            double cum = 0.0, margin = INFINITY;
+            const float target = u * W;
+            float cum = 0.f, margin = INFINITY;
             int pick = n_rem - 1;
             bool decided = false;
             for (int i = 0; i < n_rem; ++i) {
                 cum += w[i];
-                if (i < n_rem - 1) margin = fmin(margin, fabs(target - cum) / W);
+                if (i < n_rem - 1) margin = fminf(margin, fabsf(target - cum));
                 if (!decided && cum > target) { pick = i; decided = true; }
             }
-            if (margin < 1e-6) ++near;
+            if (margin < 1e-6f * W) ++near;
             chosen[n_chosen++] = id[pick];
             for (int i = pick; i + 1 < n_rem; ++i) { w[i] = w[i + 1]; id[i] = id[i + 1]; }
             --n_rem;
@@ -472,16 +480,16 @@ __device__ __forceinline__ bool process_row(const SweepParams& p, int64_t row, c
             for (int e = 0; e < len; ++e)
                 if (load_elt<DT>(rs.base, bcode + e) == m) { am = bcode + e; break; }
         }
-        const double Sd = (double)S;
-        double H = log(Sd) - kLn2 * (double)T2 / Sd;
-        if (H < 0.0) H = 0.0;
-        const float pmax = (float)(1.0 / Sd);
+        // fp32 is enough for the per-row scalars: logf/expf are good to an ulp, far inside the tolerance
+        float H = logf(S) - (float)kLn2 * T2 / S;
+        if (H < 0.f) H = 0.f;
+        const float pmax = 1.0f / S;
         if (ALIGN) {
             p.argmax[row] = am;
-            p.entropy[row] = (float)H;
+            p.entropy[row] = H;
             p.p_max[row] = pmax;
             p.misaligned[row] = mis ? 1 : 0;
-            p.p_next[row] = has_next ? (float)(exp((double)znext - (double)m) / Sd) : 0.f;
+            p.p_next[row] = has_next ? expf(znext - m) / S : 0.f;
             if (COUNT) p.rank[row] = has_next ? (int32_t)rank : -1;
             if (p.m_x > 0) {
                 if (want_cand && mis) choose_extras(p, row, m, kz, ki, nK);
@@ -491,8 +499,8 @@ __device__ __forceinline__ bool process_row(const SweepParams& p, int64_t row, c
                 }
             }
         } else {
-            p.stats[row] = make_float4(m, S, (float)H, __int_as_float(am));
-            if (p.row_entropy) p.row_entropy[row] = (float)H;
+            p.stats[row] = make_float4(m, S, H, __int_as_float(am));
+            if (p.row_entropy) p.row_entropy[row] = H;
             if (p.row_pmax) p.row_pmax[row] = pmax;
             if (p.row_argmax) p.row_argmax[row] = am;
         }

@@ -145,6 +145,23 @@ def test_align_sample_frequencies_on_device():
     assert np.all(np.abs(counts - rows * p) < 4 * np.sqrt(rows * p * (1 - p)))
 
 
+@pytest.mark.parametrize("shape", ["256,2", "256,4", "256,8", "512,2", "512,4", "512,8", "1024,1", "1024,2", "1024,4"])
+def test_every_compiled_launch_shape(shape, monkeypatch):
+    """The sweep is compiled for several (threads per row, loads in flight) shapes; the library picks by
+    row count.  Each shape must give the same answers: force them one by one."""
+    monkeypatch.setenv("AASD_SWEEP_CONFIG", shape)
+    rng = np.random.default_rng(17)
+    rows, V = 24, 128256 // 4 + 5   # several full batches for the widest shape, plus a ragged tail
+    for dtype in ("bf16", "f32"):
+        z = _random_rows(rng, rows, V, dtype, coarse=(dtype == "bf16"))
+        nt = rng.integers(-1, V, size=rows).astype(np.int32)
+        got = bk.hip_align(z, nt, 2, 4, oracle.EXTRAS_SAMPLE, seed=2)
+        ref = bk.oracle_align(z, nt, 2, 4, oracle.EXTRAS_SAMPLE, seed=2)
+        bk.compare_align(got, ref, bk.Tally(), oracle.EXTRAS_SAMPLE)
+    zd, drafts, dl, strict = _verify_case(rng, 2, 2, 3, 40000, "bf16")
+    _verify_both(zd, drafts, dl, strict, 0.1, 0.1, 0, bk.Tally())
+
+
 # --------------------------------------------------------------------------- retrieval
 def _retrieve_both(tokens, lens, plens, n_min, n_max, k, C, extras=None, n_extras=None, m=0, xs=0):
     ref = oracle.retrieve_drafts(tokens, lens, plens, n_min, n_max, k, C, extras=extras, n_extras=n_extras, m_x=m,
