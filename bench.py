@@ -117,7 +117,7 @@ def main():
     len_b = torch.from_numpy(np.concatenate([s.length for s in trace.steps]).astype(np.int32)).to(dev)
     plen_b = torch.full((BB,), w.L, dtype=torch.int32, device=dev)
     r_out = aasd.retrieve_drafts(tokens_b, len_b, plen_b, w.n_min, w.n_max, w.k, w.C)
-    ws = torch.empty(max(16, aasd.verify_workspace_bytes(BB, w.C, w.k)), dtype=torch.uint8, device=dev)
+    ws = torch.empty(max(16, aasd.verify_workspace_bytes(BB, w.C, w.k, w.V, aasd.BF16 if w.dtype == 'bf16' else aasd.F32)), dtype=torch.uint8, device=dev)
     v_out = aasd.verify(verify_logits, r_out["drafts"], r_out["draft_len"], r_out["strict"], alpha=w.alpha, beta=w.beta,
                         workspace=ws, want_rows=False, want_tokens=False)
     torch.cuda.synchronize()
@@ -189,7 +189,7 @@ def main():
     if not args.no_latency and w.B * w.R <= 512:
         n_lat = min(S, 256)
         outs_r = aasd.retrieve_drafts(tokens_b[:w.B], len_b[:w.B], plen_b[:w.B], w.n_min, w.n_max, w.k, w.C)
-        ws1 = torch.empty(max(16, aasd.verify_workspace_bytes(w.B, w.C, w.k)), dtype=torch.uint8, device=dev)
+        ws1 = torch.empty(max(16, aasd.verify_workspace_bytes(w.B, w.C, w.k, w.V, aasd.BF16 if w.dtype == 'bf16' else aasd.F32)), dtype=torch.uint8, device=dev)
         outs_v = aasd.verify(verify_logits[:w.B], outs_r["drafts"], outs_r["draft_len"], outs_r["strict"],
                              workspace=ws1, want_rows=False, want_tokens=False)
         torch.cuda.synchronize()

@@ -92,13 +92,17 @@ const char *aasd_last_error(void);
  *             near_count: one u32 that is INCREMENTED by the number of SAMPLE draws that fell
  *             within 1e-6 (relative to the total weight) of a boundary between two picks
  *             (NULL = not wanted; the caller zeroes it).
+ * workspace : DEVICE scratch of at least aasd_align_sample_workspace_bytes(rows, V, dt) bytes,
+ *             16-byte aligned; it needs no initialisation and holds nothing of value afterwards.
  * Parameters: 0 <= m <= 4, max(m,1) <= c <= 8, rows >= 0, V >= 1, row_stride >= V.
  */
+size_t aasd_align_sample_workspace_bytes(int64_t rows, int32_t V, int32_t dt);
 int aasd_align_sample(const void *logits, int32_t dt, int64_t rows, int32_t V, int64_t row_stride,
                       const int32_t *next_tok, int32_t m, int32_t c, int32_t mode, uint64_t seed,
                       uint64_t row_id_base, int32_t *argmax, uint8_t *misaligned, float *entropy,
                       float *p_next, float *p_max, int32_t *rank, int32_t *extras,
-                      uint8_t *n_extras, uint32_t *near_count, void *stream);
+                      uint8_t *n_extras, uint32_t *near_count, void *workspace,
+                      size_t workspace_bytes, void *stream);
 
 /*
  * n-gram draft retrieval (Sec. 3.1; Algorithm 1: draft-pool initialisation and the
@@ -134,9 +138,9 @@ int aasd_retrieve_drafts(const int32_t *tokens, int64_t tok_stride, const int32_
                          int32_t *src_pos, int32_t *n_cand, int32_t *key_len,
                          int32_t *draft_extras, uint8_t *strict, void *stream);
 
-/* Bytes of device workspace aasd_verify needs for B sequences of C candidates of k tokens
- * (0 on invalid arguments). */
-size_t aasd_verify_workspace_bytes(int32_t B, int32_t C, int32_t k);
+/* Bytes of device workspace aasd_verify needs for B sequences of C candidates of k tokens over
+ * a vocabulary of V logits of type dt (0 on invalid arguments). */
+size_t aasd_verify_workspace_bytes(int32_t B, int32_t C, int32_t k, int32_t V, int32_t dt);
 
 /*
  * Conditional verification (Sec. 3.3, Eq. 4-6; the cascade rule of Sec. 2.1; "the longest
@@ -164,7 +168,8 @@ size_t aasd_verify_workspace_bytes(int32_t B, int32_t C, int32_t k);
  *             tok_p[B,C,k], tok_delta[B,C,k] f32 (0 beyond draft_len; NULL = not wanted);
  *             near_count[B] u32 = number of evaluated tokens (up to and including each
  *             candidate's first failure) with |p - delta| < 1e-6 (NULL = not wanted)
- * workspace : DEVICE scratch of at least aasd_verify_workspace_bytes(B, C, k) bytes, 16-byte aligned
+ * workspace : DEVICE scratch of at least aasd_verify_workspace_bytes(B, C, k, V, dt) bytes, 16-byte
+ *             aligned; it needs no initialisation and holds nothing of value afterwards
  * Parameters: 1 <= k <= 16, 1 <= C <= 32, V >= 1, row_stride >= V, seq_stride >= R*row_stride.
  */
 int aasd_verify(const void *logits, int32_t dt, int32_t B, int32_t C, int32_t k, int32_t V,

@@ -60,7 +60,8 @@ def _dev_check(*tensors):
 
 def align_sample(logits: torch.Tensor, next_tok: Optional[torch.Tensor], m: int = 2, c: int = 4,
                  mode: int = EXTRAS_TOP, seed: int = 0, row_id_base: int = 0, V: Optional[int] = None,
-                 want_rank: bool = True, near_count: Optional[torch.Tensor] = None, out: Optional[dict] = None):
+                 want_rank: bool = True, near_count: Optional[torch.Tensor] = None,
+                 workspace: Optional[torch.Tensor] = None, out: Optional[dict] = None):
     """aasd_align_sample over logits[rows, row_stride] (fp32 or bf16, rows contiguous in memory).
 
     Returns a dict of device tensors: argmax, misaligned, entropy, p_next, p_max, rank (or None),
@@ -74,6 +75,7 @@ def align_sample(logits: torch.Tensor, next_tok: Optional[torch.Tensor], m: int 
         out = {}
     o = dict(
         argmax=out.get("argmax", None), misaligned=out.get("misaligned", None), entropy=out.get("entropy", None),
+        workspace=None,
         p_next=out.get("p_next", None), p_max=out.get("p_max", None), rank=out.get("rank", None),
         extras=out.get("extras", None), n_extras=out.get("n_extras", None))
     if o["argmax"] is None: o["argmax"] = torch.empty(rows, dtype=torch.int32, device=dev)
@@ -86,14 +88,24 @@ def align_sample(logits: torch.Tensor, next_tok: Optional[torch.Tensor], m: int 
     if o["n_extras"] is None: o["n_extras"] = torch.empty(rows, dtype=torch.uint8, device=dev)
     if next_tok is not None:
         assert next_tok.dtype == torch.int32 and next_tok.is_contiguous() and next_tok.numel() == rows
+    ws_bytes = align_sample_workspace_bytes(rows, V, _dtype_code(logits))
+    if workspace is None:
+        workspace = out.get("workspace")
+    if workspace is None or workspace.numel() * workspace.element_size() < ws_bytes:
+        workspace = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
+    o["workspace"] = workspace
     rc = _lib.load().aasd_align_sample(
         logits.data_ptr(), _dtype_code(logits), rows, V, row_stride, _ptr(next_tok), m, c, mode,
         seed & 0xFFFFFFFFFFFFFFFF, row_id_base & 0xFFFFFFFFFFFFFFFF,
         o["argmax"].data_ptr(), o["misaligned"].data_ptr(), o["entropy"].data_ptr(), o["p_next"].data_ptr(),
         o["p_max"].data_ptr(), _ptr(o["rank"]), o["extras"].data_ptr(), o["n_extras"].data_ptr(),
-        _ptr(near_count), _stream(dev))
+        _ptr(near_count), workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream(dev))
     _check(rc)
     return o
+
+
+def align_sample_workspace_bytes(rows: int, V: int, dt: int) -> int:
+    return int(_lib.load().aasd_align_sample_workspace_bytes(rows, V, dt))
 
 
 def retrieve_drafts(tokens: torch.Tensor, length: torch.Tensor, prompt_len: torch.Tensor, n_min: int, n_max: int,
@@ -137,8 +149,8 @@ def retrieve_drafts(tokens: torch.Tensor, length: torch.Tensor, prompt_len: torc
     return o
 
 
-def verify_workspace_bytes(B: int, C: int, k: int) -> int:
-    return int(_lib.load().aasd_verify_workspace_bytes(B, C, k))
+def verify_workspace_bytes(B: int, C: int, k: int, V: int, dt: int) -> int:
+    return int(_lib.load().aasd_verify_workspace_bytes(B, C, k, V, dt))
 
 
 def verify(logits: torch.Tensor, drafts: torch.Tensor, draft_len: torch.Tensor, strict: Optional[torch.Tensor] = None,
@@ -176,8 +188,10 @@ def verify(logits: torch.Tensor, drafts: torch.Tensor, draft_len: torch.Tensor, 
     need("tok_p", (B, C, k), torch.float32, want_tokens)
     need("tok_delta", (B, C, k), torch.float32, want_tokens)
     need("near_count", (B,), torch.int32, want_near)
-    ws_bytes = verify_workspace_bytes(B, C, k)
+    ws_bytes = verify_workspace_bytes(B, C, k, V, _dtype_code(logits))
     if workspace is None:
+        workspace = o.get("workspace")
+    if workspace is None or workspace.numel() * workspace.element_size() < ws_bytes:
         workspace = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
     rc = _lib.load().aasd_verify(
         logits.data_ptr(), _dtype_code(logits), B, C, k, V, row_stride, seq_stride,

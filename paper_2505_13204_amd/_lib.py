@@ -33,14 +33,17 @@ def load():
     lib.aasd_align_sample.restype = c_int32
     lib.aasd_align_sample.argtypes = [
         c_void_p, c_int32, c_int64, c_int32, c_int64, c_void_p, c_int32, c_int32, c_int32, c_uint64, c_uint64,
-        c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
+        c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+        c_void_p, c_size_t, c_void_p]
+    lib.aasd_align_sample_workspace_bytes.restype = c_size_t
+    lib.aasd_align_sample_workspace_bytes.argtypes = [c_int64, c_int32, c_int32]
     lib.aasd_retrieve_drafts.restype = c_int32
     lib.aasd_retrieve_drafts.argtypes = [
         c_void_p, c_int64, c_void_p, c_void_p, c_int32, c_int32, c_int32, c_int32, c_int32,
         c_void_p, c_void_p, c_int32, c_int64,
         c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
     lib.aasd_verify_workspace_bytes.restype = c_size_t
-    lib.aasd_verify_workspace_bytes.argtypes = [c_int32, c_int32, c_int32]
+    lib.aasd_verify_workspace_bytes.argtypes = [c_int32, c_int32, c_int32, c_int32, c_int32]
     lib.aasd_verify.restype = c_int32
     lib.aasd_verify.argtypes = [
         c_void_p, c_int32, c_int32, c_int32, c_int32, c_int32, c_int64, c_int64,

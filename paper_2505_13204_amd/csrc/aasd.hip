@@ -10,6 +10,7 @@
 #include <cstring>
 
 #include "retrieve.hip.h"
+#include "row_finish.hip.h"
 #include "row_sweep.hip.h"
 #include "verify_tail.hip.h"
 
@@ -29,34 +30,55 @@ int fail(int code, const char* fmt, ...)
 bool valid_dtype(int32_t dt) { return dt == AASD_F32 || dt == AASD_BF16; }
 size_t elt_size(int32_t dt) { return dt == AASD_F32 ? 4 : 2; }
 
-// Launch shape of the row sweep (threads per row, 16-byte loads in flight per lane and buffer).
-// Measured on MI355X at V = 128256 bf16: without the LDS chunk-maximum array (verification) 1024
-// threads x 2 loads is fastest at every row count; with it (alignment sampling) occupancy is
-// LDS-bound and 256 x 4 wins.  The environment variable
-// AASD_SWEEP_CONFIG="block,unroll" overrides the choice (developer knob for tuning and tests).
-struct SweepConfig { int block, unroll; };
+// Launch plan of the row sweep: threads per workgroup, 16-byte loads in flight per lane and
+// buffer, and how many contiguous segments a row is cut into (one workgroup each).
+// Measured on MI355X at V = 128256 bf16: with many rows, 1024 threads x 2 loads is fastest
+// without the LDS chunk-maximum array (verification) and 256 x 4 with it (alignment sampling,
+// whose occupancy is LDS-bound).  With few rows one workgroup per row cannot fill the GPU (a
+// single workgroup streams at some 15-30 GB/s), so rows are cut into segments until there are a
+// few thousand workgroups.  AASD_SWEEP_CONFIG="block,unroll[,segments]" overrides the plan
+// (developer knob for tuning runs and tests).
+struct SweepPlan { int block, unroll, nseg, seg_vecs, npart; };
 
-SweepConfig sweep_config(bool align, int64_t rows)
+constexpr int64_t kSplitBelowRows = 4096;
+
+SweepPlan plan_sweep(bool align, int64_t rows, int32_t V, int32_t dt)
 {
-    SweepConfig cfg = align ? SweepConfig{256, 4} : SweepConfig{1024, 2};
-    (void)rows;
-    if (const char* e = getenv("AASD_SWEEP_CONFIG")) {
-        int b = 0, u = 0;
-        if (sscanf(e, "%d,%d", &b, &u) == 2) { cfg.block = b; cfg.unroll = u; }
+    const int per_vec = dt == AASD_BF16 ? 8 : 4;
+    const int nvec_max = V / per_vec > 0 ? V / per_vec : 1;
+    SweepPlan pl{align ? 256 : 1024, align ? 4 : 2, 1, 0, 0};
+    if (rows > 0 && rows < kSplitBelowRows) {
+        pl.block = 256; pl.unroll = 4;
+        const int64_t want = (kSplitBelowRows + rows - 1) / rows;
+        const int by_len = nvec_max / (pl.block * 2) > 0 ? nvec_max / (pl.block * 2) : 1;  // >= 2 vectors per lane
+        const int by_part = aasd::kMaxPartials / (pl.block / aasd::kWave);
+        int n = (int)(want < by_len ? want : by_len);
+        pl.nseg = n < by_part ? n : by_part;
     }
-    return cfg;
+    if (const char* e = getenv("AASD_SWEEP_CONFIG")) {
+        int b = 0, u = 0, n = 0;
+        const int got = sscanf(e, "%d,%d,%d", &b, &u, &n);
+        if (got >= 2) { pl.block = b; pl.unroll = u; }
+        if (got >= 3 && n >= 1) pl.nseg = n;
+    }
+    const int waves = pl.block / aasd::kWave > 0 ? pl.block / aasd::kWave : 1;
+    if (pl.nseg * waves > aasd::kMaxPartials) pl.nseg = aasd::kMaxPartials / waves > 0 ? aasd::kMaxPartials / waves : 1;
+    const int per_seg = (nvec_max + pl.nseg - 1) / pl.nseg;
+    pl.seg_vecs = (per_seg + pl.block - 1) / pl.block * pl.block;
+    pl.npart = pl.nseg * waves;
+    return pl;
 }
 
 constexpr size_t kMaxChunkMaxLds = 60 * 1024;      // dynamic LDS the sweep may use for chunk maxima
-constexpr int64_t kMaxRowsPerLaunch = 1 << 22;     // keeps gridDim.x * blockDim.x below 2^32
+constexpr int64_t kMaxUnitsPerLaunch = 1 << 22;    // keeps gridDim.x * blockDim.x below 2^32
 
 template <int DT, bool ALIGN, bool COUNT, int BLOCK, int U>
-hipError_t launch_sweep_one(const aasd::SweepParams& p, int64_t rows, size_t dyn_lds, hipStream_t stream)
+hipError_t launch_sweep_one(const aasd::SweepParams& p, int64_t units, size_t dyn_lds, hipStream_t stream)
 {
-    for (int64_t row0 = 0; row0 < rows; row0 += kMaxRowsPerLaunch) {
-        const int64_t n = rows - row0 < kMaxRowsPerLaunch ? rows - row0 : kMaxRowsPerLaunch;
+    for (int64_t unit0 = 0; unit0 < units; unit0 += kMaxUnitsPerLaunch) {
+        const int64_t n = units - unit0 < kMaxUnitsPerLaunch ? units - unit0 : kMaxUnitsPerLaunch;
         hipLaunchKernelGGL((aasd::row_sweep_kernel<DT, ALIGN, COUNT, BLOCK, U>), dim3((unsigned)n), dim3(BLOCK),
-                           dyn_lds, stream, p, row0);
+                           dyn_lds, stream, p, unit0);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -64,23 +86,23 @@ hipError_t launch_sweep_one(const aasd::SweepParams& p, int64_t rows, size_t dyn
 }
 
 template <int DT, bool ALIGN, bool COUNT>
-int launch_sweep(const aasd::SweepParams& p, int64_t rows, size_t dyn_lds, hipStream_t stream)
+int launch_sweep(const aasd::SweepParams& p, const SweepPlan& pl, int64_t rows, size_t dyn_lds, hipStream_t stream)
 {
-    const SweepConfig cfg = sweep_config(ALIGN, rows);
+    const int64_t units = rows * pl.nseg;
     hipError_t e;
-    if (cfg.block == 256 && cfg.unroll == 4) e = launch_sweep_one<DT, ALIGN, COUNT, 256, 4>(p, rows, dyn_lds, stream);
-    else if (cfg.block == 256 && cfg.unroll == 2) e = launch_sweep_one<DT, ALIGN, COUNT, 256, 2>(p, rows, dyn_lds, stream);
-    else if (cfg.block == 512 && cfg.unroll == 4) e = launch_sweep_one<DT, ALIGN, COUNT, 512, 4>(p, rows, dyn_lds, stream);
-    else if (cfg.block == 512 && cfg.unroll == 2) e = launch_sweep_one<DT, ALIGN, COUNT, 512, 2>(p, rows, dyn_lds, stream);
-    else if (cfg.block == 256 && cfg.unroll == 8) e = launch_sweep_one<DT, ALIGN, COUNT, 256, 8>(p, rows, dyn_lds, stream);
-    else if (cfg.block == 512 && cfg.unroll == 8) e = launch_sweep_one<DT, ALIGN, COUNT, 512, 8>(p, rows, dyn_lds, stream);
-    else if (cfg.block == 1024 && cfg.unroll == 4) e = launch_sweep_one<DT, ALIGN, COUNT, 1024, 4>(p, rows, dyn_lds, stream);
-    else if (cfg.block == 1024 && cfg.unroll == 2) e = launch_sweep_one<DT, ALIGN, COUNT, 1024, 2>(p, rows, dyn_lds, stream);
-    else if (cfg.block == 1024 && cfg.unroll == 1) e = launch_sweep_one<DT, ALIGN, COUNT, 1024, 1>(p, rows, dyn_lds, stream);
-    else return fail(AASD_ERR_UNSUPPORTED, "AASD_SWEEP_CONFIG=%d,%d is not a compiled launch shape", cfg.block, cfg.unroll);
+    if (pl.block == 256 && pl.unroll == 4) e = launch_sweep_one<DT, ALIGN, COUNT, 256, 4>(p, units, dyn_lds, stream);
+    else if (pl.block == 256 && pl.unroll == 2) e = launch_sweep_one<DT, ALIGN, COUNT, 256, 2>(p, units, dyn_lds, stream);
+    else if (pl.block == 256 && pl.unroll == 1) e = launch_sweep_one<DT, ALIGN, COUNT, 256, 1>(p, units, dyn_lds, stream);
+    else if (pl.block == 512 && pl.unroll == 4) e = launch_sweep_one<DT, ALIGN, COUNT, 512, 4>(p, units, dyn_lds, stream);
+    else if (pl.block == 512 && pl.unroll == 2) e = launch_sweep_one<DT, ALIGN, COUNT, 512, 2>(p, units, dyn_lds, stream);
+    else if (pl.block == 1024 && pl.unroll == 2) e = launch_sweep_one<DT, ALIGN, COUNT, 1024, 2>(p, units, dyn_lds, stream);
+    else if (pl.block == 1024 && pl.unroll == 1) e = launch_sweep_one<DT, ALIGN, COUNT, 1024, 1>(p, units, dyn_lds, stream);
+    else return fail(AASD_ERR_UNSUPPORTED, "AASD_SWEEP_CONFIG=%d,%d is not a compiled launch shape", pl.block, pl.unroll);
     if (e != hipSuccess) return fail(AASD_ERR_LAUNCH, "row sweep launch failed: %s", hipGetErrorString(e));
     return AASD_OK;
 }
+
+size_t align16(size_t n) { return (n + 15) & ~(size_t)15; }
 
 }  // namespace
 
@@ -90,11 +112,19 @@ const char* aasd_version(void) { return "aasd-mi355x 0.1 (gfx950)"; }
 
 const char* aasd_last_error(void) { return g_err; }
 
+size_t aasd_align_sample_workspace_bytes(int64_t rows, int32_t V, int32_t dt)
+{
+    if (rows < 0 || V <= 0 || !valid_dtype(dt)) return 0;
+    const SweepPlan pl = plan_sweep(true, rows, V, dt);
+    return (size_t)rows * pl.npart * (sizeof(aasd::WavePartial) + aasd::kListCap * sizeof(int32_t));
+}
+
 int aasd_align_sample(const void* logits, int32_t dt, int64_t rows, int32_t V, int64_t row_stride,
                       const int32_t* next_tok, int32_t m, int32_t c, int32_t mode, uint64_t seed,
                       uint64_t row_id_base, int32_t* argmax, uint8_t* misaligned, float* entropy,
                       float* p_next, float* p_max, int32_t* rank, int32_t* extras,
-                      uint8_t* n_extras, uint32_t* near_count, void* stream)
+                      uint8_t* n_extras, uint32_t* near_count, void* workspace, size_t workspace_bytes,
+                      void* stream)
 {
     if (!valid_dtype(dt)) return fail(AASD_ERR_INVALID_ARG, "align_sample: unknown dtype %d", dt);
     if (rows < 0) return fail(AASD_ERR_INVALID_ARG, "align_sample: rows = %lld < 0", (long long)rows);
@@ -112,25 +142,59 @@ int aasd_align_sample(const void* logits, int32_t dt, int64_t rows, int32_t V, i
         return fail(AASD_ERR_INVALID_ARG, "align_sample: extras and n_extras are required when m > 0");
     if (((uintptr_t)logits % elt_size(dt)) != 0)
         return fail(AASD_ERR_UNSUPPORTED, "align_sample: logits pointer is not aligned to its element size");
+    const size_t need_ws = aasd_align_sample_workspace_bytes(rows, V, dt);
+    if (!workspace || workspace_bytes < need_ws)
+        return fail(AASD_ERR_WORKSPACE, "align_sample: workspace of %zu bytes needed, %zu given", need_ws,
+                    workspace ? workspace_bytes : (size_t)0);
+    if (((uintptr_t)workspace % 16) != 0) return fail(AASD_ERR_WORKSPACE, "align_sample: workspace is not 16-byte aligned");
+
+    const SweepPlan pl = plan_sweep(true, rows, V, dt);
+    aasd::WavePartial* partials = (aasd::WavePartial*)workspace;
+    int32_t* lists = (int32_t*)((char*)workspace + (size_t)rows * pl.npart * sizeof(aasd::WavePartial));
 
     aasd::SweepParams p{};
     p.logits = logits; p.V = V; p.row_stride = row_stride; p.seq_stride = row_stride; p.rows_per_seq = 1;
-    p.next_tok = next_tok; p.m_x = m; p.c = c; p.mode = mode; p.seed = seed; p.row_id_base = row_id_base;
-    p.argmax = argmax; p.misaligned = misaligned; p.entropy = entropy; p.p_next = p_next; p.p_max = p_max;
-    p.rank = rank; p.extras = extras; p.n_extras = n_extras; p.near_count = near_count;
-
-    // one chunk maximum per 16-byte vector of the row, kept in LDS when it fits
+    p.next_tok = next_tok; p.want_cand = m > 0; p.c = c;
+    p.nseg = pl.nseg; p.seg_vecs = pl.seg_vecs; p.partials = partials; p.lists = lists;
+    // one chunk maximum per 16-byte vector of a segment, kept in LDS when it fits
     size_t dyn = 0;
     if (m > 0 && next_tok) {
-        const size_t per_vec = dt == AASD_BF16 ? 8 : 4;
-        const size_t need = ((size_t)V / per_vec + 1) * elt_size(dt);
-        if (need <= kMaxChunkMaxLds) { dyn = (need + 15) & ~(size_t)15; p.cm_enabled = 1; }
+        const size_t need = ((size_t)pl.seg_vecs + 1) * elt_size(dt);
+        if (need <= kMaxChunkMaxLds) { dyn = align16(need); p.cm_enabled = 1; }
     }
     hipStream_t s = (hipStream_t)stream;
-    if (dt == AASD_BF16) {
-        return rank ? launch_sweep<AASD_BF16, true, true>(p, rows, dyn, s) : launch_sweep<AASD_BF16, true, false>(p, rows, dyn, s);
+    int rc;
+    if (dt == AASD_BF16)
+        rc = rank ? launch_sweep<AASD_BF16, true, true>(p, pl, rows, dyn, s) : launch_sweep<AASD_BF16, true, false>(p, pl, rows, dyn, s);
+    else
+        rc = rank ? launch_sweep<AASD_F32, true, true>(p, pl, rows, dyn, s) : launch_sweep<AASD_F32, true, false>(p, pl, rows, dyn, s);
+    if (rc != AASD_OK) return rc;
+
+    aasd::AlignFinishParams f{};
+    f.logits = logits; f.V = V; f.row_stride = row_stride; f.rows = rows; f.next_tok = next_tok;
+    f.m_x = m; f.c = c; f.mode = mode; f.seed = seed; f.row_id_base = row_id_base;
+    f.argmax = argmax; f.misaligned = misaligned; f.entropy = entropy; f.p_next = p_next; f.p_max = p_max;
+    f.rank = rank; f.extras = extras; f.n_extras = n_extras; f.near_count = near_count;
+    f.partials = partials; f.lists = lists; f.npart = pl.npart;
+    const int rows_per_block = aasd::kFinishBlock / aasd::kWave;
+    for (int64_t r0 = 0; r0 < rows; r0 += kMaxUnitsPerLaunch) {
+        const int64_t n = rows - r0 < kMaxUnitsPerLaunch ? rows - r0 : kMaxUnitsPerLaunch;
+        aasd::AlignFinishParams fc = f;
+        // a chunk of rows: shift every per-row pointer
+        fc.logits = (const char*)logits + (size_t)r0 * (size_t)row_stride * elt_size(dt);
+        fc.rows = n; fc.row_id_base = row_id_base + (uint64_t)r0;
+        fc.next_tok = next_tok ? next_tok + r0 : nullptr;
+        fc.argmax = argmax + r0; fc.misaligned = misaligned + r0; fc.entropy = entropy + r0;
+        fc.p_next = p_next + r0; fc.p_max = p_max + r0; fc.rank = rank ? rank + r0 : nullptr;
+        fc.extras = extras ? extras + r0 * m : nullptr; fc.n_extras = n_extras ? n_extras + r0 : nullptr;
+        fc.partials = partials + r0 * pl.npart; fc.lists = lists + r0 * pl.npart * aasd::kListCap;
+        const unsigned grid = (unsigned)((n + rows_per_block - 1) / rows_per_block);
+        if (dt == AASD_BF16) hipLaunchKernelGGL(aasd::align_finish_kernel<AASD_BF16>, dim3(grid), dim3(aasd::kFinishBlock), 0, s, fc);
+        else hipLaunchKernelGGL(aasd::align_finish_kernel<AASD_F32>, dim3(grid), dim3(aasd::kFinishBlock), 0, s, fc);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return fail(AASD_ERR_LAUNCH, "align finish launch failed: %s", hipGetErrorString(e));
     }
-    return rank ? launch_sweep<AASD_F32, true, true>(p, rows, dyn, s) : launch_sweep<AASD_F32, true, false>(p, rows, dyn, s);
+    return AASD_OK;
 }
 
 int aasd_retrieve_drafts(const int32_t* tokens, int64_t tok_stride, const int32_t* len,
@@ -180,10 +244,12 @@ int aasd_retrieve_drafts(const int32_t* tokens, int64_t tok_stride, const int32_
     return AASD_OK;
 }
 
-size_t aasd_verify_workspace_bytes(int32_t B, int32_t C, int32_t k)
+size_t aasd_verify_workspace_bytes(int32_t B, int32_t C, int32_t k, int32_t V, int32_t dt)
 {
-    if (B < 0 || C < 1 || C > AASD_MAX_CANDIDATES || k < 1 || k > AASD_MAX_DRAFT) return 0;
-    return (size_t)B * (size_t)(1 + C * k) * sizeof(float4);
+    if (B < 0 || C < 1 || C > AASD_MAX_CANDIDATES || k < 1 || k > AASD_MAX_DRAFT || V <= 0 || !valid_dtype(dt)) return 0;
+    const int64_t rows = (int64_t)B * (1 + C * k);
+    const SweepPlan pl = plan_sweep(false, rows, V, dt);
+    return (size_t)rows * pl.npart * sizeof(aasd::WavePartial);
 }
 
 int aasd_verify(const void* logits, int32_t dt, int32_t B, int32_t C, int32_t k, int32_t V,
@@ -209,26 +275,28 @@ int aasd_verify(const void* logits, int32_t dt, int32_t B, int32_t C, int32_t k,
         return fail(AASD_ERR_INVALID_ARG, "verify: null required pointer");
     if (((uintptr_t)logits % elt_size(dt)) != 0)
         return fail(AASD_ERR_UNSUPPORTED, "verify: logits pointer is not aligned to its element size");
-    const size_t need = aasd_verify_workspace_bytes(B, C, k);
+    const size_t need = aasd_verify_workspace_bytes(B, C, k, V, dt);
     if (!workspace || workspace_bytes < need)
         return fail(AASD_ERR_WORKSPACE, "verify: workspace of %zu bytes needed, %zu given", need, workspace ? workspace_bytes : (size_t)0);
     if (((uintptr_t)workspace % 16) != 0) return fail(AASD_ERR_WORKSPACE, "verify: workspace is not 16-byte aligned");
 
     hipStream_t s = (hipStream_t)stream;
+    const int64_t rows = (int64_t)B * R;
+    const SweepPlan pl = plan_sweep(false, rows, V, dt);
     aasd::SweepParams sp{};
     sp.logits = logits; sp.V = V; sp.row_stride = row_stride; sp.seq_stride = seq_stride; sp.rows_per_seq = (int32_t)R;
-    sp.c = 1;
-    sp.stats = (float4*)workspace; sp.row_entropy = row_entropy; sp.row_pmax = row_pmax; sp.row_argmax = row_argmax;
-    const int64_t rows = (int64_t)B * R;
-    int rc = dt == AASD_BF16 ? launch_sweep<AASD_BF16, false, false>(sp, rows, 0, s)
-                             : launch_sweep<AASD_F32, false, false>(sp, rows, 0, s);
+    sp.c = 1; sp.nseg = pl.nseg; sp.seg_vecs = pl.seg_vecs; sp.partials = (aasd::WavePartial*)workspace;
+    int rc = dt == AASD_BF16 ? launch_sweep<AASD_BF16, false, false>(sp, pl, rows, 0, s)
+                             : launch_sweep<AASD_F32, false, false>(sp, pl, rows, 0, s);
     if (rc != AASD_OK) return rc;
 
     aasd::VerifyTailParams tp{};
     tp.logits = logits; tp.B = B; tp.C = C; tp.k = k; tp.V = V; tp.row_stride = row_stride; tp.seq_stride = seq_stride;
     tp.drafts = drafts; tp.draft_len = draft_len; tp.strict = strict; tp.alpha = alpha; tp.beta = beta; tp.flags = flags;
     tp.accept_len = accept_len; tp.best_cand = best_cand; tp.next_token = next_token;
-    tp.tok_p = tok_p; tp.tok_delta = tok_delta; tp.near_count = near_count; tp.stats = (const float4*)workspace;
+    tp.tok_p = tok_p; tp.tok_delta = tok_delta; tp.near_count = near_count;
+    tp.row_entropy = row_entropy; tp.row_pmax = row_pmax; tp.row_argmax = row_argmax;
+    tp.partials = (const aasd::WavePartial*)workspace; tp.npart = pl.npart;
     if (dt == AASD_BF16)
         hipLaunchKernelGGL(aasd::verify_tail_kernel<AASD_BF16>, dim3((unsigned)B), dim3(aasd::kTailBlock), 0, s, tp);
     else

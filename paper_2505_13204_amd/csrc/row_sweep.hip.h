@@ -1,7 +1,13 @@
 // Fused single-pass row sweep: softmax normaliser, entropy, greedy pick and (for prefill
 // rows) rank of the next prompt token and the candidate tokens ranked above it.
 //
-// One workgroup owns one logits row and reads it from HBM exactly once with 16-byte loads.
+// A row is read from HBM exactly once with 16-byte loads.  A workgroup owns one row, or one of
+// several contiguous segments of a row when there are too few rows to fill the GPU.  Every
+// wave works on its own: it folds its share into a partial result (maximum, sum of
+// exponentials, entropy sum, position of the maximum, rank count, its best candidates) with
+// wave shuffles only and writes that partial to the workspace.  A second, small kernel merges
+// the partials of a row and does the per-row scalar work (see row_finish.hip.h), so the
+// streaming kernel has no barrier and no serial tail.
 // Per element the sweep does: unpack, one FMA into the log2 domain, one hardware exp2, one add
 // (sum of exponentials) and one FMA (sum of exponent * exponential, which gives the entropy as
 // ln S - T/S, Eq. 5 of Sec. 3.3 rewritten so that both terms are non-negative).  Everything
@@ -11,8 +17,9 @@
 //   - the reference exponent of the running sums, which is only moved when a chunk exceeds it
 //     by more than 44 nats (floating point does not care about a common scale),
 //   - one chunk maximum per chunk parked in LDS, from which the few chunks that can hold a
-//     top-c token are found after the sweep and re-read (Sec. 3.2 / Fig. 2 need the tokens
-//     ranked above the prompt token, not a full sort).
+//     top-c token are found after the sweep; only their positions are written out, and the
+//     finish kernel re-reads those chunks (Sec. 3.2 / Fig. 2 need the tokens ranked above the
+//     prompt token, not a full sort).
 #pragma once
 
 #include "common.hip.h"
@@ -20,8 +27,22 @@
 namespace aasd {
 
 constexpr int kNumAcc = 4;      // independent partial sums per lane (shorter rounding chains, more ILP)
-constexpr int kCandCap = 256;   // LDS candidate buffer entries per row
 constexpr float kRefSlack = 44.0f;  // nats a chunk may exceed the reference exponent before it is moved
+
+// What one wave leaves behind for the finish kernel.
+struct WavePartial {
+    float m;       // largest logit of the wave's share (-inf: the share was empty)
+    float S;       // sum of e^(z - m) over the share
+    float T;       // sum of log2(e^(z - m)) * e^(z - m)  (log2 units, <= 0)
+    int code;      // index of the first element of the chunk that holds the first maximum
+    unsigned cnt;  // elements with z > z_next
+    int nlist;     // chunks listed for this wave (they hold every token of its share that can be in the row's top-c)
+    float thr2;    // a lower bound on the c-th largest logit of the wave's share
+    int pad;
+};
+
+constexpr int kMaxPartials = 64;   // partials per row (segments x waves): one lane each in the finish kernel
+constexpr int kListCap = 48;       // chunk positions a wave may list
 
 struct SweepParams {
     const void* logits;
@@ -29,25 +50,14 @@ struct SweepParams {
     int64_t row_stride;    // elements
     int64_t seq_stride;    // elements, verification only (rows_per_seq rows per sequence)
     int32_t rows_per_seq;  // 1 for prefill rows
-    // alignment sampling
-    const int32_t* next_tok;
-    int32_t m_x, c, mode;
-    uint64_t seed, row_id_base;
-    int32_t* argmax;
-    uint8_t* misaligned;
-    float* entropy;
-    float* p_next;
-    float* p_max;
-    int32_t* rank;
-    int32_t* extras;
-    uint8_t* n_extras;
-    uint32_t* near_count;
-    int32_t cm_enabled;  // chunk maxima fit in LDS
-    // verification
-    float4* stats;  // [rows] {max logit, S, H, bits of argmax}
-    float* row_entropy;
-    float* row_pmax;
-    int32_t* row_argmax;
+    const int32_t* next_tok;  // alignment sampling only
+    int32_t want_cand;     // candidates are wanted (m > 0)
+    int32_t c;
+    int32_t cm_enabled;    // chunk maxima fit in LDS
+    int32_t nseg;          // segments per row
+    int32_t seg_vecs;      // 16-byte vectors per segment (a multiple of the block size)
+    WavePartial* partials; // [rows][nseg * waves per block]
+    int32_t* lists;        // [rows][nseg * waves per block][kListCap] first-element indices of listed chunks
 };
 
 // Running state of one lane.
@@ -113,7 +123,7 @@ __device__ __forceinline__ float accumulate(LaneAcc& a, const float (&z)[N], int
 
 // Where a row's bytes sit relative to 16-byte boundaries.
 struct RowShape {
-    const char* base;   // first element
+    const char* base;   // first element of the row
     const u32x4* vbase; // first aligned 16-byte vector
     int head;           // elements before vbase
     int nvec;           // full vectors
@@ -134,6 +144,33 @@ __device__ __forceinline__ RowShape row_shape(const void* logits, int64_t elt_of
     return s;
 }
 
+// The part of a row one workgroup sweeps: a run of vectors, plus the unaligned head elements
+// (first segment) and tail elements (last segment) of the row.
+struct SegShape {
+    const char* base;    // first element of the row (scalar loads index from here)
+    const u32x4* vbase;  // first vector of the segment
+    int first_idx;       // element index of vbase[0]
+    int nvec;            // vectors in the segment
+    int head_n;          // head elements [0, head_n) handled here
+    int tail0, tail_n;   // tail elements [tail0, tail0 + tail_n) handled here
+};
+
+template <int DT>
+__device__ __forceinline__ SegShape seg_shape(const RowShape& r, int V, int seg, int nseg, int seg_vecs)
+{
+    SegShape s;
+    const int v_lo = min(seg * seg_vecs, r.nvec);
+    const int v_hi = min(v_lo + seg_vecs, r.nvec);
+    s.base = r.base;
+    s.vbase = r.vbase + v_lo;
+    s.first_idx = r.head + v_lo * Elt<DT>::kPerVec;
+    s.nvec = v_hi - v_lo;
+    s.head_n = seg == 0 ? r.head : 0;
+    s.tail0 = r.tail0;
+    s.tail_n = seg == nseg - 1 ? V - r.tail0 : 0;
+    return s;
+}
+
 template <int DT>
 __device__ __forceinline__ void cm_store(unsigned char* cm, int vec, float cmax)
 {
@@ -150,13 +187,13 @@ __device__ __forceinline__ float cm_load(const unsigned char* cm, int vec)
 // The single HBM pass of one lane over its share of the row: vectors tid, tid+BLOCK, ...
 // loaded U at a time with the next batch in flight while the current one is folded in.
 template <int DT, bool CLAMP, bool COUNT, int BLOCK, int U>
-__device__ __forceinline__ void sweep_lane(LaneAcc& a, const RowShape& rs, int V, int tid, float zcmp,
+__device__ __forceinline__ void sweep_lane(LaneAcc& a, const SegShape& rs, int tid, float zcmp,
                                            bool store_cm, unsigned char* cm)
 {
     constexpr int EPV = Elt<DT>::kPerVec;
     lane_acc_init(a);
 
-    if (tid < rs.head) {
+    if (tid < rs.head_n) {
         const float z1[1] = {load_elt<DT>(rs.base, tid)};
         accumulate<1, CLAMP, COUNT, false>(a, z1, tid, zcmp);
     }
@@ -180,7 +217,7 @@ __device__ __forceinline__ void sweep_lane(LaneAcc& a, const RowShape& rs, int V
             float z[EPV];
             unpack<DT>(buf[u], z);
             const int vec = (it * U + u) * BLOCK + tid;
-            const float cmax = accumulate<EPV, CLAMP, COUNT, true>(a, z, rs.head + vec * EPV, zcmp);
+            const float cmax = accumulate<EPV, CLAMP, COUNT, true>(a, z, rs.first_idx + vec * EPV, zcmp);
             if (store_cm) cm_store<DT>(cm, vec, cmax);
         }
     };
@@ -207,319 +244,256 @@ __device__ __forceinline__ void sweep_lane(LaneAcc& a, const RowShape& rs, int V
             if (vec < rs.nvec) {
                 float z[EPV];
                 unpack<DT>(rem[u], z);
-                const float cmax = accumulate<EPV, CLAMP, COUNT, false>(a, z, rs.head + vec * EPV, zcmp);
+                const float cmax = accumulate<EPV, CLAMP, COUNT, false>(a, z, rs.first_idx + vec * EPV, zcmp);
                 if (store_cm) cm_store<DT>(cm, vec, cmax);
             }
         }
     }
-    if (tid < V - rs.tail0) {
+    if (tid < rs.tail_n) {
         const int idx = rs.tail0 + tid;
         const float z1[1] = {load_elt<DT>(rs.base, idx)};
         accumulate<1, CLAMP, COUNT, false>(a, z1, idx, zcmp);
     }
 }
 
-// LDS used by the row reductions of one workgroup.
-template <int NW>
-struct SweepShared {
-    float gmax[NW][8];   // maxima of the 8-lane groups of every wave
-    float S[NW];
-    float T[NW];
-    int code[NW];
-    unsigned cnt[NW];
-    unsigned ncand;
-    float cand_z[kCandCap];
-    int cand_i[kCandCap];
-    float fb_z[2][NW];   // exact fallback selection, double-buffered by round
-    int fb_i[2][NW];
-};
-
-// Exact top-c by c full re-reads of the row; only used when the candidate buffer overflowed
-// (hundreds of tokens tied near the top).  All threads of the block must call it.
-template <int DT, int BLOCK>
-__device__ void topc_by_rescan(const RowShape& rs, int V, int tid, float znext, int c,
-                               SweepShared<BLOCK / kWave>& sh, float (&kz)[AASD_MAX_CANDSET],
-                               int (&ki)[AASD_MAX_CANDSET], int& nK)
+// Visit every element of this lane's share once more (used by the rare exact fallback).
+template <int DT, int BLOCK, typename F>
+__device__ __forceinline__ void for_each_own_element(const SegShape& rs, int tid, F&& f)
 {
     constexpr int EPV = Elt<DT>::kPerVec;
-    constexpr int NW = BLOCK / kWave;
-    const int lane = tid & 63, wid = tid >> 6;
+    if (tid < rs.head_n) f(load_elt<DT>(rs.base, tid), tid);
+    for (int vec = tid; vec < rs.nvec; vec += BLOCK) {
+        float z[EPV];
+        unpack<DT>(rs.vbase[vec], z);
+#pragma unroll
+        for (int e = 0; e < EPV; ++e) f(z[e], rs.first_idx + vec * EPV + e);
+    }
+    if (tid < rs.tail_n) f(load_elt<DT>(rs.base, rs.tail0 + tid), rs.tail0 + tid);
+}
+
+// Record the r-th pick in the (register-resident) ranked list.
+__device__ __forceinline__ void set_pick(float (&kz)[AASD_MAX_CANDSET], int (&ki)[AASD_MAX_CANDSET], int r, float z, int i)
+{
+#pragma unroll
+    for (int q = 0; q < AASD_MAX_CANDSET; ++q)
+        if (q == r) { kz[q] = z; ki[q] = i; }
+}
+
+// Exact top-c of the wave's share above z_next by c re-reads of the share; only used when the
+// candidate buffer overflowed (more than 64 tokens of one wave tied near the top).
+template <int DT, int BLOCK>
+__device__ void wave_topc_by_rescan(const SegShape& rs, int tid, float znext, int c, float (&kz)[AASD_MAX_CANDSET],
+                                    int (&ki)[AASD_MAX_CANDSET], int& nK)
+{
     float pz = INFINITY;
     int pi = -1;
     nK = 0;
     for (int r = 0; r < c; ++r) {
         float bz = -INFINITY;
         int bi = 0x7fffffff;
-        auto consider = [&](float z, int idx) {
+        for_each_own_element<DT, BLOCK>(rs, tid, [&](float z, int idx) {
             const bool after_prev = (r == 0) || z < pz || (z == pz && idx > pi);
             if (z > znext && after_prev && better(z, idx, bz, bi)) { bz = z; bi = idx; }
-        };
-        if (tid < rs.head) consider(load_elt<DT>(rs.base, tid), tid);
-        for (int vec = tid; vec < rs.nvec; vec += BLOCK) {
-            float z[EPV];
-            unpack<DT>(rs.vbase[vec], z);
-#pragma unroll
-            for (int e = 0; e < EPV; ++e) consider(z[e], rs.head + vec * EPV + e);
-        }
-        if (tid < V - rs.tail0) consider(load_elt<DT>(rs.base, rs.tail0 + tid), rs.tail0 + tid);
+        });
         wave_best(bz, bi);
-        if (lane == 0) { sh.fb_z[r & 1][wid] = bz; sh.fb_i[r & 1][wid] = bi; }
-        __syncthreads();
-        bz = sh.fb_z[r & 1][0]; bi = sh.fb_i[r & 1][0];
-#pragma unroll
-        for (int w = 1; w < NW; ++w)
-            if (better(sh.fb_z[r & 1][w], sh.fb_i[r & 1][w], bz, bi)) { bz = sh.fb_z[r & 1][w]; bi = sh.fb_i[r & 1][w]; }
-        if (bi == 0x7fffffff) break;  // same decision in every thread
+        if (bi == 0x7fffffff) break;  // the same in every lane
         pz = bz; pi = bi;
-#pragma unroll
-        for (int q = 0; q < AASD_MAX_CANDSET; ++q)
-            if (q == r) { kz[q] = bz; ki[q] = bi; }
+        set_pick(kz, ki, r, bz, bi);
         nK = r + 1;
     }
 }
 
-// Top-c of the buffered candidates by wave 0 (c rounds of "best remaining").
-__device__ __forceinline__ void topc_from_buffer(const float* cand_z, const int* cand_i, int n, int lane, int c,
-                                                 float (&kz)[AASD_MAX_CANDSET], int (&ki)[AASD_MAX_CANDSET], int& nK)
+// Top-c of per-lane entries (PER_LANE each, invalid ones at -inf / INT_MAX): c rounds of "best remaining".
+template <int PER_LANE>
+__device__ __forceinline__ void wave_topc(float (&lz)[PER_LANE], int (&li)[PER_LANE], int c, float (&kz)[AASD_MAX_CANDSET],
+                                          int (&ki)[AASD_MAX_CANDSET], int& nK)
 {
-    constexpr int kPerLane = kCandCap / kWave;
-    float lz[kPerLane];
-    int li[kPerLane];
-#pragma unroll
-    for (int q = 0; q < kPerLane; ++q) {
-        const int e = lane + q * kWave;
-        lz[q] = e < n ? cand_z[e] : -INFINITY;
-        li[q] = e < n ? cand_i[e] : 0x7fffffff;
-    }
     nK = 0;
     for (int r = 0; r < c; ++r) {
         float bz = lz[0];
         int bi = li[0];
 #pragma unroll
-        for (int q = 1; q < kPerLane; ++q)
+        for (int q = 1; q < PER_LANE; ++q)
             if (better(lz[q], li[q], bz, bi)) { bz = lz[q]; bi = li[q]; }
         wave_best(bz, bi);
         if (bi == 0x7fffffff) break;
 #pragma unroll
-        for (int q = 0; q < kPerLane; ++q)
+        for (int q = 0; q < PER_LANE; ++q)
             if (li[q] == bi) { lz[q] = -INFINITY; li[q] = 0x7fffffff; }
-#pragma unroll
-        for (int q = 0; q < AASD_MAX_CANDSET; ++q)
-            if (q == r) { kz[q] = bz; ki[q] = bi; }
+        set_pick(kz, ki, r, bz, bi);
         nK = r + 1;
     }
 }
 
-// Choose the extra draft tokens of a misaligned row from its ranked candidate list K
-// (Sec. 3.2; reading: TOP takes the best-ranked, SAMPLE draws without replacement).
-__device__ __forceinline__ void choose_extras(const SweepParams& p, int64_t row, float m,
-                                              const float (&kz)[AASD_MAX_CANDSET],
-                                              const int (&ki)[AASD_MAX_CANDSET], int nK)
-{
-    int chosen[AASD_MAX_EXTRAS];
-    int n_chosen = 0;
-    if (p.mode == AASD_EXTRAS_TOP || nK <= p.m_x) {
-        for (int i = 0; i < nK && i < p.m_x; ++i) chosen[n_chosen++] = ki[i];
-    } else {
-        float w[AASD_MAX_CANDSET];
-        int id[AASD_MAX_CANDSET];
-        int n_rem = nK;
-        for (int i = 0; i < nK; ++i) { w[i] = expf(kz[i] - m); id[i] = ki[i]; }
-        const uint64_t row_id = p.row_id_base + (uint64_t)row;
-        unsigned near = 0;
-        for (int j = 0; j < p.m_x; ++j) {
-            uint32_t rnd[4];
-            philox4x32_10((uint32_t)row_id, (uint32_t)(row_id >> 32), (uint32_t)j, 0x41415344u,
-                          (uint32_t)p.seed, (uint32_t)(p.seed >> 32), rnd);
-            const float u = (float)(rnd[0] >> 8) * (1.0f / 16777216.0f);  // 24 bits: exact in fp32
-            float W = 0.f;
-            for (int i = 0; i < n_rem; ++i) W += w[i];
-            const float target = u * W;
-            float cum = 0.f, margin = INFINITY;
-            int pick = n_rem - 1;
-            bool decided = false;
-            for (int i = 0; i < n_rem; ++i) {
-                cum += w[i];
-                if (i < n_rem - 1) margin = fminf(margin, fabsf(target - cum));
-                if (!decided && cum > target) { pick = i; decided = true; }
-            }
-            if (margin < 1e-6f * W) ++near;
-            chosen[n_chosen++] = id[pick];
-            for (int i = pick; i + 1 < n_rem; ++i) { w[i] = w[i + 1]; id[i] = id[i + 1]; }
-            --n_rem;
-        }
-        if (near && p.near_count) atomicAdd(p.near_count, near);
-    }
-    for (int j = 0; j < p.m_x; ++j) p.extras[row * p.m_x + j] = j < n_chosen ? chosen[j] : -1;
-    p.n_extras[row] = (uint8_t)n_chosen;
-}
+// LDS of the sweep kernel besides the chunk maxima: one short list of chunk positions per wave.
+template <int NW>
+struct SweepShared {
+    int list[NW][kListCap];
+    unsigned count[NW];
+};
 
-// One attempt at a row.  Returns false (in every thread) if the sums came out non-finite,
-// which happens when the row holds -inf logits; the caller then repeats with CLAMP.
+// One attempt of a wave at its share.  Returns false (in every lane) if the sums came out
+// non-finite, which happens when the share holds -inf logits; the caller repeats with CLAMP.
 template <int DT, bool ALIGN, bool COUNT, bool CLAMP, int BLOCK, int U>
-__device__ __forceinline__ bool process_row(const SweepParams& p, int64_t row, const RowShape& rs,
-                                            SweepShared<BLOCK / kWave>& sh, unsigned char* cm)
+__device__ __forceinline__ bool process_wave(const SweepParams& p, const SegShape& rs, bool has_next, float znext,
+                                             SweepShared<BLOCK / kWave>& sh, unsigned char* cm, const RowShape& row_s,
+                                             WavePartial* out, int32_t* out_list)
 {
     constexpr int EPV = Elt<DT>::kPerVec;
-    constexpr int NW = BLOCK / kWave;
     const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
-    const int V = p.V;
-
-    int nt = -1;
-    float znext = 0.f;
-    if (ALIGN) {
-        nt = p.next_tok ? p.next_tok[row] : -1;
-        if (nt >= V) nt = -1;
-        if (nt >= 0) znext = load_elt<DT>(rs.base, nt);
-    }
-    const bool has_next = ALIGN && nt >= 0;
-    const bool want_cand = has_next && p.m_x > 0;
+    const bool want_cand = ALIGN && has_next && p.want_cand;
     const float zcmp = has_next ? znext : INFINITY;
 
     LaneAcc a;
-    sweep_lane<DT, CLAMP, ALIGN && COUNT, BLOCK, U>(a, rs, V, tid, zcmp, want_cand && p.cm_enabled, cm);
+    sweep_lane<DT, CLAMP, ALIGN && COUNT, BLOCK, U>(a, rs, tid, zcmp, want_cand && p.cm_enabled, cm);
 
-    // ---- round 1: row maximum, and a lower bound on the c-th largest logit ----
-    float g = a.vmax;
-    g = fmaxf(g, __shfl_xor(g, 1));
-    g = fmaxf(g, __shfl_xor(g, 2));
-    g = fmaxf(g, __shfl_xor(g, 4));
-    if ((lane & 7) == 0) sh.gmax[wid][lane >> 3] = g;
-    if (tid == 0) sh.ncand = 0;
-    __syncthreads();
-    float G = sh.gmax[0][lane & 7];
-#pragma unroll
-    for (int w = 1; w < NW; ++w) G = fmaxf(G, sh.gmax[w][lane & 7]);
-    // G: maximum over class j = lane & 7, the j-th 8-lane group of every wave (a partition of the row)
+    // ---- wave maximum, and a lower bound on the c-th largest logit of the wave's share ----
+    float G = a.vmax;  // becomes the maximum of this lane's 4-lane group
+    G = fmaxf(G, __shfl_xor(G, 1));
+    G = fmaxf(G, __shfl_xor(G, 2));
     float m = G;
-    m = fmaxf(m, __shfl_xor(m, 1));
-    m = fmaxf(m, __shfl_xor(m, 2));
-    m = fmaxf(m, __shfl_xor(m, 4));
+#pragma unroll
+    for (int o = 4; o < 64; o <<= 1) m = fmaxf(m, __shfl_xor(m, o));
     float thr2 = -INFINITY;
     if (ALIGN) {
-        // Merge the 8 classes into c' >= c classes (c' a power of two).  Each class maximum is a
-        // distinct element, so the smallest of them is a lower bound on the c-th largest logit.
-        const int merge = p.c > 4 ? 1 : (p.c > 2 ? 2 : (p.c > 1 ? 4 : 8));
-        thr2 = G;
-        for (int o = 1; o < merge; o <<= 1) thr2 = fmaxf(thr2, __shfl_xor(thr2, o));
-        for (int o = merge; o < 8; o <<= 1) thr2 = fminf(thr2, __shfl_xor(thr2, o));
+        // The 16 group maxima are 16 distinct elements, so the c-th largest of them (c <= 8) bounds the
+        // c-th largest logit from below.  Bitonic sort of the 16 values (descending in group index);
+        // the number of elements above this bound has a light tail, unlike a minimum over c classes.
+        const int g = lane >> 2;
+        float v = G;
+#pragma unroll
+        for (int k = 2; k <= 16; k <<= 1) {
+#pragma unroll
+            for (int j = k >> 1; j > 0; j >>= 1) {
+                const float o = __shfl_xor(v, j << 2);
+                const bool desc = (g & k) == 0;    // direction of this block (the last stage: all descending)
+                const bool lower = (g & j) == 0;   // this lane holds the lower-indexed element of the pair
+                v = (lower == desc) ? fmaxf(v, o) : fminf(v, o);
+            }
+        }
+        thr2 = __shfl(v, (p.c - 1) << 2);
     }
 
     // ---- lane sums brought to the common reference m ----
     const float M2 = m * kLog2e;
     const float res = fmaf(m, kLog2e, -M2);  // rounding error of M2, so that the maximum weighs exactly 1
-    float ssum = (a.s[0] + a.s[1]) + (a.s[2] + a.s[3]);
-    float tsum = (a.t[0] + a.t[1]) + (a.t[2] + a.t[3]);
+    const float ssum = (a.s[0] + a.s[1]) + (a.s[2] + a.s[3]);
+    const float tsum = (a.t[0] + a.t[1]) + (a.t[2] + a.t[3]);
     const float dlt = (a.r2 - M2) - res;
     const float f = __builtin_amdgcn_exp2f(dlt);
-    float Sp = ssum * f;
-    float Tp = (tsum + dlt * ssum) * f;
-
-    // ---- candidates ranked above the prompt token (misaligned rows only) ----
-    const bool mis = has_next && (znext < m);
-    if (ALIGN && want_cand && mis) {
-        auto consider = [&](float z, int idx) {
-            if (z > znext && z >= thr2) {
-                const unsigned pos = atomicAdd(&sh.ncand, 1u);
-                if (pos < (unsigned)kCandCap) { sh.cand_z[pos] = z; sh.cand_i[pos] = idx; }
-            }
-        };
-        if (a.vmax > znext && a.vmax >= thr2) {  // only lanes that saw a qualifying element look again
-            if (tid < rs.head) consider(load_elt<DT>(rs.base, tid), tid);
-            for (int vec = tid; vec < rs.nvec; vec += BLOCK) {
-                const float cmx = p.cm_enabled ? cm_load<DT>(cm, vec) : INFINITY;  // own entries: no barrier needed
-                if (cmx > znext && cmx >= thr2) {
-                    float z[EPV];
-                    unpack<DT>(rs.vbase[vec], z);
-#pragma unroll
-                    for (int e = 0; e < EPV; ++e) consider(z[e], rs.head + vec * EPV + e);
-                }
-            }
-            if (tid < V - rs.tail0) consider(load_elt<DT>(rs.base, rs.tail0 + tid), rs.tail0 + tid);
-        }
+    const float S = wave_sum(ssum * f);
+    const float T = wave_sum((tsum + dlt * ssum) * f);
+    if (!CLAMP) {
+        if (!(S > 0.f) || !(S < INFINITY) || T != T) return false;
     }
-
-    // ---- round 2: sums, position of the maximum, rank ----
-    Sp = wave_sum(Sp);
-    Tp = wave_sum(Tp);
     const int code = wave_min(a.vmax == m ? a.code : 0x7fffffff);
     unsigned cnt = 0;
     if (ALIGN && COUNT) cnt = a.cnt_u + wave_sum(a.cnt_l);
-    if (lane == 0) { sh.S[wid] = Sp; sh.T[wid] = Tp; sh.code[wid] = code; sh.cnt[wid] = cnt; }
-    __syncthreads();
-    float S = 0.f, T2 = 0.f;
-    int bcode = 0x7fffffff;
-    unsigned rank = 0;
-#pragma unroll
-    for (int w = 0; w < NW; ++w) {
-        S += sh.S[w]; T2 += sh.T[w];
-        bcode = min(bcode, sh.code[w]);
-        rank += sh.cnt[w];
-    }
-    if (!CLAMP) {
-        if (!(S > 0.f) || !(S < INFINITY) || T2 != T2) return false;
-    }
 
-    float kz[AASD_MAX_CANDSET];
-    int ki[AASD_MAX_CANDSET];
-    int nK = 0;
-#pragma unroll
-    for (int q = 0; q < AASD_MAX_CANDSET; ++q) { kz[q] = 0.f; ki[q] = -1; }
-    if (ALIGN && want_cand && mis) {
-        const unsigned nc = sh.ncand;
-        if (nc > (unsigned)kCandCap) topc_by_rescan<DT, BLOCK>(rs, V, tid, znext, p.c, sh, kz, ki, nK);
-        else if (wid == 0) topc_from_buffer(sh.cand_z, sh.cand_i, (int)nc, lane, p.c, kz, ki, nK);
-    }
-
-    if (tid == 0) {
-        // greedy pick: first element of chunk `bcode` that attains the maximum
-        int am = 0;
-        if ((unsigned)bcode < (unsigned)V) {  // always, unless the row holds no comparable value at all
-            am = bcode;
-            const int len = (bcode >= rs.head && bcode < rs.tail0) ? EPV : 1;
-            for (int e = 0; e < len; ++e)
-                if (load_elt<DT>(rs.base, bcode + e) == m) { am = bcode + e; break; }
-        }
-        // fp32 is enough for the per-row scalars: logf/expf are good to an ulp, far inside the tolerance
-        float H = logf(S) - (float)kLn2 * T2 / S;
-        if (H < 0.f) H = 0.f;
-        const float pmax = 1.0f / S;
-        if (ALIGN) {
-            p.argmax[row] = am;
-            p.entropy[row] = H;
-            p.p_max[row] = pmax;
-            p.misaligned[row] = mis ? 1 : 0;
-            p.p_next[row] = has_next ? expf(znext - m) / S : 0.f;
-            if (COUNT) p.rank[row] = has_next ? (int32_t)rank : -1;
-            if (p.m_x > 0) {
-                if (want_cand && mis) choose_extras(p, row, m, kz, ki, nK);
-                else {
-                    for (int j = 0; j < p.m_x; ++j) p.extras[row * p.m_x + j] = -1;
-                    p.n_extras[row] = 0;
-                }
+    // ---- chunks of this wave's share that can hold a token of the row's top-c above the prompt token ----
+    int nlist = 0;
+    if (want_cand && znext < m) {
+        if (lane == 0) sh.count[wid] = 0;
+        if (a.vmax > znext && a.vmax >= thr2) {  // only lanes that saw a qualifying element look again
+            auto note = [&](int first_elem) {
+                const unsigned pos = atomicAdd(&sh.count[wid], 1u);
+                if (pos < (unsigned)kListCap) sh.list[wid][pos] = first_elem;
+            };
+            if (tid < rs.head_n) {
+                const float z = load_elt<DT>(rs.base, tid);
+                if (z > znext && z >= thr2) note(tid);
             }
-        } else {
-            p.stats[row] = make_float4(m, S, H, __int_as_float(am));
-            if (p.row_entropy) p.row_entropy[row] = H;
-            if (p.row_pmax) p.row_pmax[row] = pmax;
-            if (p.row_argmax) p.row_argmax[row] = am;
+            for (int vec = tid; vec < rs.nvec; vec += BLOCK) {
+                float cmx;
+                if (p.cm_enabled) {
+                    cmx = cm_load<DT>(cm, vec);  // entries this lane wrote itself: LDS only, no barrier needed
+                } else {                          // vocabulary too large for LDS: look at the chunk again
+                    float z[EPV];
+                    unpack<DT>(rs.vbase[vec], z);
+                    cmx = z[0];
+#pragma unroll
+                    for (int e = 1; e < EPV; ++e) cmx = fmaxf(cmx, z[e]);
+                }
+                if (cmx > znext && cmx >= thr2) note(rs.first_idx + vec * EPV);
+            }
+            if (tid < rs.tail_n) {
+                const float z = load_elt<DT>(rs.base, rs.tail0 + tid);
+                if (z > znext && z >= thr2) note(rs.tail0 + tid);
+            }
         }
+        __threadfence_block();  // the wave's LDS appends are complete before they are read back
+        const unsigned n = sh.count[wid];
+        if (n <= (unsigned)kListCap) {
+            nlist = (int)n;
+            if (lane < nlist) out_list[lane] = sh.list[wid][lane];
+        } else {
+            // more than kListCap chunks tie near the top: find the share's exact top-c and list their chunks
+            float kz[AASD_MAX_CANDSET];
+            int ki[AASD_MAX_CANDSET];
+#pragma unroll
+            for (int q = 0; q < AASD_MAX_CANDSET; ++q) { kz[q] = 0.f; ki[q] = -1; }
+            wave_topc_by_rescan<DT, BLOCK>(rs, tid, znext, p.c, kz, ki, nlist);
+            if (lane < nlist) {
+                int idx = -1;
+#pragma unroll
+                for (int q = 0; q < AASD_MAX_CANDSET; ++q)
+                    if (q == lane) idx = ki[q];
+                const bool in_body = idx >= row_s.head && idx < row_s.tail0;
+                out_list[lane] = in_body ? row_s.head + (idx - row_s.head) / EPV * EPV : idx;
+            }
+        }
+    }
+
+    if (lane == 0) {
+        WavePartial wp;
+        wp.m = m; wp.S = S; wp.T = T; wp.code = code; wp.cnt = cnt; wp.nlist = nlist; wp.thr2 = thr2; wp.pad = 0;
+        *out = wp;
     }
     return true;
 }
 
+// Streaming kernel: grid = rows x segments; every wave writes one WavePartial.
 template <int DT, bool ALIGN, bool COUNT, int BLOCK, int U>
-__global__ __launch_bounds__(BLOCK) void row_sweep_kernel(SweepParams p, int64_t row0)
+__global__ __launch_bounds__(BLOCK) void row_sweep_kernel(SweepParams p, int64_t unit0)
 {
-    extern __shared__ __align__(16) unsigned char cm[];  // chunk maxima of this row (alignment sampling only)
-    __shared__ SweepShared<BLOCK / kWave> sh;
-    const int64_t row = row0 + blockIdx.x;
+    constexpr int NW = BLOCK / kWave;
+    extern __shared__ __align__(16) unsigned char cm[];  // chunk maxima of this segment (alignment sampling only)
+    __shared__ SweepShared<ALIGN ? NW : 1> sh_store;
+    SweepShared<NW>& sh = *reinterpret_cast<SweepShared<NW>*>(&sh_store);  // not touched unless ALIGN
+
+    const int64_t unit = unit0 + blockIdx.x;
+    const int64_t row = unit / p.nseg;
+    const int seg = (int)(unit - row * p.nseg);
     const int64_t off = (row / p.rows_per_seq) * p.seq_stride + (row % p.rows_per_seq) * p.row_stride;
-    const RowShape rs = row_shape<DT>(p.logits, off, p.V);
-    if (!process_row<DT, ALIGN, COUNT, false, BLOCK, U>(p, row, rs, sh, cm)) {
-        __syncthreads();  // everyone has read the failed attempt's partials
-        process_row<DT, ALIGN, COUNT, true, BLOCK, U>(p, row, rs, sh, cm);
+    const RowShape row_s = row_shape<DT>(p.logits, off, p.V);
+    const SegShape rs = seg_shape<DT>(row_s, p.V, seg, p.nseg, p.seg_vecs);
+    const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
+
+    const int64_t slot = (row * p.nseg + seg) * NW + wid;
+    WavePartial* out = p.partials + slot;
+    int32_t* out_list = ALIGN ? p.lists + slot * kListCap : nullptr;
+
+    // a wave whose lanes own no element at all leaves the neutral partial
+    const bool owns = tid < rs.head_n || tid < rs.nvec || tid < rs.tail_n;
+    if (__ballot(owns) == 0ull) {
+        if (lane == 0) {
+            WavePartial wp;
+            wp.m = -INFINITY; wp.S = 0.f; wp.T = 0.f; wp.code = 0x7fffffff; wp.cnt = 0; wp.nlist = 0; wp.thr2 = -INFINITY; wp.pad = 0;
+            *out = wp;
+        }
+        return;
     }
+
+    int nt = -1;
+    float znext = 0.f;
+    if (ALIGN) {
+        nt = p.next_tok ? p.next_tok[row] : -1;
+        if (nt >= p.V) nt = -1;
+        if (nt >= 0) znext = load_elt<DT>(row_s.base, nt);
+    }
+    const bool has_next = ALIGN && nt >= 0;
+    if (!process_wave<DT, ALIGN, COUNT, false, BLOCK, U>(p, rs, has_next, znext, sh, cm, row_s, out, out_list))
+        process_wave<DT, ALIGN, COUNT, true, BLOCK, U>(p, rs, has_next, znext, sh, cm, row_s, out, out_list);
 }
 
 }  // namespace aasd

@@ -24,8 +24,8 @@ def test_exports_every_declared_symbol(lib):
     header = open(os.path.join(ROOT, "include", "aasd.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(aasd_[a-z_]+)\s*\(", header))
-    assert {"aasd_version", "aasd_last_error", "aasd_align_sample", "aasd_retrieve_drafts",
-            "aasd_verify_workspace_bytes", "aasd_verify"} <= names
+    assert {"aasd_version", "aasd_last_error", "aasd_align_sample", "aasd_align_sample_workspace_bytes",
+            "aasd_retrieve_drafts", "aasd_verify_workspace_bytes", "aasd_verify"} <= names
     for n in names:
         assert hasattr(lib, n), n
     assert b"gfx950" in lib.aasd_version()
@@ -33,11 +33,12 @@ def test_exports_every_declared_symbol(lib):
 
 def _align(lib, **kw):
     a = dict(logits=FAKE, dt=1, rows=4, V=100, row_stride=100, next_tok=FAKE, m=2, c=4, mode=0, seed=0, base=0,
-             argmax=FAKE, mis=FAKE, ent=FAKE, pn=FAKE, pm=FAKE, rank=FAKE, extras=FAKE, nx=FAKE, near=None, stream=None)
+             argmax=FAKE, mis=FAKE, ent=FAKE, pn=FAKE, pm=FAKE, rank=FAKE, extras=FAKE, nx=FAKE, near=None, ws=FAKE,
+             wsb=1 << 20, stream=None)
     a.update(kw)
     return lib.aasd_align_sample(a["logits"], a["dt"], a["rows"], a["V"], a["row_stride"], a["next_tok"], a["m"], a["c"],
                                  a["mode"], a["seed"], a["base"], a["argmax"], a["mis"], a["ent"], a["pn"], a["pm"],
-                                 a["rank"], a["extras"], a["nx"], a["near"], a["stream"])
+                                 a["rank"], a["extras"], a["nx"], a["near"], a["ws"], a["wsb"], a["stream"])
 
 
 def test_align_sample_rejects_invalid_arguments(lib):
@@ -47,7 +48,10 @@ def test_align_sample_rejects_invalid_arguments(lib):
         assert _align(lib, **kw) == INVALID, kw
         assert lib.aasd_last_error() != b""
     assert _align(lib, logits=FAKE + 1) == UNSUPPORTED
-    assert _align(lib, rows=0, logits=None) == 0  # empty call is a successful no-op
+    assert _align(lib, ws=None) == WORKSPACE
+    assert _align(lib, wsb=lib.aasd_align_sample_workspace_bytes(4, 100, 1) - 1) == WORKSPACE
+    assert _align(lib, ws=FAKE + 8) == WORKSPACE
+    assert _align(lib, rows=0, logits=None, ws=None) == 0  # empty call is a successful no-op
 
 
 def _retrieve(lib, **kw):
@@ -83,15 +87,25 @@ def test_verify_rejects_invalid_arguments(lib):
         assert _verify(lib, **kw) == INVALID, kw
     assert _verify(lib, logits=FAKE + 1) == UNSUPPORTED
     assert _verify(lib, ws=None) == WORKSPACE
-    assert _verify(lib, wsb=2 * 9 * 16 - 1) == WORKSPACE
+    assert _verify(lib, wsb=lib.aasd_verify_workspace_bytes(2, 2, 4, 100, 1) - 1) == WORKSPACE
     assert _verify(lib, ws=FAKE + 4) == WORKSPACE
     assert b"workspace" in lib.aasd_last_error()
     assert _verify(lib, B=0) == 0
 
 
 def test_workspace_query(lib):
-    assert lib.aasd_verify_workspace_bytes(2, 2, 4) == 2 * 9 * 16
-    assert lib.aasd_verify_workspace_bytes(64, 16, 8) == 64 * 129 * 16
-    assert lib.aasd_verify_workspace_bytes(1, 0, 4) == 0
-    assert lib.aasd_verify_workspace_bytes(1, 4, 17) == 0
-    assert lib.aasd_verify_workspace_bytes(0, 1, 1) == 0
+    """One 32-byte partial per wave of the sweep; alignment sampling adds a list of 48 chunk positions."""
+    big = lib.aasd_verify_workspace_bytes(64, 16, 8, 152064, 1)      # 8256 rows, one workgroup of 16 waves per row
+    assert big == 64 * 129 * 16 * 32
+    small = lib.aasd_verify_workspace_bytes(1, 1, 8, 128256, 1)      # 9 rows: rows are cut into segments
+    assert small % (9 * 32) == 0 and 9 * 32 < small <= 9 * 64 * 32
+    assert lib.aasd_verify_workspace_bytes(1, 0, 4, 100, 1) == 0
+    assert lib.aasd_verify_workspace_bytes(1, 4, 17, 100, 1) == 0
+    assert lib.aasd_verify_workspace_bytes(1, 4, 8, 0, 1) == 0
+    assert lib.aasd_verify_workspace_bytes(1, 4, 8, 100, 5) == 0
+    assert lib.aasd_verify_workspace_bytes(0, 1, 1, 100, 1) == 0
+    a = lib.aasd_align_sample_workspace_bytes(65536, 128256, 1)   # 4 waves per row
+    assert a == 65536 * 4 * (32 + 48 * 4)
+    assert lib.aasd_align_sample_workspace_bytes(10, 0, 1) == 0
+    assert lib.aasd_align_sample_workspace_bytes(10, 128256, 3) == 0
+    assert lib.aasd_align_sample_workspace_bytes(0, 128256, 1) == 0

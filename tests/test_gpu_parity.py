@@ -145,10 +145,12 @@ def test_align_sample_frequencies_on_device():
     assert np.all(np.abs(counts - rows * p) < 4 * np.sqrt(rows * p * (1 - p)))
 
 
-@pytest.mark.parametrize("shape", ["256,2", "256,4", "256,8", "512,2", "512,4", "512,8", "1024,1", "1024,2", "1024,4"])
+@pytest.mark.parametrize("shape", ["256,1", "256,2", "256,4", "512,2", "512,4", "1024,1", "1024,2",
+                                   "256,4,1", "256,4,2", "256,2,5", "256,1,16", "512,2,8", "1024,1,4"])
 def test_every_compiled_launch_shape(shape, monkeypatch):
-    """The sweep is compiled for several (threads per row, loads in flight) shapes; the library picks by
-    row count.  Each shape must give the same answers: force them one by one."""
+    """The sweep is compiled for several (threads per workgroup, loads in flight) shapes and cuts rows into
+    segments when there are few of them; the library picks by row count.  Every plan must give the same
+    answers: force them one by one ("block,unroll[,segments]")."""
     monkeypatch.setenv("AASD_SWEEP_CONFIG", shape)
     rng = np.random.default_rng(17)
     rows, V = 24, 128256 // 4 + 5   # several full batches for the widest shape, plus a ragged tail
