@@ -37,7 +37,8 @@ def parse():
     ap.add_argument("--prefill-rows", type=int, default=None, help="cap on prefill rows held in HBM")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-latency", action="store_true")
-    ap.add_argument("--traffic-json", default=None, help="JSON file with measured HBM bytes per launch (from rocprofv3 --pmc)")
+    ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "row_sweep_traffic.txt"),
+                    help="text file with HBM bytes per launch measured by rocprofv3 --pmc (key = value lines)")
     return ap.parse_args()
 
 
@@ -140,19 +141,38 @@ def main():
     torch.cuda.synchronize()
 
     # ---------------------------------------------------------------- timed region: exactly K steps
+    # HIP events on the stream the kernels run on: one pair around each API call, and (through the
+    # library's measurement hook) one pair around each row-sweep kernel alone.
+    import ctypes
+    hip = ctypes.CDLL("libamdhip64.so")
+
+    def hip_event():
+        e = ctypes.c_void_p()
+        assert hip.hipEventCreate(ctypes.byref(e)) == 0
+        return e
+
+    def hip_elapsed(a, b):
+        ms = ctypes.c_float()
+        assert hip.hipEventElapsedTime(ctypes.byref(ms), a, b) == 0
+        return ms.value
+
     K = args.steps
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(K)]
+    kev = [[hip_event() for _ in range(4)] for _ in range(K)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(K):
         ev[i][0].record()
+        aasd.set_sweep_events(kev[i][0], kev[i][1])
         aasd.align_sample(prefill, next_tok_d, m=w.m, c=w.c, mode=aasd.EXTRAS_TOP, seed=w.seed, out=align_out)
         ev[i][1].record()
         aasd.retrieve_drafts(tokens_b, len_b, plen_b, w.n_min, w.n_max, w.k, w.C, out=r_out)
         ev[i][2].record()
+        aasd.set_sweep_events(kev[i][2], kev[i][3])
         aasd.verify(verify_logits, r_out["drafts"], r_out["draft_len"], r_out["strict"], alpha=w.alpha, beta=w.beta,
                     workspace=ws, want_rows=False, want_tokens=False, out=v_out)
         ev[i][3].record()
+    aasd.set_sweep_events(None, None)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / K
@@ -160,28 +180,37 @@ def main():
     align_ms = float(np.mean([ev[i][0].elapsed_time(ev[i][1]) for i in range(K)]))
     retr_ms = float(np.mean([ev[i][1].elapsed_time(ev[i][2]) for i in range(K)]))
     verify_ms = float(np.mean([ev[i][2].elapsed_time(ev[i][3]) for i in range(K)]))
+    align_sweep_ms = float(np.mean([hip_elapsed(kev[i][0], kev[i][1]) for i in range(K)]))
+    verify_sweep_ms = float(np.mean([hip_elapsed(kev[i][2], kev[i][3]) for i in range(K)]))
 
     row_bytes = w.V * elt
-    align_gbs = prefill_rows * row_bytes / (align_ms * 1e-3) / 1e9
-    verify_gbs = verify_rows * row_bytes / (verify_ms * 1e-3) / 1e9
+    align_gbs = prefill_rows * row_bytes / (align_sweep_ms * 1e-3) / 1e9
+    verify_gbs = verify_rows * row_bytes / (verify_sweep_ms * 1e-3) / 1e9
+    # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE), if this workload was profiled
     traffic = None
-    if args.traffic_json and os.path.exists(args.traffic_json):
-        traffic = json.load(open(args.traffic_json))
-    # the dominant kernel is the row sweep; its verify instantiation moves the most bytes per step here
-    dom = "verify" if verify_ms >= align_ms else "align"
+    measured = {}
+    if args.traffic_file and os.path.exists(args.traffic_file):
+        for line in open(args.traffic_file):
+            if "=" in line and not line.lstrip().startswith("#"):
+                k_, v_ = line.split("=", 1)
+                measured[k_.strip()] = v_.strip()
+    # the dominant kernel is the row sweep; of its two launches per step the one that runs longer is reported
+    dom = "verify" if verify_sweep_ms >= align_sweep_ms else "align"
+    key = f"{w.name}.{dom}_sweep.hbm_bytes_per_launch"
+    if key in measured and measured.get(f"{w.name}.{dom}_sweep.rows") == str(verify_rows if dom == "verify" else prefill_rows):
+        traffic = int(float(measured[key]))
+    dom_rows, dom_ms, dom_gbs = ((verify_rows, verify_sweep_ms, verify_gbs) if dom == "verify"
+                                 else (prefill_rows, align_sweep_ms, align_gbs))
     roofline = {
-        "bound": "hbm", "kernel": f"row_sweep_kernel ({dom} instantiation)",
-        "achieved": round(verify_gbs if dom == "verify" else align_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-        "frac": round((verify_gbs if dom == "verify" else align_gbs) / HBM_PEAK_GBS, 4),
-        "traffic": traffic,
-        "bytes_per_launch": (verify_rows if dom == "verify" else prefill_rows) * row_bytes,
-        "avg_launch_ms": round(verify_ms if dom == "verify" else align_ms, 4),
-        "align_sample": {"rows": prefill_rows, "ms": round(align_ms, 4), "GB/s": round(align_gbs, 1),
-                         "frac": round(align_gbs / HBM_PEAK_GBS, 4)},
-        "verify": {"rows": verify_rows, "ms": round(verify_ms, 4), "GB/s": round(verify_gbs, 1),
-                   "frac": round(verify_gbs / HBM_PEAK_GBS, 4),
-                   "note": "events bracket the sweep and the per-sequence accept-scan kernel"},
-        "retrieve_drafts": {"sequences": BB, "ms": round(retr_ms, 4)},
+        "bound": "hbm", "kernel": f"aasd::row_sweep_kernel ({dom} launch, {dom_rows} rows)",
+        "achieved": round(dom_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(dom_gbs / HBM_PEAK_GBS, 4),
+        "traffic": traffic, "bytes_per_launch": dom_rows * row_bytes, "avg_launch_ms": round(dom_ms, 4),
+        "align_sample": {"rows": prefill_rows, "sweep_kernel_ms": round(align_sweep_ms, 4), "GB/s": round(align_gbs, 1),
+                         "frac": round(align_gbs / HBM_PEAK_GBS, 4), "call_ms": round(align_ms, 4)},
+        "verify": {"rows": verify_rows, "sweep_kernel_ms": round(verify_sweep_ms, 4), "GB/s": round(verify_gbs, 1),
+                   "frac": round(verify_gbs / HBM_PEAK_GBS, 4), "call_ms": round(verify_ms, 4)},
+        "retrieve_drafts": {"sequences": BB, "call_ms": round(retr_ms, 4)},
+        "note": "kernel times: HIP events recorded by the library around the sweep kernel alone; call times include the finish kernels",
     }
 
     # ---------------------------------------------------------------- sequential per-step latency (context)

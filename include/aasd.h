@@ -59,6 +59,14 @@ const char *aasd_version(void);
 const char *aasd_last_error(void);
 
 /*
+ * Measurement hook, not part of the method: while two hipEvent_t handles (passed as void*) are
+ * set for the calling thread, aasd_align_sample and aasd_verify record `start` on the stream
+ * immediately before and `stop` immediately after their row-sweep kernel, so that a caller can
+ * time that kernel alone.  Pass NULL, NULL to switch it off (the default).
+ */
+void aasd_set_sweep_events(void *start, void *stop);
+
+/*
  * Alignment sampling over the prefill logits (Sec. 2.3 for aligned/misaligned
  * positions; Sec. 3.2 and the caption of Fig. 2 for the extra tokens; Sec. 4.1
  * for the cap of two extras per position).

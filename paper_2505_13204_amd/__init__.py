@@ -36,6 +36,11 @@ def _check(rc: int):
         raise AasdError(rc, _lib.load().aasd_last_error().decode())
 
 
+def set_sweep_events(start, stop):
+    """Measurement hook: raw hipEvent_t handles (ints) recorded around the row-sweep kernel; None, None = off."""
+    _lib.load().aasd_set_sweep_events(start, stop)
+
+
 def _dtype_code(t: torch.Tensor) -> int:
     if t.dtype == torch.float32:
         return F32

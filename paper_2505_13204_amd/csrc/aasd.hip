@@ -17,6 +17,7 @@
 namespace {
 
 thread_local char g_err[512] = "";
+thread_local hipEvent_t g_sweep_start = nullptr, g_sweep_stop = nullptr;  // measurement hook
 
 int fail(int code, const char* fmt, ...)
 {
@@ -90,6 +91,7 @@ int launch_sweep(const aasd::SweepParams& p, const SweepPlan& pl, int64_t rows, 
 {
     const int64_t units = rows * pl.nseg;
     hipError_t e;
+    if (g_sweep_start) (void)hipEventRecord(g_sweep_start, stream);
     if (pl.block == 256 && pl.unroll == 4) e = launch_sweep_one<DT, ALIGN, COUNT, 256, 4>(p, units, dyn_lds, stream);
     else if (pl.block == 256 && pl.unroll == 2) e = launch_sweep_one<DT, ALIGN, COUNT, 256, 2>(p, units, dyn_lds, stream);
     else if (pl.block == 256 && pl.unroll == 1) e = launch_sweep_one<DT, ALIGN, COUNT, 256, 1>(p, units, dyn_lds, stream);
@@ -98,6 +100,7 @@ int launch_sweep(const aasd::SweepParams& p, const SweepPlan& pl, int64_t rows, 
     else if (pl.block == 1024 && pl.unroll == 2) e = launch_sweep_one<DT, ALIGN, COUNT, 1024, 2>(p, units, dyn_lds, stream);
     else if (pl.block == 1024 && pl.unroll == 1) e = launch_sweep_one<DT, ALIGN, COUNT, 1024, 1>(p, units, dyn_lds, stream);
     else return fail(AASD_ERR_UNSUPPORTED, "AASD_SWEEP_CONFIG=%d,%d is not a compiled launch shape", pl.block, pl.unroll);
+    if (g_sweep_stop) (void)hipEventRecord(g_sweep_stop, stream);
     if (e != hipSuccess) return fail(AASD_ERR_LAUNCH, "row sweep launch failed: %s", hipGetErrorString(e));
     return AASD_OK;
 }
@@ -111,6 +114,12 @@ extern "C" {
 const char* aasd_version(void) { return "aasd-mi355x 0.1 (gfx950)"; }
 
 const char* aasd_last_error(void) { return g_err; }
+
+void aasd_set_sweep_events(void* start, void* stop)
+{
+    g_sweep_start = (hipEvent_t)start;
+    g_sweep_stop = (hipEvent_t)stop;
+}
 
 size_t aasd_align_sample_workspace_bytes(int64_t rows, int32_t V, int32_t dt)
 {

@@ -338,3 +338,91 @@ def test_workloads_scaled(name, rows_n, steps):
     pb2 = bk.ParityBackend(DEV)
     harness.decode(synth.scaled(w, steps=2), pb2, peaked=True)
     print(name, tally, pb.tally, pb2.tally, "MAL", trace.mean_accept_len)
+
+
+# --------------------------------------------------------------------------- full sizes, in the launch plans bench.py times
+def _sample_rows(n, k, rng):
+    idx = np.unique(np.concatenate([[0, n - 1], rng.choice(n, size=min(k, n), replace=False)]))
+    return idx
+
+
+def test_full_size_llama3_single_as_benched():
+    """Config 2 at full size in bench.py's launch configuration: alignment sampling over all 2048 prefill
+    rows in one call, verification of all 512 decode steps as one batch of 512 x 9 rows.  The oracle checks
+    every prefill row and every decode step."""
+    w = synth.WORKLOADS["llama3_single"]
+    tally = bk.Tally()
+    _align_workload(w, 0, slice(0, w.L), tally, mode=oracle.EXTRAS_TOP)
+    # decode loop on the HIP path (sequential 9-row steps), then the batched pass over the same inputs
+    hip = bk.HipBackend(DEV)
+    trace = harness.decode(w, hip, keep_logits=True)
+    S = len(trace.steps)
+    logits = torch.stack([s.logits for s in trace.steps]).view(S, w.R, w.V)
+    tokens = torch.from_numpy(np.tile(trace.tokens, (S, 1))).to(DEV)
+    lens = torch.from_numpy(np.concatenate([s.length for s in trace.steps]).astype(np.int32)).to(DEV)
+    plens = torch.full((S,), w.L, dtype=torch.int32, device=DEV)
+    r = aasd.retrieve_drafts(tokens, lens, plens, w.n_min, w.n_max, w.k, w.C)
+    v = aasd.verify(logits, r["drafts"], r["draft_len"], r["strict"], alpha=w.alpha, beta=w.beta)
+    torch.cuda.synchronize()
+    r_np, v_np = bk.to_np(r), bk.to_np(v)
+    # batched == sequential, bit for bit
+    for name in ("drafts", "draft_len", "src_pos", "n_cand", "key_len", "strict"):
+        np.testing.assert_array_equal(r_np[name], np.concatenate([s.retrieved[name] for s in trace.steps]), err_msg=name)
+    for name in ("accept_len", "best_cand", "next_token"):
+        np.testing.assert_array_equal(v_np[name], np.concatenate([s.verified[name] for s in trace.steps]), err_msg=name)
+    # oracle on every decode step
+    ref_r = oracle.retrieve_drafts(np.tile(trace.tokens, (S, 1)), lens.cpu().numpy(), plens.cpu().numpy(),
+                                   w.n_min, w.n_max, w.k, w.C)
+    bk.compare_retrieve(r_np, ref_r)
+    ref_v = oracle.verify(synth.to_host_bits(logits), ref_r["drafts"], ref_r["draft_len"], ref_r["strict"],
+                          alpha=bk.f32(w.alpha), beta=bk.f32(w.beta))
+    bk.compare_verify(v_np, ref_v, tally)
+    print("llama3_single full", tally)
+
+
+@pytest.mark.parametrize("name,align_rows,seqs", [("long_context", 8192, 1), ("batched_serving", 8192, 32),
+                                                  ("stress_tree", 4096, 64)])
+def test_full_shapes_sampled(name, align_rows, seqs):
+    """Configs 3-5 in full per-launch shape (all prefill rows of the launch / the whole [B, R, V] verify
+    step), with the oracle on sampled rows and sequences."""
+    w = synth.WORKLOADS[name]
+    rng = np.random.default_rng(5)
+    tally = bk.Tally()
+    # alignment sampling: a launch of `align_rows` rows (>= 4096: the many-rows plan, as for the full prompt set)
+    g, copied = synth.token_stream(w, 0)
+    rows = slice(0, min(align_rows, w.L))
+    z = synth.prefill_logits(w, 0, g, copied, DEV, rows=rows)
+    nt = synth.next_tokens(w, g)[rows]
+    reps = max(1, align_rows // z.shape[0])
+    zz = z.repeat(reps, 1) if reps > 1 else z
+    ntt = np.tile(nt, reps)
+    got = bk.hip_align(zz, ntt, w.m, w.c, oracle.EXTRAS_SAMPLE, seed=3, row_id_base=0)
+    pick = _sample_rows(zz.shape[0], 96, rng)
+    for i in pick:  # one by one: each sampled row with its own row id
+        ref = bk.oracle_align(zz[i:i + 1], ntt[i:i + 1], w.m, w.c, oracle.EXTRAS_SAMPLE, seed=3, row_id_base=int(i))
+        one = {k: (v[i:i + 1] if v is not None else None) for k, v in got.items()}
+        bk.compare_align(one, ref, tally, oracle.EXTRAS_SAMPLE)
+    # one full verify step [B, R, V] on the state after two decode steps
+    hip = bk.HipBackend(DEV)
+    ws = synth.scaled(w, steps=3)
+    trace = harness.decode(ws, hip, keep_logits=True)
+    st = trace.steps[-1]
+    t = lambda a, dt: torch.as_tensor(np.ascontiguousarray(a), device=DEV).to(dt)
+    for peaked in (False, True):
+        logits = st.logits if not peaked else synth.verify_logits(
+            ws, 99, [synth.token_stream(ws, b)[0] for b in range(w.B)], [synth.token_stream(ws, b)[1] for b in range(w.B)],
+            st.length, st.retrieved["drafts"], st.retrieved["draft_len"], DEV, peaked=True)
+        out = bk.to_np(aasd.verify(logits, t(st.retrieved["drafts"], torch.int32), t(st.retrieved["draft_len"], torch.int32),
+                                   t(st.retrieved["strict"], torch.uint8), alpha=w.alpha, beta=w.beta))
+        torch.cuda.synchronize()
+        bsel = _sample_rows(w.B, 3, rng)
+        ref = oracle.verify(synth.to_host_bits(logits[torch.as_tensor(bsel, device=DEV)]), st.retrieved["drafts"][bsel],
+                            st.retrieved["draft_len"][bsel], st.retrieved["strict"][bsel], alpha=bk.f32(w.alpha),
+                            beta=bk.f32(w.beta))
+        bk.compare_verify({k: v[bsel] for k, v in out.items() if v is not None}, ref, tally)
+        # properties that hold at any size
+        assert ((out["accept_len"] >= 0) & (out["accept_len"] <= st.retrieved["draft_len"].max(axis=1))).all()
+        assert (out["row_pmax"] > 0).all() and (out["row_pmax"] <= 1.0 + 1e-6).all()
+        assert (out["row_entropy"] >= 0).all() and (out["row_entropy"] <= math.log(w.V) + 1e-3).all()
+        assert ((out["row_argmax"] >= 0) & (out["row_argmax"] < w.V)).all()
+    print(name, "full shapes", tally)
