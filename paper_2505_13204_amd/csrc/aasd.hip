@@ -165,11 +165,13 @@ int aasd_align_sample(const void* logits, int32_t dt, int64_t rows, int32_t V, i
     p.logits = logits; p.V = V; p.row_stride = row_stride; p.seq_stride = row_stride; p.rows_per_seq = 1;
     p.next_tok = next_tok; p.want_cand = m > 0; p.c = c;
     p.nseg = pl.nseg; p.seg_vecs = pl.seg_vecs; p.partials = partials; p.lists = lists;
-    // one chunk maximum per 16-byte vector of a segment, kept in LDS when it fits
+    // one chunk maximum per 16-byte vector of a segment, kept in LDS (lane-contiguous) when it fits
     size_t dyn = 0;
     if (m > 0 && next_tok) {
-        const size_t need = ((size_t)pl.seg_vecs + 1) * elt_size(dt);
-        if (need <= kMaxChunkMaxLds) { dyn = align16(need); p.cm_enabled = 1; }
+        const size_t per_lane = (size_t)(pl.seg_vecs / pl.block) * elt_size(dt);
+        size_t stride = (per_lane + 15) / 16 * 16;  // 16-byte slots; an odd number of them spreads lanes over the banks
+        if ((stride / 16) % 2 == 0) stride += 16;
+        if (stride * pl.block <= kMaxChunkMaxLds) { dyn = stride * pl.block; p.cm_enabled = 1; p.cm_stride = (int32_t)stride; }
     }
     hipStream_t s = (hipStream_t)stream;
     int rc;

@@ -54,6 +54,7 @@ struct SweepParams {
     int32_t want_cand;     // candidates are wanted (m > 0)
     int32_t c;
     int32_t cm_enabled;    // chunk maxima fit in LDS
+    int32_t cm_stride;     // bytes between the chunk-maximum rows of neighbouring lanes
     int32_t nseg;          // segments per row
     int32_t seg_vecs;      // 16-byte vectors per segment (a multiple of the block size)
     WavePartial* partials; // [rows][nseg * waves per block]
@@ -171,24 +172,42 @@ __device__ __forceinline__ SegShape seg_shape(const RowShape& r, int V, int seg,
     return s;
 }
 
+// Chunk maxima in LDS, lane-contiguous: entry j of a lane is the maximum of its j-th chunk (vector
+// j*BLOCK + tid of the segment), stored in the logits' own type.  The rows of neighbouring lanes are
+// cm_stride bytes apart, an odd number of 16-byte slots, so that 16-byte reads of eight neighbouring
+// lanes fall into distinct banks.  A lane only ever reads what it wrote itself: no barrier is needed.
 template <int DT>
-__device__ __forceinline__ void cm_store(unsigned char* cm, int vec, float cmax)
+__device__ __forceinline__ void cm_store(unsigned char* cm_lane, int j, float cmax)
 {
-    if constexpr (DT == AASD_BF16) ((uint16_t*)cm)[vec] = (uint16_t)(__float_as_uint(cmax) >> 16);
-    else ((float*)cm)[vec] = cmax;
+    if constexpr (DT == AASD_BF16) ((uint16_t*)cm_lane)[j] = (uint16_t)(__float_as_uint(cmax) >> 16);
+    else ((float*)cm_lane)[j] = cmax;
 }
-template <int DT>
-__device__ __forceinline__ float cm_load(const unsigned char* cm, int vec)
+// U consecutive entries starting at entry j0 (j0 a multiple of U): one wide LDS store.
+template <int DT, int U>
+__device__ __forceinline__ void cm_store_batch(unsigned char* cm_lane, int j0, const float (&cmax)[U])
 {
-    if constexpr (DT == AASD_BF16) return bits_to_float((uint32_t)((const uint16_t*)cm)[vec] << 16);
-    else return ((const float*)cm)[vec];
+    if constexpr (DT == AASD_BF16 && (U == 2 || U == 4)) {
+        uint32_t w[U / 2];
+#pragma unroll
+        for (int q = 0; q < U / 2; ++q)
+            w[q] = (__float_as_uint(cmax[2 * q + 1]) & 0xffff0000u) | (__float_as_uint(cmax[2 * q]) >> 16);
+        if constexpr (U == 4) *(uint2*)(cm_lane + j0 * 2) = make_uint2(w[0], w[1]);
+        else *(uint32_t*)(cm_lane + j0 * 2) = w[0];
+    } else if constexpr (DT == AASD_F32 && U == 4) {
+        *(float4*)(cm_lane + j0 * 4) = make_float4(cmax[0], cmax[1], cmax[2], cmax[3]);
+    } else if constexpr (DT == AASD_F32 && U == 2) {
+        *(float2*)(cm_lane + j0 * 4) = make_float2(cmax[0], cmax[1]);
+    } else {
+#pragma unroll
+        for (int u = 0; u < U; ++u) cm_store<DT>(cm_lane, j0 + u, cmax[u]);
+    }
 }
 
 // The single HBM pass of one lane over its share of the row: vectors tid, tid+BLOCK, ...
 // loaded U at a time with the next batch in flight while the current one is folded in.
 template <int DT, bool CLAMP, bool COUNT, int BLOCK, int U>
 __device__ __forceinline__ void sweep_lane(LaneAcc& a, const SegShape& rs, int tid, float zcmp,
-                                           bool store_cm, unsigned char* cm)
+                                           bool store_cm, unsigned char* cm_lane)
 {
     constexpr int EPV = Elt<DT>::kPerVec;
     lane_acc_init(a);
@@ -212,14 +231,15 @@ __device__ __forceinline__ void sweep_lane(LaneAcc& a, const SegShape& rs, int t
         for (int u = 0; u < U; ++u) buf[u] = *(const u32x4*)(b + (voff + (unsigned)u * (BLOCK * 16u)));
     };
     auto fold_batch = [&](const u32x4 (&buf)[U], int it) {
+        float cmax[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             float z[EPV];
             unpack<DT>(buf[u], z);
             const int vec = (it * U + u) * BLOCK + tid;
-            const float cmax = accumulate<EPV, CLAMP, COUNT, true>(a, z, rs.first_idx + vec * EPV, zcmp);
-            if (store_cm) cm_store<DT>(cm, vec, cmax);
+            cmax[u] = accumulate<EPV, CLAMP, COUNT, true>(a, z, rs.first_idx + vec * EPV, zcmp);
         }
+        if (store_cm) cm_store_batch<DT, U>(cm_lane, it * U, cmax);
     };
     u32x4 bufA[U], bufB[U];
     int it = 0;
@@ -245,7 +265,7 @@ __device__ __forceinline__ void sweep_lane(LaneAcc& a, const SegShape& rs, int t
                 float z[EPV];
                 unpack<DT>(rem[u], z);
                 const float cmax = accumulate<EPV, CLAMP, COUNT, false>(a, z, rs.first_idx + vec * EPV, zcmp);
-                if (store_cm) cm_store<DT>(cm, vec, cmax);
+                if (store_cm) cm_store<DT>(cm_lane, nsuper * U + u, cmax);
             }
         }
     }
@@ -336,7 +356,7 @@ struct SweepShared {
 // non-finite, which happens when the share holds -inf logits; the caller repeats with CLAMP.
 template <int DT, bool ALIGN, bool COUNT, bool CLAMP, int BLOCK, int U>
 __device__ __forceinline__ bool process_wave(const SweepParams& p, const SegShape& rs, bool has_next, float znext,
-                                             SweepShared<BLOCK / kWave>& sh, unsigned char* cm, const RowShape& row_s,
+                                             SweepShared<BLOCK / kWave>& sh, unsigned char* cm_lane, const RowShape& row_s,
                                              WavePartial* out, int32_t* out_list)
 {
     constexpr int EPV = Elt<DT>::kPerVec;
@@ -345,7 +365,7 @@ __device__ __forceinline__ bool process_wave(const SweepParams& p, const SegShap
     const float zcmp = has_next ? znext : INFINITY;
 
     LaneAcc a;
-    sweep_lane<DT, CLAMP, ALIGN && COUNT, BLOCK, U>(a, rs, tid, zcmp, want_cand && p.cm_enabled, cm);
+    sweep_lane<DT, CLAMP, ALIGN && COUNT, BLOCK, U>(a, rs, tid, zcmp, want_cand && p.cm_enabled, cm_lane);
 
     // ---- wave maximum, and a lower bound on the c-th largest logit of the wave's share ----
     float G = a.vmax;  // becomes the maximum of this lane's 4-lane group
@@ -403,18 +423,27 @@ __device__ __forceinline__ bool process_wave(const SweepParams& p, const SegShap
                 const float z = load_elt<DT>(rs.base, tid);
                 if (z > znext && z >= thr2) note(tid);
             }
-            for (int vec = tid; vec < rs.nvec; vec += BLOCK) {
-                float cmx;
-                if (p.cm_enabled) {
-                    cmx = cm_load<DT>(cm, vec);  // entries this lane wrote itself: LDS only, no barrier needed
-                } else {                          // vocabulary too large for LDS: look at the chunk again
+            if (p.cm_enabled) {
+                // this lane's chunk maxima, 16 bytes at a time (LDS only; entries past the lane's last chunk are ignored)
+                const int nown = tid < rs.nvec ? (rs.nvec - tid + BLOCK - 1) / BLOCK : 0;
+                for (int j0 = 0; j0 < nown; j0 += EPV) {
+                    float cmx[EPV];
+                    unpack<DT>(*(const u32x4*)(cm_lane + (size_t)j0 * Elt<DT>::kBytes), cmx);
+#pragma unroll
+                    for (int e = 0; e < EPV; ++e)
+                        if (j0 + e < nown && cmx[e] > znext && cmx[e] >= thr2)
+                            note(rs.first_idx + ((j0 + e) * BLOCK + tid) * EPV);
+                }
+            } else {
+                // vocabulary too large for LDS: look at every chunk again
+                for (int vec = tid; vec < rs.nvec; vec += BLOCK) {
                     float z[EPV];
                     unpack<DT>(rs.vbase[vec], z);
-                    cmx = z[0];
+                    float cmx = z[0];
 #pragma unroll
                     for (int e = 1; e < EPV; ++e) cmx = fmaxf(cmx, z[e]);
+                    if (cmx > znext && cmx >= thr2) note(rs.first_idx + vec * EPV);
                 }
-                if (cmx > znext && cmx >= thr2) note(rs.first_idx + vec * EPV);
             }
             if (tid < rs.tail_n) {
                 const float z = load_elt<DT>(rs.base, rs.tail0 + tid);
@@ -492,8 +521,9 @@ __global__ __launch_bounds__(BLOCK) void row_sweep_kernel(SweepParams p, int64_t
         if (nt >= 0) znext = load_elt<DT>(row_s.base, nt);
     }
     const bool has_next = ALIGN && nt >= 0;
-    if (!process_wave<DT, ALIGN, COUNT, false, BLOCK, U>(p, rs, has_next, znext, sh, cm, row_s, out, out_list))
-        process_wave<DT, ALIGN, COUNT, true, BLOCK, U>(p, rs, has_next, znext, sh, cm, row_s, out, out_list);
+    unsigned char* cm_lane = cm + (size_t)tid * (size_t)p.cm_stride;
+    if (!process_wave<DT, ALIGN, COUNT, false, BLOCK, U>(p, rs, has_next, znext, sh, cm_lane, row_s, out, out_list))
+        process_wave<DT, ALIGN, COUNT, true, BLOCK, U>(p, rs, has_next, znext, sh, cm_lane, row_s, out, out_list);
 }
 
 }  // namespace aasd
