@@ -4,8 +4,8 @@
 // A row is read from HBM exactly once with 16-byte loads.  A workgroup owns one row, or one of
 // several contiguous segments of a row when there are too few rows to fill the GPU.  Every
 // wave works on its own: it folds its share into a partial result (maximum, sum of
-// exponentials, entropy sum, position of the maximum, rank count, its best candidates) with
-// wave shuffles only and writes that partial to the workspace.  A second, small kernel merges
+// exponentials, entropy sum, position of the maximum, rank count, the chunks that may hold its
+// best candidates) with wave shuffles only and writes that partial to the workspace.  A second, small kernel merges
 // the partials of a row and does the per-row scalar work (see row_finish.hip.h), so the
 // streaming kernel has no barrier and no serial tail.
 // Per element the sweep does: unpack, one FMA into the log2 domain, one hardware exp2, one add
