@@ -46,7 +46,7 @@ def lib():
         _lib = ctypes.CDLL(_LIB)
         _lib.orc_philox4x32_10.restype = None
         for name in ("orc_widen_row", "orc_row_softmax", "orc_row_stats", "orc_align_sample",
-                     "orc_retrieve_drafts", "orc_verify"):
+                     "orc_retrieve_drafts", "orc_verify", "orc_build_tree", "orc_verify_tree"):
             getattr(_lib, name).restype = c_int
     return _lib
 
@@ -177,4 +177,57 @@ def verify(logits: np.ndarray, drafts, draft_len, strict=None, alpha: float = 0.
         _ptr(out["near_count"], c_uint32))
     if rc != 0:
         raise ValueError(f"orc_verify rc={rc}")
+    return out
+
+
+def build_tree(drafts, draft_len, strict=None, draft_extras=None, root_tok=None, max_nodes: int = 64):
+    """drafts [B,C,k], draft_len [B,C], strict [B,C,k] or None, draft_extras [B,C,k,m] or None."""
+    drafts = np.ascontiguousarray(drafts, dtype=np.int32)
+    draft_len = np.ascontiguousarray(draft_len, dtype=np.int32)
+    B, C, k = drafts.shape
+    st = None if strict is None else np.ascontiguousarray(strict, dtype=np.uint8)
+    dx = None if draft_extras is None else np.ascontiguousarray(draft_extras, dtype=np.int32)
+    m_x = 0 if dx is None else dx.shape[3]
+    rt = None if root_tok is None else np.ascontiguousarray(root_tok, dtype=np.int32)
+    N, W = max_nodes, (max_nodes + 31) // 32
+    out = dict(
+        node_token=np.empty((B, N), np.int32), node_parent=np.empty((B, N), np.int32),
+        node_depth=np.empty((B, N), np.int32), node_strict=np.empty((B, N), np.uint8),
+        n_nodes=np.empty(B, np.int32), mask=np.empty((B, N, W), np.uint32), cand_node=np.empty((B, C, k), np.int32))
+    rc = lib().orc_build_tree(
+        _ptr(drafts, c_int32), _ptr(draft_len, c_int32), _ptr(st, c_uint8), _ptr(dx, c_int32), c_int32(m_x),
+        _ptr(rt, c_int32), c_int32(B), c_int32(C), c_int32(k), c_int32(N),
+        _ptr(out["node_token"], c_int32), _ptr(out["node_parent"], c_int32), _ptr(out["node_depth"], c_int32),
+        _ptr(out["node_strict"], c_uint8), _ptr(out["n_nodes"], c_int32), _ptr(out["mask"], c_uint32),
+        _ptr(out["cand_node"], c_int32))
+    if rc != 0:
+        raise ValueError(f"orc_build_tree rc={rc}")
+    return out
+
+
+def verify_tree(logits: np.ndarray, node_token, node_parent, node_strict, n_nodes, alpha: float = 0.1,
+                beta: float = 0.1, flags: int = 0, V: int | None = None):
+    """logits [B, N, row_stride]; node arrays [B, N]."""
+    assert logits.ndim == 3 and logits.flags["C_CONTIGUOUS"]
+    B, N, row_stride = logits.shape
+    V = row_stride if V is None else V
+    nt = np.ascontiguousarray(node_token, dtype=np.int32)
+    npar = np.ascontiguousarray(node_parent, dtype=np.int32)
+    ns = None if node_strict is None else np.ascontiguousarray(node_strict, dtype=np.uint8)
+    nn = np.ascontiguousarray(n_nodes, dtype=np.int32)
+    out = dict(
+        accept_len=np.empty(B, np.int32), best_node=np.empty(B, np.int32), accept_path=np.empty((B, 16), np.int32),
+        next_token=np.empty(B, np.int32), row_entropy=np.empty((B, N), np.float64), row_pmax=np.empty((B, N), np.float64),
+        row_argmax=np.empty((B, N), np.int32), node_p=np.empty((B, N), np.float64), node_delta=np.empty((B, N), np.float64),
+        node_margin=np.empty((B, N), np.float64), near_count=np.empty(B, np.uint32))
+    rc = lib().orc_verify_tree(
+        c_void_p(logits.ctypes.data), _dtype_of(logits), c_int32(B), c_int32(N), c_int32(V), c_int64(row_stride),
+        c_int64(N * row_stride), _ptr(nt, c_int32), _ptr(npar, c_int32), _ptr(ns, c_uint8), _ptr(nn, c_int32),
+        c_double(alpha), c_double(beta), c_uint32(flags),
+        _ptr(out["accept_len"], c_int32), _ptr(out["best_node"], c_int32), _ptr(out["accept_path"], c_int32),
+        _ptr(out["next_token"], c_int32), _ptr(out["row_entropy"], c_double), _ptr(out["row_pmax"], c_double),
+        _ptr(out["row_argmax"], c_int32), _ptr(out["node_p"], c_double), _ptr(out["node_delta"], c_double),
+        _ptr(out["node_margin"], c_double), _ptr(out["near_count"], c_uint32))
+    if rc != 0:
+        raise ValueError(f"orc_verify_tree rc={rc}")
     return out

@@ -410,3 +410,182 @@ int orc_verify(const void *logits, int dtype, int32_t B, int32_t C, int32_t k, i
     free(z); free(m); free(S); free(H); free(am);
     return 0;
 }
+
+/* ------------------------------------------------------------------------- */
+/* draft tree and tree attention mask                                         */
+/* ------------------------------------------------------------------------- */
+int orc_build_tree(const int32_t *drafts, const int32_t *draft_len, const uint8_t *strict,
+                   const int32_t *draft_extras, int32_t m_x, const int32_t *root_tok, int32_t B,
+                   int32_t C, int32_t k, int32_t max_nodes, int32_t *node_token,
+                   int32_t *node_parent, int32_t *node_depth, uint8_t *node_strict,
+                   int32_t *n_nodes, uint32_t *mask, int32_t *cand_node)
+{
+    if (!drafts || !draft_len || B < 0) return -1;
+    if (k < 1 || k > 16 || C < 1 || C > 32 || m_x < 0 || m_x > 4) return -1;
+    if (max_nodes < 1 || max_nodes > 256) return -1;
+    const int32_t N = max_nodes, W = (N + 31) / 32;
+    int32_t *tok = (int32_t *)malloc(sizeof(int32_t) * (size_t)N);
+    int32_t *par = (int32_t *)malloc(sizeof(int32_t) * (size_t)N);
+    int32_t *dep = (int32_t *)malloc(sizeof(int32_t) * (size_t)N);
+    uint8_t *str = (uint8_t *)malloc((size_t)N);
+    if (!tok || !par || !dep || !str) { free(tok); free(par); free(dep); free(str); return -2; }
+
+    for (int32_t b = 0; b < B; ++b) {
+        int32_t n = 1;
+        tok[0] = root_tok ? root_tok[b] : -1; par[0] = -1; dep[0] = 0; str[0] = 0;
+        int32_t cur[32];                       /* node at the end of each candidate's path so far */
+        for (int32_t c = 0; c < C; ++c) cur[c] = 0;
+        if (cand_node)
+            for (int32_t i = 0; i < C * k; ++i) cand_node[(size_t)b * C * k + i] = -1;
+
+        for (int32_t j = 1; j <= k; ++j) {                 /* layer by layer */
+            int32_t next_cur[32];
+            for (int32_t c = 0; c < C; ++c) next_cur[c] = -1;
+            for (int32_t c = 0; c < C; ++c) {
+                size_t bc = (size_t)b * C + c;
+                int32_t dl = draft_len[bc] < 0 ? 0 : (draft_len[bc] > k ? k : draft_len[bc]);
+                if (cur[c] < 0 || j > dl) continue;
+                for (int32_t slot = 0; slot <= m_x; ++slot) {
+                    int32_t t;
+                    int is_strict;
+                    if (slot == 0) {
+                        t = drafts[bc * k + (j - 1)];
+                        is_strict = strict ? strict[bc * k + (j - 1)] != 0 : 0;
+                    } else {
+                        if (!draft_extras) break;
+                        t = draft_extras[(bc * k + (j - 1)) * m_x + (slot - 1)];
+                        is_strict = 0;             /* extras are verified conditionally */
+                    }
+                    if (t < 0) { if (slot == 0) break; else continue; }  /* no token: the path ends here */
+                    int32_t found = -1;
+                    for (int32_t i = 1; i < n; ++i)
+                        if (par[i] == cur[c] && tok[i] == t) { found = i; break; }
+                    if (found < 0 && n < N) {
+                        found = n++;
+                        tok[found] = t; par[found] = cur[c]; dep[found] = j; str[found] = (uint8_t)is_strict;
+                    } else if (found >= 0 && !is_strict) {
+                        str[found] = 0;            /* one conditional source is enough */
+                    }
+                    if (slot == 0) {
+                        next_cur[c] = found;       /* -1 if the node budget is exhausted */
+                        if (cand_node) cand_node[bc * k + (j - 1)] = found;
+                    }
+                }
+            }
+            for (int32_t c = 0; c < C; ++c) cur[c] = next_cur[c];
+        }
+
+        if (n_nodes) n_nodes[b] = n;
+        for (int32_t i = 0; i < N; ++i) {
+            size_t bi = (size_t)b * N + i;
+            int used = i < n;
+            if (node_token) node_token[bi] = used ? tok[i] : -1;
+            if (node_parent) node_parent[bi] = used ? par[i] : -1;
+            if (node_depth) node_depth[bi] = used ? dep[i] : 0;
+            if (node_strict) node_strict[bi] = used ? str[i] : 0;
+            if (mask) {
+                for (int32_t w = 0; w < W; ++w) mask[bi * W + w] = 0;
+                if (used)
+                    for (int32_t a = i; a >= 0; a = par[a]) mask[bi * W + a / 32] |= 1u << (a % 32);
+            }
+        }
+    }
+    free(tok); free(par); free(dep); free(str);
+    return 0;
+}
+
+int orc_verify_tree(const void *logits, int dtype, int32_t B, int32_t N, int32_t V,
+                    int64_t row_stride, int64_t seq_stride, const int32_t *node_token,
+                    const int32_t *node_parent, const uint8_t *node_strict,
+                    const int32_t *n_nodes, double alpha, double beta, uint32_t flags,
+                    int32_t *accept_len, int32_t *best_node, int32_t *accept_path,
+                    int32_t *next_token, double *row_entropy, double *row_pmax,
+                    int32_t *row_argmax, double *node_p, double *node_delta, double *node_margin,
+                    uint32_t *near_count)
+{
+    if (!logits || !node_token || !node_parent || !n_nodes || B < 0 || V <= 0) return -1;
+    if (dtype != ORC_F32 && dtype != ORC_BF16) return -1;
+    if (N < 1 || N > 256 || row_stride < V || seq_stride < (int64_t)N * row_stride) return -1;
+
+    double *z = (double *)malloc(sizeof(double) * 2 * (size_t)V);
+    double *m = (double *)malloc(sizeof(double) * (size_t)N);
+    double *S = (double *)malloc(sizeof(double) * (size_t)N);
+    double *H = (double *)malloc(sizeof(double) * (size_t)N);
+    int32_t *am = (int32_t *)malloc(sizeof(int32_t) * (size_t)N);
+    int *ok = (int *)malloc(sizeof(int) * (size_t)N);      /* node and all its ancestors pass */
+    int32_t *depth = (int32_t *)malloc(sizeof(int32_t) * (size_t)N);
+    if (!z || !m || !S || !H || !am || !ok || !depth) {
+        free(z); free(m); free(S); free(H); free(am); free(ok); free(depth);
+        return -2;
+    }
+    for (int32_t b = 0; b < B; ++b) {
+        const char *seq = (const char *)logits + (size_t)b * (size_t)seq_stride * elt_bytes(dtype);
+        int32_t n = n_nodes[b] < 1 ? 1 : (n_nodes[b] > N ? N : n_nodes[b]);
+        for (int32_t i = 0; i < N; ++i) {
+            size_t bi = (size_t)b * N + i;
+            if (i < n) {
+                const char *row = seq + (size_t)i * (size_t)row_stride * elt_bytes(dtype);
+                orc_widen_row(row, dtype, V, z);
+                stats_of(z, V, z + V, &m[i], &S[i], &H[i], &am[i]);
+            }
+            if (row_entropy) row_entropy[bi] = i < n ? H[i] : 0.0;
+            if (row_pmax) row_pmax[bi] = i < n ? 1.0 / S[i] : 0.0;
+            if (row_argmax) row_argmax[bi] = i < n ? am[i] : -1;
+        }
+        ok[0] = 1; depth[0] = 0;
+        int32_t best = 0;
+        uint32_t near = 0;
+        for (int32_t i = 1; i < N; ++i) {
+            size_t bi = (size_t)b * N + i;
+            double p = 0.0, delta = 0.0, margin = -1.0;
+            if (i < n) {
+                int32_t par = node_parent[bi];
+                int valid_par = par >= 0 && par < i;       /* parents precede their children */
+                int32_t t = node_token[bi];
+                int valid = valid_par && t >= 0 && t < V;
+                int pass = 0;
+                if (valid_par) {
+                    const char *row = seq + (size_t)par * (size_t)row_stride * elt_bytes(dtype);
+                    double zt = valid ? widen_one(row, dtype, t) : 0.0;
+                    p = valid ? exp(zt - m[par]) / S[par] : 0.0;
+                    double Delta = 1.0 / S[par];
+                    double thr = alpha * H[par] + beta;
+                    int is_strict = node_strict ? node_strict[bi] != 0 : 0;
+                    if (flags & ORC_VERIFY_NO_CLAMP) {
+                        delta = thr;
+                        pass = valid && p >= delta;
+                    } else {
+                        delta = is_strict ? Delta : (thr < Delta ? thr : Delta);
+                        pass = valid && (p >= delta || zt == m[par]);
+                    }
+                    depth[i] = depth[par] + 1;
+                    if (ok[par]) {                         /* the node is reached: it is evaluated */
+                        margin = fabs(p - delta);
+                        if (margin < 1e-6) ++near;
+                    }
+                    ok[i] = ok[par] && pass;
+                } else {
+                    ok[i] = 0; depth[i] = 0;
+                }
+                if (ok[i] && depth[i] > depth[best]) best = i;   /* deepest; lowest index on ties */
+            }
+            if (node_p) node_p[bi] = p;
+            if (node_delta) node_delta[bi] = delta;
+            if (node_margin) node_margin[bi] = margin;
+        }
+        if (node_p) node_p[(size_t)b * N] = 0.0;
+        if (node_delta) node_delta[(size_t)b * N] = 0.0;
+        if (node_margin) node_margin[(size_t)b * N] = -1.0;
+        if (accept_len) accept_len[b] = depth[best];
+        if (best_node) best_node[b] = best;
+        if (next_token) next_token[b] = am[best];
+        if (near_count) near_count[b] = near;
+        if (accept_path) {
+            for (int32_t d = 0; d < 16; ++d) accept_path[(size_t)b * 16 + d] = -1;
+            for (int32_t a = best; a > 0; a = node_parent[(size_t)b * N + a])
+                if (depth[a] >= 1 && depth[a] <= 16) accept_path[(size_t)b * 16 + depth[a] - 1] = a;
+        }
+    }
+    free(z); free(m); free(S); free(H); free(am); free(ok); free(depth);
+    return 0;
+}

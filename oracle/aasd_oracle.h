@@ -100,6 +100,41 @@ int orc_verify(const void *logits, int dtype, int32_t B, int32_t C, int32_t k, i
                double *row_entropy, double *row_pmax, int32_t *row_argmax, double *tok_p,
                double *tok_delta, double *tok_margin, uint32_t *near_count);
 
+/* Draft tree (Sec. 3.2, Eq. 2): the candidate n-grams and the alignment extras of their positions
+ * merged into one tree under the last committed token, plus the tree attention mask.
+ *   Node 0 is the root.  Layer j (depth j) is built from the j-th tokens of the candidates in the
+ *   order (candidate, slot), slot 0 = the retrieved token, slots 1..m_x = its extras; a (parent,
+ *   token) pair that already exists is reused, otherwise it becomes the next node.  Extras are
+ *   siblings of the retrieved token and have no continuation of their own.  Nodes beyond
+ *   max_nodes are dropped (and with them whatever would hang below).  A node is strict iff every
+ *   occurrence that maps to it is a strict retrieved token.
+ * Outputs (any may be NULL): node_token/node_parent/node_depth [B,max_nodes] (-1 / -1 / 0 for
+ *   unused slots; root: token root_tok[b] or -1, parent -1), node_strict [B,max_nodes],
+ *   n_nodes[B], mask[B,max_nodes,W] with W = (max_nodes+31)/32: bit a of row i is set iff node a
+ *   is node i or one of its ancestors; cand_node[B,C,k] = node of each candidate token (-1 if
+ *   it has none).                                                                              */
+int orc_build_tree(const int32_t *drafts, const int32_t *draft_len, const uint8_t *strict,
+                   const int32_t *draft_extras, int32_t m_x, const int32_t *root_tok, int32_t B,
+                   int32_t C, int32_t k, int32_t max_nodes, int32_t *node_token,
+                   int32_t *node_parent, int32_t *node_depth, uint8_t *node_strict,
+                   int32_t *n_nodes, uint32_t *mask, int32_t *cand_node);
+
+/* Conditional verification over a draft tree: logits[B, N, V], row i = distribution after node i.
+ * Node i >= 1 is verified by the row of its parent exactly as in orc_verify; a node is accepted iff
+ * it and all its ancestors pass.  The deepest accepted node wins (lowest index on ties).
+ * Outputs (any may be NULL): accept_len[B] (its depth), best_node[B], accept_path[B,16] (nodes from
+ * depth 1 to the best node, -1 padded), next_token[B] (greedy pick of the best node's row),
+ * row_entropy/row_pmax/row_argmax [B,N] (rows >= n_nodes: 0/0/-1), node_p/node_delta [B,N],
+ * node_margin[B,N] = |p - delta| for evaluated nodes (parent accepted) else -1, near_count[B]. */
+int orc_verify_tree(const void *logits, int dtype, int32_t B, int32_t N, int32_t V,
+                    int64_t row_stride, int64_t seq_stride, const int32_t *node_token,
+                    const int32_t *node_parent, const uint8_t *node_strict,
+                    const int32_t *n_nodes, double alpha, double beta, uint32_t flags,
+                    int32_t *accept_len, int32_t *best_node, int32_t *accept_path,
+                    int32_t *next_token, double *row_entropy, double *row_pmax,
+                    int32_t *row_argmax, double *node_p, double *node_delta, double *node_margin,
+                    uint32_t *near_count);
+
 #ifdef __cplusplus
 }
 #endif
