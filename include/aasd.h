@@ -54,6 +54,7 @@ typedef enum {
 #define AASD_MAX_KEY 8         /* n_max */
 #define AASD_MAX_DRAFT 16      /* k */
 #define AASD_MAX_CANDIDATES 32 /* C */
+#define AASD_MAX_TREE_NODES 256 /* nodes of a draft tree, root included */
 
 const char *aasd_version(void);
 const char *aasd_last_error(void);
@@ -187,6 +188,66 @@ int aasd_verify(const void *logits, int32_t dt, int32_t B, int32_t C, int32_t k,
                 float *row_entropy, float *row_pmax, int32_t *row_argmax, float *tok_p,
                 float *tok_delta, uint32_t *near_count, void *workspace, size_t workspace_bytes,
                 void *stream);
+
+/*
+ * Draft tree and tree attention mask (Sec. 3.2, Eq. 2): the retrieved candidates and the
+ * alignment extras of their positions are merged into one tree under the last committed token,
+ * so that one forward pass of the target model can verify all of them.
+ *
+ * For every sequence: node 0 is the root (the last committed token, root_tok[b]).  Layer j of the
+ * tree is built from the j-th tokens of the candidates, in the order (candidate, slot) with slot 0
+ * the retrieved token and slots 1..m its extras from draft_extras: a (parent, token) pair that
+ * already exists is reused, otherwise it becomes the next node, so candidates that share a prefix
+ * share nodes.  Extras are siblings of the retrieved token and have no continuation of their own.
+ * Nodes are numbered in creation order (parents before children); nodes beyond max_nodes are dropped
+ * together with what would hang below them.  A token id < 0 inside draft_len ends its candidate.
+ * A node is strict iff every occurrence that maps to it is a retrieved token flagged strict.
+ *
+ * DEVICE in : drafts[B,C,k] i32, draft_len[B,C] i32, strict[B,C,k] u8 (NULL = none strict),
+ *             draft_extras[B,C,k,m] i32 (NULL = no extras), root_tok[B] i32 (NULL = -1)
+ * DEVICE out: node_token, node_parent, node_depth [B,max_nodes] i32 (unused slots -1, -1, 0; the
+ *             root has parent -1), node_strict[B,max_nodes] u8, n_nodes[B] i32 (all required);
+ *             mask[B, max_nodes, W] u32 with W = (max_nodes+31)/32: bit a of row i is set iff node a
+ *             is node i or an ancestor of it (NULL = not wanted);
+ *             cand_node[B,C,k] i32: the node of every candidate token, -1 if none (NULL = not wanted)
+ * Parameters: 1 <= k <= 16, 1 <= C <= 32, 0 <= m <= 4, 1 <= max_nodes <= 256, B >= 0.
+ */
+int aasd_build_tree(const int32_t *drafts, const int32_t *draft_len, const uint8_t *strict,
+                    const int32_t *draft_extras, int32_t m, const int32_t *root_tok, int32_t B,
+                    int32_t C, int32_t k, int32_t max_nodes, int32_t *node_token,
+                    int32_t *node_parent, int32_t *node_depth, uint8_t *node_strict,
+                    int32_t *n_nodes, uint32_t *mask, int32_t *cand_node, void *stream);
+
+/*
+ * Conditional verification over a draft tree (Sec. 3.3, Eq. 4-6, applied to the nodes of Eq. 2).
+ * logits[B, N, V]: row i is the distribution after node i (element (b, i, v) at
+ * b*seq_stride + i*row_stride + v); rows at or beyond n_nodes[b] are not read.  Node i >= 1 with
+ * token t is verified by the row of its parent exactly as in aasd_verify (p, Delta, delta, pass,
+ * strict nodes, AASD_VERIFY_NO_CLAMP).  A node is accepted iff it and all its ancestors pass.
+ * The deepest accepted node wins (lowest node index on ties): accept_len[b] is its depth,
+ * best_node[b] its index, accept_path[b, 0..15] the nodes from depth 1 down to it (-1 padded),
+ * next_token[b] the greedy pick of its row (of the root's row if nothing was accepted).
+ * Parents must precede their children (node_parent[i] < i); a node that breaks this is rejected.
+ *
+ * DEVICE in : logits, node_token[B,N], node_parent[B,N] i32, node_strict[B,N] u8 (NULL = none),
+ *             n_nodes[B] i32 (clamped to [1, N])
+ * DEVICE out: accept_len[B], best_node[B], next_token[B] i32 (required); accept_path[B,16] i32;
+ *             row_entropy, row_pmax [B,N] f32 and row_argmax[B,N] i32 (0, 0, -1 for unused rows);
+ *             node_p, node_delta [B,N] f32; near_count[B] u32 = evaluated nodes (all ancestors
+ *             accepted) with |p - delta| < 1e-6 (each NULL = not wanted)
+ * workspace : DEVICE scratch of at least aasd_verify_tree_workspace_bytes(B, N, V, dt) bytes, 16-byte
+ *             aligned; needs no initialisation.
+ * Parameters: 1 <= N <= 256, V >= 1, row_stride >= V, seq_stride >= N*row_stride, B >= 0.
+ */
+size_t aasd_verify_tree_workspace_bytes(int32_t B, int32_t N, int32_t V, int32_t dt);
+int aasd_verify_tree(const void *logits, int32_t dt, int32_t B, int32_t N, int32_t V,
+                     int64_t row_stride, int64_t seq_stride, const int32_t *node_token,
+                     const int32_t *node_parent, const uint8_t *node_strict,
+                     const int32_t *n_nodes, float alpha, float beta, uint32_t flags,
+                     int32_t *accept_len, int32_t *best_node, int32_t *accept_path,
+                     int32_t *next_token, float *row_entropy, float *row_pmax,
+                     int32_t *row_argmax, float *node_p, float *node_delta,
+                     uint32_t *near_count, void *workspace, size_t workspace_bytes, void *stream);
 
 #ifdef __cplusplus
 }

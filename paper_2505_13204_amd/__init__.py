@@ -18,6 +18,7 @@ EXTRAS_TOP, EXTRAS_SAMPLE = 0, 1
 VERIFY_NO_CLAMP = 1
 
 MAX_EXTRAS, MAX_CANDSET, MAX_KEY, MAX_DRAFT, MAX_CANDIDATES = 4, 8, 8, 16, 32
+MAX_TREE_NODES = 256
 HASH_BASE = 0x9E3779B1  # multiplier of the retrieval kernel's window hash (mod 2^32)
 
 
@@ -203,6 +204,105 @@ def verify(logits: torch.Tensor, drafts: torch.Tensor, draft_len: torch.Tensor, 
         drafts.data_ptr(), draft_len.data_ptr(), _ptr(strict), float(alpha), float(beta), flags,
         o["accept_len"].data_ptr(), o["best_cand"].data_ptr(), o["next_token"].data_ptr(),
         _ptr(o["row_entropy"]), _ptr(o["row_pmax"]), _ptr(o["row_argmax"]), _ptr(o["tok_p"]), _ptr(o["tok_delta"]),
+        _ptr(o["near_count"]), workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream(dev))
+    _check(rc)
+    o["workspace"] = workspace
+    return o
+
+
+def build_tree(drafts: torch.Tensor, draft_len: torch.Tensor, strict: Optional[torch.Tensor] = None,
+               draft_extras: Optional[torch.Tensor] = None, root_tok: Optional[torch.Tensor] = None,
+               max_nodes: int = 64, want_mask: bool = True, want_cand_node: bool = True, out: Optional[dict] = None):
+    """aasd_build_tree over drafts [B,C,k], draft_len [B,C], strict [B,C,k] u8, draft_extras [B,C,k,m].
+
+    Returns a dict of device tensors: node_token, node_parent, node_depth [B,max_nodes] i32, node_strict u8,
+    n_nodes [B], mask [B,max_nodes,W] (int32 storage of the u32 words), cand_node [B,C,k]."""
+    _dev_check(drafts, draft_len, strict, draft_extras, root_tok)
+    assert drafts.dtype == torch.int32 and drafts.is_contiguous() and drafts.dim() == 3
+    assert draft_len.dtype == torch.int32 and draft_len.is_contiguous()
+    B, C, k = drafts.shape
+    m = 0
+    if draft_extras is not None:
+        assert draft_extras.dtype == torch.int32 and draft_extras.is_contiguous() and draft_extras.shape[:3] == (B, C, k)
+        m = draft_extras.shape[3]
+    if strict is not None:
+        assert strict.dtype == torch.uint8 and strict.is_contiguous() and strict.shape == (B, C, k)
+    if root_tok is not None:
+        assert root_tok.dtype == torch.int32 and root_tok.is_contiguous() and root_tok.shape == (B,)
+    dev = drafts.device
+    o = dict(out or {})
+    W = (max_nodes + 31) // 32
+    def need(name, shape, dtype, wanted=True):
+        if not wanted:
+            o[name] = None
+        elif o.get(name) is None:
+            o[name] = torch.empty(shape, dtype=dtype, device=dev)
+    need("node_token", (B, max_nodes), torch.int32)
+    need("node_parent", (B, max_nodes), torch.int32)
+    need("node_depth", (B, max_nodes), torch.int32)
+    need("node_strict", (B, max_nodes), torch.uint8)
+    need("n_nodes", (B,), torch.int32)
+    need("mask", (B, max_nodes, W), torch.int32, want_mask)
+    need("cand_node", (B, C, k), torch.int32, want_cand_node)
+    rc = _lib.load().aasd_build_tree(
+        drafts.data_ptr(), draft_len.data_ptr(), _ptr(strict), _ptr(draft_extras), m, _ptr(root_tok), B, C, k, max_nodes,
+        o["node_token"].data_ptr(), o["node_parent"].data_ptr(), o["node_depth"].data_ptr(), o["node_strict"].data_ptr(),
+        o["n_nodes"].data_ptr(), _ptr(o["mask"]), _ptr(o["cand_node"]), _stream(dev))
+    _check(rc)
+    return o
+
+
+def verify_tree_workspace_bytes(B: int, N: int, V: int, dt: int) -> int:
+    return int(_lib.load().aasd_verify_tree_workspace_bytes(B, N, V, dt))
+
+
+def verify_tree(logits: torch.Tensor, node_token: torch.Tensor, node_parent: torch.Tensor, n_nodes: torch.Tensor,
+                node_strict: Optional[torch.Tensor] = None, alpha: float = 0.1, beta: float = 0.1, flags: int = 0,
+                V: Optional[int] = None, want_rows: bool = True, want_nodes: bool = True, want_near: bool = True,
+                workspace: Optional[torch.Tensor] = None, out: Optional[dict] = None):
+    """aasd_verify_tree over logits[B, N, row_stride] and a tree of up to N nodes per sequence.
+
+    Returns a dict of device tensors: accept_len, best_node, next_token [B]; accept_path [B,16]; row_entropy,
+    row_pmax, row_argmax [B,N]; node_p, node_delta [B,N]; near_count [B] (the optional ones may be None)."""
+    _dev_check(logits, node_token, node_parent, n_nodes, node_strict, workspace)
+    assert logits.dim() == 3 and logits.stride(2) == 1
+    B, N = logits.shape[0], logits.shape[1]
+    for t in (node_token, node_parent):
+        assert t.dtype == torch.int32 and t.is_contiguous() and t.shape == (B, N)
+    assert n_nodes.dtype == torch.int32 and n_nodes.is_contiguous() and n_nodes.shape == (B,)
+    if node_strict is not None:
+        assert node_strict.dtype == torch.uint8 and node_strict.is_contiguous() and node_strict.shape == (B, N)
+    row_stride = logits.stride(1)
+    seq_stride = logits.stride(0) if B > 1 else N * row_stride
+    V = logits.shape[2] if V is None else V
+    dev = logits.device
+    o = dict(out or {})
+    def need(name, shape, dtype, wanted=True):
+        if not wanted:
+            o[name] = None
+        elif o.get(name) is None:
+            o[name] = torch.empty(shape, dtype=dtype, device=dev)
+    need("accept_len", (B,), torch.int32)
+    need("best_node", (B,), torch.int32)
+    need("accept_path", (B, MAX_DRAFT), torch.int32)
+    need("next_token", (B,), torch.int32)
+    need("row_entropy", (B, N), torch.float32, want_rows)
+    need("row_pmax", (B, N), torch.float32, want_rows)
+    need("row_argmax", (B, N), torch.int32, want_rows)
+    need("node_p", (B, N), torch.float32, want_nodes)
+    need("node_delta", (B, N), torch.float32, want_nodes)
+    need("near_count", (B,), torch.int32, want_near)
+    ws_bytes = verify_tree_workspace_bytes(B, N, V, _dtype_code(logits))
+    if workspace is None:
+        workspace = o.get("workspace")
+    if workspace is None or workspace.numel() * workspace.element_size() < ws_bytes:
+        workspace = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
+    rc = _lib.load().aasd_verify_tree(
+        logits.data_ptr(), _dtype_code(logits), B, N, V, row_stride, seq_stride,
+        node_token.data_ptr(), node_parent.data_ptr(), _ptr(node_strict), n_nodes.data_ptr(),
+        float(alpha), float(beta), flags,
+        o["accept_len"].data_ptr(), o["best_node"].data_ptr(), o["accept_path"].data_ptr(), o["next_token"].data_ptr(),
+        _ptr(o["row_entropy"]), _ptr(o["row_pmax"]), _ptr(o["row_argmax"]), _ptr(o["node_p"]), _ptr(o["node_delta"]),
         _ptr(o["near_count"]), workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream(dev))
     _check(rc)
     o["workspace"] = workspace

@@ -12,6 +12,7 @@
 #include "retrieve.hip.h"
 #include "row_finish.hip.h"
 #include "row_sweep.hip.h"
+#include "tree.hip.h"
 #include "verify_tail.hip.h"
 
 namespace {
@@ -314,6 +315,96 @@ int aasd_verify(const void* logits, int32_t dt, int32_t B, int32_t C, int32_t k,
         hipLaunchKernelGGL(aasd::verify_tail_kernel<AASD_F32>, dim3((unsigned)B), dim3(aasd::kTailBlock), 0, s, tp);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(AASD_ERR_LAUNCH, "verify tail launch failed: %s", hipGetErrorString(e));
+    return AASD_OK;
+}
+
+int aasd_build_tree(const int32_t* drafts, const int32_t* draft_len, const uint8_t* strict,
+                    const int32_t* draft_extras, int32_t m, const int32_t* root_tok, int32_t B,
+                    int32_t C, int32_t k, int32_t max_nodes, int32_t* node_token,
+                    int32_t* node_parent, int32_t* node_depth, uint8_t* node_strict,
+                    int32_t* n_nodes, uint32_t* mask, int32_t* cand_node, void* stream)
+{
+    if (B < 0) return fail(AASD_ERR_INVALID_ARG, "build_tree: B = %d < 0", B);
+    if (k < 1 || k > AASD_MAX_DRAFT) return fail(AASD_ERR_INVALID_ARG, "build_tree: k = %d outside [1,%d]", k, AASD_MAX_DRAFT);
+    if (C < 1 || C > AASD_MAX_CANDIDATES) return fail(AASD_ERR_INVALID_ARG, "build_tree: C = %d outside [1,%d]", C, AASD_MAX_CANDIDATES);
+    if (m < 0 || m > AASD_MAX_EXTRAS) return fail(AASD_ERR_INVALID_ARG, "build_tree: m = %d outside [0,%d]", m, AASD_MAX_EXTRAS);
+    if (draft_extras && m < 1) return fail(AASD_ERR_INVALID_ARG, "build_tree: draft_extras given with m = %d", m);
+    if (max_nodes < 1 || max_nodes > AASD_MAX_TREE_NODES)
+        return fail(AASD_ERR_INVALID_ARG, "build_tree: max_nodes = %d outside [1,%d]", max_nodes, AASD_MAX_TREE_NODES);
+    if (B == 0) return AASD_OK;
+    if (!drafts || !draft_len || !node_token || !node_parent || !node_depth || !node_strict || !n_nodes)
+        return fail(AASD_ERR_INVALID_ARG, "build_tree: null required pointer");
+    aasd::BuildTreeParams p{};
+    p.drafts = drafts; p.draft_len = draft_len; p.strict = strict; p.draft_extras = draft_extras; p.m_x = m;
+    p.root_tok = root_tok; p.B = B; p.C = C; p.k = k; p.max_nodes = max_nodes;
+    p.node_token = node_token; p.node_parent = node_parent; p.node_depth = node_depth; p.node_strict = node_strict;
+    p.n_nodes = n_nodes; p.mask = mask; p.cand_node = cand_node;
+    hipLaunchKernelGGL(aasd::build_tree_kernel, dim3((unsigned)B), dim3(aasd::kTreeBlock), 0, (hipStream_t)stream, p);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(AASD_ERR_LAUNCH, "build_tree launch failed: %s", hipGetErrorString(e));
+    return AASD_OK;
+}
+
+size_t aasd_verify_tree_workspace_bytes(int32_t B, int32_t N, int32_t V, int32_t dt)
+{
+    if (B < 0 || N < 1 || N > AASD_MAX_TREE_NODES || V <= 0 || !valid_dtype(dt)) return 0;
+    const int64_t rows = (int64_t)B * N;
+    const SweepPlan pl = plan_sweep(false, rows, V, dt);
+    return (size_t)rows * pl.npart * sizeof(aasd::WavePartial);
+}
+
+int aasd_verify_tree(const void* logits, int32_t dt, int32_t B, int32_t N, int32_t V,
+                     int64_t row_stride, int64_t seq_stride, const int32_t* node_token,
+                     const int32_t* node_parent, const uint8_t* node_strict,
+                     const int32_t* n_nodes, float alpha, float beta, uint32_t flags,
+                     int32_t* accept_len, int32_t* best_node, int32_t* accept_path,
+                     int32_t* next_token, float* row_entropy, float* row_pmax,
+                     int32_t* row_argmax, float* node_p, float* node_delta,
+                     uint32_t* near_count, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!valid_dtype(dt)) return fail(AASD_ERR_INVALID_ARG, "verify_tree: unknown dtype %d", dt);
+    if (B < 0) return fail(AASD_ERR_INVALID_ARG, "verify_tree: B = %d < 0", B);
+    if (N < 1 || N > AASD_MAX_TREE_NODES) return fail(AASD_ERR_INVALID_ARG, "verify_tree: N = %d outside [1,%d]", N, AASD_MAX_TREE_NODES);
+    if (V <= 0) return fail(AASD_ERR_INVALID_ARG, "verify_tree: V = %d <= 0", V);
+    if (row_stride < V) return fail(AASD_ERR_INVALID_ARG, "verify_tree: row_stride %lld < V %d", (long long)row_stride, V);
+    if (seq_stride < (int64_t)N * row_stride)
+        return fail(AASD_ERR_INVALID_ARG, "verify_tree: seq_stride %lld < N*row_stride %lld", (long long)seq_stride, (long long)((int64_t)N * row_stride));
+    if (flags & ~AASD_VERIFY_NO_CLAMP) return fail(AASD_ERR_INVALID_ARG, "verify_tree: unknown flag bits 0x%x", flags);
+    if (B == 0) return AASD_OK;
+    if (!logits || !node_token || !node_parent || !n_nodes || !accept_len || !best_node || !next_token)
+        return fail(AASD_ERR_INVALID_ARG, "verify_tree: null required pointer");
+    if (((uintptr_t)logits % elt_size(dt)) != 0)
+        return fail(AASD_ERR_UNSUPPORTED, "verify_tree: logits pointer is not aligned to its element size");
+    const size_t need = aasd_verify_tree_workspace_bytes(B, N, V, dt);
+    if (!workspace || workspace_bytes < need)
+        return fail(AASD_ERR_WORKSPACE, "verify_tree: workspace of %zu bytes needed, %zu given", need, workspace ? workspace_bytes : (size_t)0);
+    if (((uintptr_t)workspace % 16) != 0) return fail(AASD_ERR_WORKSPACE, "verify_tree: workspace is not 16-byte aligned");
+
+    hipStream_t s = (hipStream_t)stream;
+    const int64_t rows = (int64_t)B * N;
+    const SweepPlan pl = plan_sweep(false, rows, V, dt);
+    aasd::SweepParams sp{};
+    sp.logits = logits; sp.V = V; sp.row_stride = row_stride; sp.seq_stride = seq_stride; sp.rows_per_seq = N;
+    sp.rows_used = n_nodes;
+    sp.c = 1; sp.nseg = pl.nseg; sp.seg_vecs = pl.seg_vecs; sp.partials = (aasd::WavePartial*)workspace;
+    int rc = dt == AASD_BF16 ? launch_sweep<AASD_BF16, false, false>(sp, pl, rows, 0, s)
+                             : launch_sweep<AASD_F32, false, false>(sp, pl, rows, 0, s);
+    if (rc != AASD_OK) return rc;
+
+    aasd::VerifyTreeParams tp{};
+    tp.logits = logits; tp.B = B; tp.N = N; tp.V = V; tp.row_stride = row_stride; tp.seq_stride = seq_stride;
+    tp.node_token = node_token; tp.node_parent = node_parent; tp.node_strict = node_strict; tp.n_nodes = n_nodes;
+    tp.alpha = alpha; tp.beta = beta; tp.flags = flags;
+    tp.accept_len = accept_len; tp.best_node = best_node; tp.accept_path = accept_path; tp.next_token = next_token;
+    tp.node_p = node_p; tp.node_delta = node_delta; tp.near_count = near_count;
+    tp.row_entropy = row_entropy; tp.row_pmax = row_pmax; tp.row_argmax = row_argmax;
+    tp.partials = (const aasd::WavePartial*)workspace; tp.npart = pl.npart;
+    if (dt == AASD_BF16)
+        hipLaunchKernelGGL(aasd::verify_tree_kernel<AASD_BF16>, dim3((unsigned)B), dim3(aasd::kTreeBlock), 0, s, tp);
+    else
+        hipLaunchKernelGGL(aasd::verify_tree_kernel<AASD_F32>, dim3((unsigned)B), dim3(aasd::kTreeBlock), 0, s, tp);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(AASD_ERR_LAUNCH, "verify_tree launch failed: %s", hipGetErrorString(e));
     return AASD_OK;
 }
 

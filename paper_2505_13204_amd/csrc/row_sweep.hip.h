@@ -27,7 +27,10 @@
 namespace aasd {
 
 constexpr int kNumAcc = 4;      // independent partial sums per lane (shorter rounding chains, more ILP)
-constexpr float kRefSlack = 44.0f;  // nats a chunk may exceed the reference exponent before it is moved
+// Nats a chunk may exceed the lane's reference exponent before the reference is moved.  The sum t carries
+// the term d*2^d of the largest element, which cancels when the sums are brought to the row maximum; its
+// rounding error is eps*d, so d is kept small: 4 nats bound the entropy error of a peaked row by ~2e-7 nats.
+constexpr float kRefSlack = 4.0f;  // nats a chunk may exceed the reference exponent before it is moved
 
 // What one wave leaves behind for the finish kernel.
 struct WavePartial {
@@ -50,6 +53,7 @@ struct SweepParams {
     int64_t row_stride;    // elements
     int64_t seq_stride;    // elements, verification only (rows_per_seq rows per sequence)
     int32_t rows_per_seq;  // 1 for prefill rows
+    const int32_t* rows_used;  // optional [sequences]: rows of a sequence at or beyond max(this count, 1) are skipped
     const int32_t* next_tok;  // alignment sampling only
     int32_t want_cand;     // candidates are wanted (m > 0)
     int32_t c;
@@ -502,8 +506,9 @@ __global__ __launch_bounds__(BLOCK) void row_sweep_kernel(SweepParams p, int64_t
     WavePartial* out = p.partials + slot;
     int32_t* out_list = ALIGN ? p.lists + slot * kListCap : nullptr;
 
-    // a wave whose lanes own no element at all leaves the neutral partial
-    const bool owns = tid < rs.head_n || tid < rs.nvec || tid < rs.tail_n;
+    // a wave whose lanes own no element at all, or whose row is not in use, leaves the neutral partial
+    bool owns = tid < rs.head_n || tid < rs.nvec || tid < rs.tail_n;
+    if (p.rows_used && (int)(row % p.rows_per_seq) >= max(p.rows_used[row / p.rows_per_seq], 1)) owns = false;
     if (__ballot(owns) == 0ull) {
         if (lane == 0) {
             WavePartial wp;

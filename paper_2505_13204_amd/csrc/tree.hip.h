@@ -1,0 +1,309 @@
+// Draft tree (Sec. 3.2, Eq. 2): merging the candidate n-grams and the alignment extras of their
+// positions into one tree under the last committed token, the tree attention mask, and conditional
+// verification (Sec. 3.3) over that tree.
+#pragma once
+
+#include "row_finish.hip.h"
+
+namespace aasd {
+
+constexpr int kTreeBlock = 256;
+constexpr int kMaxLayerEvents = AASD_MAX_CANDIDATES * (1 + AASD_MAX_EXTRAS);  // 160 tokens can enter one layer
+
+struct BuildTreeParams {
+    const int32_t* drafts;        // [B, C, k]
+    const int32_t* draft_len;     // [B, C]
+    const uint8_t* strict;        // [B, C, k] or null
+    const int32_t* draft_extras;  // [B, C, k, m] or null
+    int32_t m_x;
+    const int32_t* root_tok;      // [B] or null
+    int32_t B, C, k, max_nodes;
+    int32_t* node_token;
+    int32_t* node_parent;
+    int32_t* node_depth;
+    uint8_t* node_strict;
+    int32_t* n_nodes;
+    uint32_t* mask;               // [B, max_nodes, W] or null
+    int32_t* cand_node;           // [B, C, k] or null
+};
+
+// One workgroup per sequence.  The tree grows layer by layer.  In layer j every (candidate, slot)
+// pair is an event (slot 0 = the candidate's j-th token, slots 1..m = its extras) with the key
+// (node at the end of the candidate's path, token).  An event whose key no earlier event of the
+// layer has opens a node; nodes are numbered in event order by a ballot/popcount prefix, which
+// is exactly the order a serial insertion into a (parent, token) dictionary would give.
+__global__ __launch_bounds__(kTreeBlock) void build_tree_kernel(BuildTreeParams p)
+{
+    __shared__ int ev_par[kMaxLayerEvents], ev_tok[kMaxLayerEvents], ev_node[kMaxLayerEvents];
+    __shared__ unsigned char ev_valid[kMaxLayerEvents], ev_flag[kMaxLayerEvents];
+    __shared__ int cur[AASD_MAX_CANDIDATES];
+    __shared__ int n_tok[AASD_MAX_TREE_NODES], n_par[AASD_MAX_TREE_NODES], n_dep[AASD_MAX_TREE_NODES];
+    __shared__ unsigned char n_str[AASD_MAX_TREE_NODES];
+    __shared__ int wave_cnt[kTreeBlock / kWave];
+
+    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
+    const int C = p.C, k = p.k, m = p.draft_extras ? p.m_x : 0, N = p.max_nodes;
+    const int per = 1 + m, E = C * per;
+    const int e = tid, c = e / per, slot = e - c * per;
+    const size_t bc = (size_t)b * C + (e < E ? c : 0);
+
+    if (tid < C) cur[tid] = 0;
+    if (tid == 0) {
+        n_tok[0] = p.root_tok ? p.root_tok[b] : -1;
+        n_par[0] = -1; n_dep[0] = 0; n_str[0] = 0;
+    }
+    if (p.cand_node)
+        for (int i = tid; i < C * k; i += kTreeBlock) p.cand_node[(size_t)b * C * k + i] = -1;
+    int dl = 0;
+    if (e < E) {
+        dl = p.draft_len[bc];
+        dl = dl < 0 ? 0 : (dl > k ? k : dl);
+    }
+    __syncthreads();
+
+    int n = 1;  // nodes so far: the same value in every thread
+    for (int j = 1; j <= k; ++j) {
+        bool valid = false;
+        int tok = -1, par = -1, st = 0;
+        if (e < E) {
+            par = cur[c];
+            if (par >= 0 && j <= dl) {
+                const int main_tok = p.drafts[bc * k + (j - 1)];
+                if (main_tok >= 0) {  // a missing token ends the candidate's path, extras included
+                    if (slot == 0) {
+                        tok = main_tok; valid = true;
+                        st = p.strict ? (p.strict[bc * k + (j - 1)] != 0) : 0;
+                    } else {
+                        const int x = p.draft_extras[(bc * k + (j - 1)) * m + (slot - 1)];
+                        if (x >= 0) { tok = x; valid = true; }  // extras are verified conditionally
+                    }
+                }
+            }
+            ev_par[e] = par; ev_tok[e] = tok; ev_valid[e] = valid; ev_flag[e] = (unsigned char)st;
+        }
+        __syncthreads();
+        int rep = e;  // earliest event of the layer with the same key
+        if (valid) {
+            for (int e2 = 0; e2 < e; ++e2)
+                if (ev_valid[e2] && ev_par[e2] == par && ev_tok[e2] == tok) { rep = e2; break; }
+        }
+        const bool first = valid && rep == e;
+        const unsigned long long bal = __ballot(first);
+        const int before = __popcll(bal & ((1ull << lane) - 1ull));
+        if (lane == 0) wave_cnt[wid] = __popcll(bal);
+        __syncthreads();
+        int offset = n, total = 0;
+#pragma unroll
+        for (int w = 0; w < kTreeBlock / kWave; ++w) {
+            if (w < wid) offset += wave_cnt[w];
+            total += wave_cnt[w];
+        }
+        int id = -1;
+        if (first) {
+            id = offset + before < N ? offset + before : -1;  // beyond the node budget: dropped
+            ev_node[e] = id;
+            if (id >= 0) { n_tok[id] = tok; n_par[id] = par; n_dep[id] = j; }
+        }
+        __syncthreads();
+        if (valid && !first && st == 0) ev_flag[rep] = 0;  // one conditional source makes the node conditional
+        __syncthreads();
+        if (first && id >= 0) n_str[id] = ev_flag[e];
+        if (e < E && slot == 0) {
+            const int nid = valid ? ev_node[rep] : -1;
+            cur[c] = nid;
+            if (valid && p.cand_node) p.cand_node[bc * k + (j - 1)] = nid;
+        }
+        n = n + total < N ? n + total : N;
+        __syncthreads();
+    }
+
+    if (tid == 0) p.n_nodes[b] = n;
+    const int W = (N + 31) / 32;
+    for (int i = tid; i < N; i += kTreeBlock) {
+        const size_t bi = (size_t)b * N + i;
+        const bool used = i < n;
+        p.node_token[bi] = used ? n_tok[i] : -1;
+        p.node_parent[bi] = used ? n_par[i] : -1;
+        p.node_depth[bi] = used ? n_dep[i] : 0;
+        p.node_strict[bi] = used ? n_str[i] : 0;
+        if (p.mask) {
+            for (int wi = 0; wi < W; ++wi) {  // tree attention mask: the node and its ancestors
+                uint32_t word = 0;
+                for (int a = used ? i : -1; a >= 0; a = n_par[a])
+                    if ((a >> 5) == wi) word |= 1u << (a & 31);
+                p.mask[bi * W + wi] = word;
+            }
+        }
+    }
+}
+
+struct VerifyTreeParams {
+    const void* logits;
+    int32_t B, N, V;
+    int64_t row_stride, seq_stride;
+    const int32_t* node_token;
+    const int32_t* node_parent;
+    const uint8_t* node_strict;
+    const int32_t* n_nodes;
+    float alpha, beta;
+    uint32_t flags;
+    int32_t* accept_len;
+    int32_t* best_node;
+    int32_t* accept_path;  // [B, AASD_MAX_DRAFT]
+    int32_t* next_token;
+    float* node_p;
+    float* node_delta;
+    uint32_t* near_count;
+    float* row_entropy;
+    float* row_pmax;
+    int32_t* row_argmax;
+    const WavePartial* partials;  // [B * N][npart]
+    int32_t npart;
+};
+
+// One workgroup per sequence, a thread per node.  Node i is decided against the row of its parent
+// (Eq. 4-6); it is accepted iff it and all its ancestors pass; the deepest accepted node wins.
+template <int DT>
+__global__ __launch_bounds__(kTreeBlock) void verify_tree_kernel(VerifyTreeParams p)
+{
+    __shared__ float4 stats[AASD_MAX_TREE_NODES];  // per row {max logit, S, H, bits of argmax}
+    __shared__ int par_s[AASD_MAX_TREE_NODES];
+    __shared__ unsigned char pass_s[AASD_MAX_TREE_NODES];
+    __shared__ unsigned red_key[kTreeBlock / kWave], red_near[kTreeBlock / kWave];
+
+    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
+    const int N = p.N;
+    int n = p.n_nodes[b];
+    n = n < 1 ? 1 : (n > N ? N : n);
+
+    // ---- statistics of the used rows from the sweep's partials: G lanes per row ----
+    {
+        int G = 1;
+        while (G < p.npart) G <<= 1;
+        const int rows_per_pass = kTreeBlock / G;
+        const int sub = tid / G, s = tid - sub * G;
+        for (int r0 = 0; r0 < N; r0 += rows_per_pass) {
+            const int r = r0 + sub;
+            const bool have_row = r < n;
+            const int64_t row = (int64_t)b * N + (r < N ? r : 0);
+            WavePartial wp;
+            wp.m = -INFINITY; wp.S = 0.f; wp.T = 0.f; wp.code = 0x7fffffff;
+            if (have_row && s < p.npart) wp = p.partials[row * p.npart + s];
+            float m = wp.m;
+            for (int o = 1; o < G; o <<= 1) m = fmaxf(m, __shfl_xor(m, o));
+            const bool live = wp.S > 0.f;
+            float dl2 = 0.f, f = 0.f;
+            if (live) partial_scale(wp.m, m, dl2, f);
+            float S = live ? wp.S * f : 0.f;
+            float T2 = live ? (wp.T + dl2 * wp.S) * f : 0.f;
+            int code = live && wp.m == m ? wp.code : 0x7fffffff;
+            for (int o = 1; o < G; o <<= 1) {
+                S += __shfl_xor(S, o);
+                T2 += __shfl_xor(T2, o);
+                code = min(code, __shfl_xor(code, o));
+            }
+            if (r < N && s == 0) {
+                float H = 0.f, pmax = 0.f;
+                int am = -1;
+                if (have_row) {
+                    const RowShape rs = row_shape<DT>(p.logits, (int64_t)b * p.seq_stride + (int64_t)r * p.row_stride, p.V);
+                    am = 0;
+                    if ((unsigned)code < (unsigned)p.V) {
+                        am = code;
+                        const int len = (code >= rs.head && code < rs.tail0) ? Elt<DT>::kPerVec : 1;
+                        for (int e = 0; e < len; ++e)
+                            if (load_elt<DT>(rs.base, code + e) == m) { am = code + e; break; }
+                    }
+                    H = entropy_from_sums(S, T2);
+                    pmax = 1.0f / S;
+                    stats[r] = make_float4(m, S, H, __int_as_float(am));
+                }
+                if (p.row_entropy) p.row_entropy[row] = H;
+                if (p.row_pmax) p.row_pmax[row] = pmax;
+                if (p.row_argmax) p.row_argmax[row] = am;
+            }
+        }
+    }
+
+    // ---- per-node decision against the parent's row ----
+    const int i = tid;
+    const size_t bi = (size_t)b * N + (i < N ? i : 0);
+    int par = -1;
+    if (i >= 1 && i < n) {
+        par = p.node_parent[bi];
+        if (par < 0 || par >= i) par = -1;  // parents precede their children
+    }
+    if (i < N) par_s[i] = par;
+    __syncthreads();
+
+    bool pass = false, near = false;
+    float pf = 0.f, df = 0.f;
+    if (par >= 0) {
+        const int t = p.node_token[bi];
+        const float4 st = stats[par];
+        const double m = (double)st.x, S = (double)st.y, H = (double)st.z;
+        const bool valid = t >= 0 && t < p.V;
+        float zt = 0.f;
+        if (valid) zt = load_elt<DT>(p.logits, (int64_t)b * p.seq_stride + (int64_t)par * p.row_stride + t);
+        const double pr = valid ? exp((double)zt - m) / S : 0.0;
+        const double Delta = 1.0 / S;                              // Eq. 6
+        const double thr = (double)p.alpha * H + (double)p.beta;   // Eq. 5
+        double delta;
+        if (p.flags & AASD_VERIFY_NO_CLAMP) {
+            delta = thr;
+            pass = valid && pr >= delta;
+        } else {
+            const bool is_strict = p.node_strict != nullptr && p.node_strict[bi] != 0;
+            delta = is_strict ? Delta : fmin(thr, Delta);
+            pass = valid && (pr >= delta || zt == st.x);           // Eq. 4; ties with the maximum pass
+        }
+        near = fabs(pr - delta) < 1e-6;
+        pf = (float)pr;
+        df = (float)delta;
+    }
+    if (i < N) {
+        pass_s[i] = pass;
+        if (p.node_p) p.node_p[bi] = pf;
+        if (p.node_delta) p.node_delta[bi] = df;
+    }
+    __syncthreads();
+
+    // ---- accepted iff the node and all its ancestors pass; depth by walking up (parents have smaller indices) ----
+    bool reached = par >= 0;  // all ancestors pass: the node is evaluated
+    int depth = 0;
+    if (par >= 0) {
+        depth = 1;
+        for (int a = par; a > 0; a = par_s[a]) {
+            reached = reached && pass_s[a];
+            ++depth;
+        }
+    }
+    const bool ok = reached && pass;
+    unsigned key = ok ? ((unsigned)depth << 16) | (unsigned)(0xffff - i) : 0u;  // deepest, then lowest index
+    unsigned nr = (reached && near) ? 1u : 0u;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        key = max(key, (unsigned)__shfl_xor((int)key, o));
+        nr += __shfl_xor(nr, o);
+    }
+    if (lane == 0) { red_key[wid] = key; red_near[wid] = nr; }
+    __syncthreads();
+    if (tid == 0) {
+        unsigned best_key = 0, near_total = 0;
+        for (int w = 0; w < kTreeBlock / kWave; ++w) { best_key = max(best_key, red_key[w]); near_total += red_near[w]; }
+        const int best = best_key ? (int)(0xffff - (best_key & 0xffff)) : 0;
+        const int best_depth = (int)(best_key >> 16);
+        p.accept_len[b] = best_depth;
+        p.best_node[b] = best;
+        p.next_token[b] = __float_as_int(stats[best].w);
+        if (p.near_count) p.near_count[b] = near_total;
+        if (p.accept_path) {
+            for (int d = 0; d < AASD_MAX_DRAFT; ++d) p.accept_path[(size_t)b * AASD_MAX_DRAFT + d] = -1;
+            int d = best_depth;
+            for (int a = best; a > 0; a = par_s[a], --d)
+                if (d >= 1 && d <= AASD_MAX_DRAFT) p.accept_path[(size_t)b * AASD_MAX_DRAFT + d - 1] = a;
+        }
+    }
+}
+
+}  // namespace aasd

@@ -109,3 +109,45 @@ def test_workspace_query(lib):
     assert lib.aasd_align_sample_workspace_bytes(10, 0, 1) == 0
     assert lib.aasd_align_sample_workspace_bytes(10, 128256, 3) == 0
     assert lib.aasd_align_sample_workspace_bytes(0, 128256, 1) == 0
+
+
+def _build_tree(lib, **kw):
+    a = dict(drafts=FAKE, dl=FAKE, strict=None, dx=None, m=0, root=None, B=2, C=4, k=8, N=64, tok=FAKE, par=FAKE,
+             dep=FAKE, st=FAKE, nn=FAKE, mask=None, cn=None, stream=None)
+    a.update(kw)
+    return lib.aasd_build_tree(a["drafts"], a["dl"], a["strict"], a["dx"], a["m"], a["root"], a["B"], a["C"], a["k"],
+                               a["N"], a["tok"], a["par"], a["dep"], a["st"], a["nn"], a["mask"], a["cn"], a["stream"])
+
+
+def test_build_tree_rejects_invalid_arguments(lib):
+    for kw in [dict(B=-1), dict(k=0), dict(k=17), dict(C=0), dict(C=33), dict(m=-1), dict(m=5), dict(dx=FAKE, m=0),
+               dict(N=0), dict(N=257), dict(drafts=None), dict(dl=None), dict(tok=None), dict(par=None), dict(dep=None),
+               dict(st=None), dict(nn=None)]:
+        assert _build_tree(lib, **kw) == INVALID, kw
+        assert b"build_tree" in lib.aasd_last_error()
+    assert _build_tree(lib, B=0, drafts=None) == 0
+
+
+def _verify_tree(lib, **kw):
+    a = dict(logits=FAKE, dt=1, B=2, N=16, V=100, rs=100, ss=1600, tok=FAKE, par=FAKE, st=None, nn=FAKE, alpha=0.1,
+             beta=0.1, flags=0, al=FAKE, bn=FAKE, path=None, nt=FAKE, re=None, rp=None, ra=None, np_=None, nd=None,
+             near=None, ws=FAKE, wsb=1 << 20, stream=None)
+    a.update(kw)
+    return lib.aasd_verify_tree(a["logits"], a["dt"], a["B"], a["N"], a["V"], a["rs"], a["ss"], a["tok"], a["par"],
+                                a["st"], a["nn"], a["alpha"], a["beta"], a["flags"], a["al"], a["bn"], a["path"], a["nt"],
+                                a["re"], a["rp"], a["ra"], a["np_"], a["nd"], a["near"], a["ws"], a["wsb"], a["stream"])
+
+
+def test_verify_tree_rejects_invalid_arguments(lib):
+    for kw in [dict(dt=2), dict(B=-1), dict(N=0), dict(N=257), dict(V=0), dict(rs=99), dict(ss=1599), dict(flags=4),
+               dict(logits=None), dict(tok=None), dict(par=None), dict(nn=None), dict(al=None), dict(bn=None),
+               dict(nt=None)]:
+        assert _verify_tree(lib, **kw) == INVALID, kw
+    assert _verify_tree(lib, logits=FAKE + 1) == UNSUPPORTED
+    assert _verify_tree(lib, ws=None) == WORKSPACE
+    assert _verify_tree(lib, wsb=lib.aasd_verify_tree_workspace_bytes(2, 16, 100, 1) - 1) == WORKSPACE
+    assert _verify_tree(lib, ws=FAKE + 4) == WORKSPACE
+    assert _verify_tree(lib, B=0) == 0
+    assert lib.aasd_verify_tree_workspace_bytes(64, 64, 128256, 1) == 64 * 64 * 16 * 32   # 4096 rows, 16 waves per row
+    assert lib.aasd_verify_tree_workspace_bytes(1, 0, 100, 1) == 0
+    assert lib.aasd_verify_tree_workspace_bytes(1, 257, 100, 1) == 0

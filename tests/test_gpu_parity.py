@@ -101,6 +101,29 @@ def test_align_degenerate_rows():
         assert abs(got["entropy"][3] - math.log(2)) < 1e-5
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_low_entropy_rows_with_a_dominant_logit(dtype):
+    """One logit far above the rest, met late in the sweep: the entropy is small and its error must not
+    grow with the height of the peak above what the lane had seen before."""
+    rng = np.random.default_rng(77)
+    rows, V = 96, 40000
+    z = rng.standard_normal((rows, V)).astype(np.float32) * 1.7
+    for r in range(rows):
+        pos = rng.choice(np.arange(V // 2, V), 3, replace=False)
+        h = 8.0 + 0.5 * r      # 8 .. 55 nats above the bulk
+        z[r, pos] = [h, h - 5.0, h - 6.0]
+    zd = _dev_logits(z, dtype)
+    nt = rng.integers(0, V, size=rows).astype(np.int32)
+    tally = bk.Tally()
+    ref = bk.oracle_align(zd, nt, 2, 4, oracle.EXTRAS_TOP)
+    assert 0.03 < ref["entropy"].min() < 0.06
+    bk.compare_align(bk.hip_align(zd, nt, 2, 4, oracle.EXTRAS_TOP), ref, tally, oracle.EXTRAS_TOP)
+    B = rows // 3
+    drafts = rng.integers(0, V, size=(B, 1, 2)).astype(np.int32)
+    _verify_both(zd.view(B, 3, V), drafts, np.full((B, 1), 2, np.int32), None, 0.1, 0.1, 0, tally)
+    print("low entropy", dtype, tally)
+
+
 def test_align_many_ties_above_next_token_overflows_candidate_buffer():
     """More than 256 tokens tied above the prompt token: the exact fallback selection runs."""
     V = 6000
