@@ -11,6 +11,9 @@ throughput form; the sequential per-step latency is reported beside it).
 The metric is logit rows per second (prefill rows sampled + verify rows verified); the roofline
 block gives the achieved HBM bandwidth of the dominant kernel, the fused row sweep.
 
+The workloads tree_single and tree_batch run the draft-tree form of the same path instead (alignment
+sampling, retrieval with the extras, tree build, tree verification over one row per tree node).
+
 Prints ONE JSON line.  `--gpus N` with N > 1 is refused: this build is single-GPU.
 """
 import argparse
@@ -32,14 +35,47 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="llama3_single",
-                    choices=["tiny", "llama3_single", "long_context", "batched_serving", "stress_tree"])
+                    choices=["tiny", "llama3_single", "long_context", "batched_serving", "stress_tree",
+                             "tree_single", "tree_batch"])
     ap.add_argument("--decode-steps", type=int, default=None, help="override the workload's number of decode steps")
     ap.add_argument("--prefill-rows", type=int, default=None, help="cap on prefill rows held in HBM")
+    ap.add_argument("--max-nodes", type=int, default=None, help="tree_* workloads: node budget per sequence (default min(256, 1 + C*k*(1+m)))")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-latency", action="store_true")
     ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "row_sweep_traffic.txt"),
                     help="text file with HBM bytes per launch measured by rocprofv3 --pmc (key = value lines)")
     return ap.parse_args()
+
+
+_hip = None
+
+
+def hip_event():
+    """A raw hipEvent_t: the library's measurement hook records these around the sweep kernel alone."""
+    global _hip
+    import ctypes
+    if _hip is None:
+        _hip = ctypes.CDLL("libamdhip64.so")
+    e = ctypes.c_void_p()
+    assert _hip.hipEventCreate(ctypes.byref(e)) == 0
+    return e
+
+
+def hip_elapsed(a, b):
+    import ctypes
+    ms = ctypes.c_float()
+    assert _hip.hipEventElapsedTime(ctypes.byref(ms), a, b) == 0
+    return ms.value
+
+
+def read_traffic(path):
+    measured = {}
+    if path and os.path.exists(path):
+        for line in open(path):
+            if "=" in line and not line.lstrip().startswith("#"):
+                k_, v_ = line.split("=", 1)
+                measured[k_.strip()] = v_.strip()
+    return measured
 
 
 def main():
@@ -63,6 +99,8 @@ def main():
     if args.decode_steps:
         w = synth.scaled(w, steps=args.decode_steps)
     elt = 2 if w.dtype == "bf16" else 4
+    if w.name.startswith("tree_"):
+        return bench_tree(args, w, dev)
 
     # ---------------------------------------------------------------- setup (untimed)
     t_setup = time.time()
@@ -143,19 +181,6 @@ def main():
     # ---------------------------------------------------------------- timed region: exactly K steps
     # HIP events on the stream the kernels run on: one pair around each API call, and (through the
     # library's measurement hook) one pair around each row-sweep kernel alone.
-    import ctypes
-    hip = ctypes.CDLL("libamdhip64.so")
-
-    def hip_event():
-        e = ctypes.c_void_p()
-        assert hip.hipEventCreate(ctypes.byref(e)) == 0
-        return e
-
-    def hip_elapsed(a, b):
-        ms = ctypes.c_float()
-        assert hip.hipEventElapsedTime(ctypes.byref(ms), a, b) == 0
-        return ms.value
-
     K = args.steps
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(K)]
     kev = [[hip_event() for _ in range(4)] for _ in range(K)]
@@ -188,12 +213,7 @@ def main():
     verify_gbs = verify_rows * row_bytes / (verify_sweep_ms * 1e-3) / 1e9
     # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE), if this workload was profiled
     traffic = None
-    measured = {}
-    if args.traffic_file and os.path.exists(args.traffic_file):
-        for line in open(args.traffic_file):
-            if "=" in line and not line.lstrip().startswith("#"):
-                k_, v_ = line.split("=", 1)
-                measured[k_.strip()] = v_.strip()
+    measured = read_traffic(args.traffic_file)
     # the dominant kernel is the row sweep; of its two launches per step the one that runs longer is reported
     dom = "verify" if verify_sweep_ms >= align_sweep_ms else "align"
     key = f"{w.name}.{dom}_sweep.hbm_bytes_per_launch"
@@ -267,6 +287,191 @@ def main():
                    "verify_rows": verify_rows, "rows_per_step": rows_per_step,
                    "form": "all decode steps verified as one batch"},
         "roofline": roofline, "cpu_baseline": cpu, "latency": latency,
+        "tokens_per_decode_step": round(trace.mean_accept_len, 3), "setup_s": round(setup_s, 1),
+    }
+    print(json.dumps(out))
+
+
+def bench_tree(args, w, dev):
+    """The draft-tree form of the path (Sec. 3.2, Eq. 2): per step align_sample over the resident prefill
+    rows, then for every recorded decode step retrieval with the alignment extras, tree build and tree
+    verification (one logits row per tree node; rows beyond a sequence's node count are not read)."""
+    import numpy as np
+    import torch
+
+    import paper_2505_13204_amd as aasd
+    from paper_2505_13204_amd import harness, synth
+
+    elt = 2 if w.dtype == "bf16" else 4
+    dt_code = aasd.BF16 if w.dtype == "bf16" else aasd.F32
+    N = args.max_nodes or min(aasd.MAX_TREE_NODES, 1 + w.C * w.k * (1 + w.m))
+    t_setup = time.time()
+    streams = [synth.tree_stream(w, b) for b in range(w.B)]
+    cap_rows = args.prefill_rows or 16384
+    n_prefill_seq = max(1, min(w.B, cap_rows // w.L))
+    prefill_rows = n_prefill_seq * w.L
+    prefill = torch.empty((prefill_rows, w.V), dtype=w.torch_dtype, device=dev)
+    scratch = torch.empty((w.L, w.V), dtype=w.torch_dtype, device=dev)
+    next_tok = np.empty(w.B * w.L, dtype=np.int32)
+    extras = torch.empty((w.B * w.L, w.m), dtype=torch.int32, device=dev)
+    n_extras = torch.empty((w.B * w.L,), dtype=torch.uint8, device=dev)
+    for b in range(w.B):   # alignment sampling of every prompt (setup); the first sequences stay resident for the timed pass
+        g, alt, slot = streams[b]
+        buf = prefill[b * w.L:(b + 1) * w.L] if b < n_prefill_seq else scratch
+        synth.tree_prefill_logits(w, b, g, alt, slot, dev, out=buf)
+        next_tok[b * w.L:(b + 1) * w.L] = synth.next_tokens(w, g)
+        o = aasd.align_sample(buf, torch.from_numpy(next_tok[b * w.L:(b + 1) * w.L]).to(dev), m=w.m, c=w.c,
+                              mode=aasd.EXTRAS_TOP, seed=w.seed, row_id_base=b * w.L)
+        extras[b * w.L:(b + 1) * w.L] = o["extras"]
+        n_extras[b * w.L:(b + 1) * w.L] = o["n_extras"]
+    del scratch
+    next_tok_d = torch.from_numpy(next_tok[:prefill_rows]).to(dev)
+    align_out = aasd.align_sample(prefill, next_tok_d, m=w.m, c=w.c, mode=aasd.EXTRAS_TOP, seed=w.seed)
+    extras_h, n_extras_h = extras.cpu().numpy(), n_extras.cpu().numpy()
+
+    class Recorder(harness.Backend):
+        def __init__(self):
+            self.logits = []
+
+        def _d(self, a, dt):
+            return torch.as_tensor(np.ascontiguousarray(a), device=dev).to(dt)
+
+        def retrieve(self, tokens, length, prompt_len, w_, ex, nx):
+            out = aasd.retrieve_drafts(self._d(tokens, torch.int32), self._d(length, torch.int32),
+                                       self._d(prompt_len, torch.int32), w_.n_min, w_.n_max, w_.k, w_.C,
+                                       extras=extras, n_extras=n_extras, m=w_.m, extras_stride=w_.L)
+            return {k: (v.cpu().numpy() if v is not None else None) for k, v in out.items()}
+
+        def build_tree(self, r, root_tok, max_nodes):
+            out = aasd.build_tree(self._d(r["drafts"], torch.int32), self._d(r["draft_len"], torch.int32),
+                                  self._d(r["strict"], torch.uint8), self._d(r["draft_extras"], torch.int32),
+                                  self._d(root_tok, torch.int32), max_nodes=max_nodes)
+            return {k: v.cpu().numpy() for k, v in out.items() if v is not None}
+
+        def make_tree_logits(self, w_, step, gs, length, tree):
+            z = synth.tree_verify_logits(w_, step, gs, length, tree, dev)
+            self.logits.append(z)
+            return z
+
+        def verify_tree(self, logits, tree, w_):
+            out = aasd.verify_tree(logits, self._d(tree["node_token"], torch.int32), self._d(tree["node_parent"], torch.int32),
+                                   self._d(tree["n_nodes"], torch.int32), self._d(tree["node_strict"], torch.uint8),
+                                   alpha=w_.alpha, beta=w_.beta, want_rows=False, want_nodes=False, want_near=False)
+            return {k: v.cpu().numpy() for k, v in out.items() if v is not None and k != "workspace"}
+
+    step_bytes = w.B * N * w.V * elt
+    max_steps_resident = max(1, min(w.steps, int(24 * 2 ** 30 // step_bytes)))
+    rec = Recorder()
+    trace = harness.decode_tree(synth.scaled(w, steps=max_steps_resident), rec, streams, extras_h, n_extras_h,
+                                max_nodes=N)
+    S = len(trace.steps)
+    BB = S * w.B
+    tree_logits = torch.stack(rec.logits).view(BB, N, w.V)
+    rec.logits = None
+    tokens_b = torch.from_numpy(np.tile(trace.tokens, (S, 1))).to(dev).contiguous()
+    len_h = np.concatenate([s.length for s in trace.steps]).astype(np.int32)
+    len_b = torch.from_numpy(len_h).to(dev)
+    plen_b = torch.full((BB,), w.L, dtype=torch.int32, device=dev)
+    root_b = torch.from_numpy(np.tile(trace.tokens, (S, 1))[np.arange(BB), len_h - 1].astype(np.int32)).to(dev)
+    # sequence s*B + b of the batch reads the extras of prompt b: tile them like the token buffers
+    extras_b = extras.view(w.B, w.L, w.m).repeat(S, 1, 1).view(BB * w.L, w.m).contiguous()
+    n_extras_b = n_extras.view(w.B, w.L).repeat(S, 1).view(BB * w.L).contiguous()
+    ws = torch.empty(max(16, aasd.verify_tree_workspace_bytes(BB, N, w.V, dt_code)), dtype=torch.uint8, device=dev)
+    r_out = aasd.retrieve_drafts(tokens_b, len_b, plen_b, w.n_min, w.n_max, w.k, w.C, extras=extras_b,
+                                 n_extras=n_extras_b, m=w.m, extras_stride=w.L)
+    t_out = aasd.build_tree(r_out["drafts"], r_out["draft_len"], r_out["strict"], r_out["draft_extras"], root_b, max_nodes=N)
+    v_out = aasd.verify_tree(tree_logits, t_out["node_token"], t_out["node_parent"], t_out["n_nodes"], t_out["node_strict"],
+                             alpha=w.alpha, beta=w.beta, workspace=ws, want_rows=False, want_nodes=False)
+    torch.cuda.synchronize()
+    seq_accept = np.concatenate([s.verified["accept_len"] for s in trace.steps])
+    assert (v_out["accept_len"].cpu().numpy() == seq_accept).all(), "batched tree verification differs from the decode loop"
+    n_nodes_h = t_out["n_nodes"].cpu().numpy()
+    tree_rows = int(n_nodes_h.sum())
+    setup_s = time.time() - t_setup
+    rows_per_step = prefill_rows + tree_rows
+
+    def one_pass(i=None, ev=None, kev=None):
+        if ev: ev[0].record(); aasd.set_sweep_events(kev[0], kev[1])
+        aasd.align_sample(prefill, next_tok_d, m=w.m, c=w.c, mode=aasd.EXTRAS_TOP, seed=w.seed, out=align_out)
+        if ev: ev[1].record()
+        aasd.retrieve_drafts(tokens_b, len_b, plen_b, w.n_min, w.n_max, w.k, w.C, extras=extras_b, n_extras=n_extras_b,
+                             m=w.m, extras_stride=w.L, out=r_out)
+        if ev: ev[2].record()
+        aasd.build_tree(r_out["drafts"], r_out["draft_len"], r_out["strict"], r_out["draft_extras"], root_b, max_nodes=N,
+                        out=t_out)
+        if ev: ev[3].record(); aasd.set_sweep_events(kev[2], kev[3])
+        aasd.verify_tree(tree_logits, t_out["node_token"], t_out["node_parent"], t_out["n_nodes"], t_out["node_strict"],
+                         alpha=w.alpha, beta=w.beta, workspace=ws, want_rows=False, want_nodes=False, out=v_out)
+        if ev: ev[4].record()
+
+    for _ in range(args.warmup):
+        one_pass()
+    torch.cuda.synchronize()
+    K = args.steps
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(K)]
+    kev = [[hip_event() for _ in range(4)] for _ in range(K)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):
+        one_pass(i, ev[i], kev[i])
+    aasd.set_sweep_events(None, None)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / K
+    mean = lambda a, b: float(np.mean([ev[i][a].elapsed_time(ev[i][b]) for i in range(K)]))
+    align_ms, retr_ms, build_ms, verify_ms = mean(0, 1), mean(1, 2), mean(2, 3), mean(3, 4)
+    align_sweep_ms = float(np.mean([hip_elapsed(kev[i][0], kev[i][1]) for i in range(K)]))
+    tree_sweep_ms = float(np.mean([hip_elapsed(kev[i][2], kev[i][3]) for i in range(K)]))
+    row_bytes = w.V * elt
+    align_gbs = prefill_rows * row_bytes / (align_sweep_ms * 1e-3) / 1e9
+    tree_gbs = tree_rows * row_bytes / (tree_sweep_ms * 1e-3) / 1e9
+    roofline = {
+        "bound": "hbm", "kernel": f"aasd::row_sweep_kernel (tree verification launch, {tree_rows} used rows of {BB * N})",
+        "achieved": round(tree_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(tree_gbs / HBM_PEAK_GBS, 4),
+        "traffic": None, "bytes_per_launch": tree_rows * row_bytes, "avg_launch_ms": round(tree_sweep_ms, 4),
+        "align_sample": {"rows": prefill_rows, "sweep_kernel_ms": round(align_sweep_ms, 4), "GB/s": round(align_gbs, 1),
+                         "frac": round(align_gbs / HBM_PEAK_GBS, 4), "call_ms": round(align_ms, 4)},
+        "verify_tree": {"rows_used": tree_rows, "rows_launched": BB * N, "sweep_kernel_ms": round(tree_sweep_ms, 4),
+                        "GB/s": round(tree_gbs, 1), "frac": round(tree_gbs / HBM_PEAK_GBS, 4), "call_ms": round(verify_ms, 4)},
+        "retrieve_drafts": {"sequences": BB, "call_ms": round(retr_ms, 4)},
+        "build_tree": {"sequences": BB, "call_ms": round(build_ms, 4), "mean_nodes": round(float(n_nodes_h.mean()), 2),
+                       "max_nodes": int(n_nodes_h.max())},
+        "note": "only the rows of existing tree nodes are read and counted; kernel times from HIP events around the sweep kernel alone",
+    }
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        n_a = min(prefill_rows, 4096)
+        nb = max(1, min(BB, 4096 // max(1, int(n_nodes_h.mean()))))
+        bits_a = synth.to_host_bits(prefill[:n_a])
+        bits_v = synth.to_host_bits(tree_logits[:nb])
+        tok_h = tokens_b[:nb].cpu().numpy()
+        ex_h, nx_h = extras_b[:nb * w.L].cpu().numpy(), n_extras_b[:nb * w.L].cpu().numpy()
+        root_h = root_b[:nb].cpu().numpy()
+        tc = time.perf_counter()
+        oracle.align_sample(bits_a, next_tok[:n_a], m_x=w.m, c=w.c)
+        r = oracle.retrieve_drafts(tok_h, len_h[:nb], np.full(nb, w.L, np.int32), w.n_min, w.n_max, w.k, w.C,
+                                   extras=ex_h, n_extras=nx_h, m_x=w.m, extras_stride=w.L)
+        t = oracle.build_tree(r["drafts"], r["draft_len"], r["strict"], r["draft_extras"], root_tok=root_h, max_nodes=N)
+        oracle.verify_tree(bits_v, t["node_token"], t["node_parent"], t["node_strict"], t["n_nodes"],
+                           alpha=float(np.float32(w.alpha)), beta=float(np.float32(w.beta)))
+        dtc = time.perf_counter() - tc
+        used = int(t["n_nodes"].sum())
+        cpu = {"value": round((n_a + used) / dtc, 1), "unit": "rows/s", "cores": 1, "kind": "oracle",
+               "sample": f"first {n_a} prefill rows + first {nb} trees ({used} tree rows) of the same workload, {dtc:.1f} s",
+               "host_cores_present": os.cpu_count()}
+
+    out = {
+        "metric": "logit rows/sec verified+sampled at V=%d %s" % (w.V, w.dtype),
+        "value": round(rows_per_step / (ms_per_step * 1e-3), 1), "unit": "rows/s", "n_gpus": 1, "steps": K,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "prompt_len": w.L, "V": w.V, "logits_dtype": w.dtype,
+                   "k": w.k, "C": w.C, "m": w.m, "n_gram": [w.n_min, w.n_max], "max_nodes": N, "decode_steps": S,
+                   "prefill_rows": prefill_rows, "tree_rows": tree_rows, "rows_per_step": rows_per_step,
+                   "form": "all decode steps built and verified as one batch of trees"},
+        "roofline": roofline, "cpu_baseline": cpu, "latency": None,
         "tokens_per_decode_step": round(trace.mean_accept_len, 3), "setup_s": round(setup_s, 1),
     }
     print(json.dumps(out))

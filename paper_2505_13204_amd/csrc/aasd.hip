@@ -106,6 +106,42 @@ int launch_sweep(const aasd::SweepParams& p, const SweepPlan& pl, int64_t rows, 
     return AASD_OK;
 }
 
+// Sweep of the first rows_used[seq] rows of every sequence.  One launch covers `block` sequences and has as
+// many workgroups as the GPU holds at once (256 compute units x 2048 threads), or fewer if the rows cannot
+// be that many.
+template <int DT, int BLOCK, int U>
+hipError_t launch_sweep_used_one(const aasd::SweepParams& p, const SweepPlan& pl, int64_t sequences, hipStream_t stream)
+{
+    const int64_t resident = 256 * (2048 / BLOCK);
+    for (int64_t seq0 = 0; seq0 < sequences; seq0 += BLOCK) {
+        const int nseq = (int)(sequences - seq0 < BLOCK ? sequences - seq0 : BLOCK);
+        const int64_t most = (int64_t)nseq * p.rows_per_seq * pl.nseg;
+        const unsigned grid = (unsigned)(most < resident ? most : resident);
+        hipLaunchKernelGGL((aasd::row_sweep_used_kernel<DT, BLOCK, U>), dim3(grid), dim3(BLOCK), 0, stream, p, seq0, nseq);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+template <int DT>
+int launch_sweep_used(const aasd::SweepParams& p, const SweepPlan& pl, int64_t sequences, hipStream_t stream)
+{
+    hipError_t e;
+    if (g_sweep_start) (void)hipEventRecord(g_sweep_start, stream);
+    if (pl.block == 256 && pl.unroll == 4) e = launch_sweep_used_one<DT, 256, 4>(p, pl, sequences, stream);
+    else if (pl.block == 256 && pl.unroll == 2) e = launch_sweep_used_one<DT, 256, 2>(p, pl, sequences, stream);
+    else if (pl.block == 256 && pl.unroll == 1) e = launch_sweep_used_one<DT, 256, 1>(p, pl, sequences, stream);
+    else if (pl.block == 512 && pl.unroll == 4) e = launch_sweep_used_one<DT, 512, 4>(p, pl, sequences, stream);
+    else if (pl.block == 512 && pl.unroll == 2) e = launch_sweep_used_one<DT, 512, 2>(p, pl, sequences, stream);
+    else if (pl.block == 1024 && pl.unroll == 2) e = launch_sweep_used_one<DT, 1024, 2>(p, pl, sequences, stream);
+    else if (pl.block == 1024 && pl.unroll == 1) e = launch_sweep_used_one<DT, 1024, 1>(p, pl, sequences, stream);
+    else return fail(AASD_ERR_UNSUPPORTED, "AASD_SWEEP_CONFIG=%d,%d is not a compiled launch shape", pl.block, pl.unroll);
+    if (g_sweep_stop) (void)hipEventRecord(g_sweep_stop, stream);
+    if (e != hipSuccess) return fail(AASD_ERR_LAUNCH, "row sweep launch failed: %s", hipGetErrorString(e));
+    return AASD_OK;
+}
+
 size_t align16(size_t n) { return (n + 15) & ~(size_t)15; }
 
 }  // namespace
@@ -387,8 +423,7 @@ int aasd_verify_tree(const void* logits, int32_t dt, int32_t B, int32_t N, int32
     sp.logits = logits; sp.V = V; sp.row_stride = row_stride; sp.seq_stride = seq_stride; sp.rows_per_seq = N;
     sp.rows_used = n_nodes;
     sp.c = 1; sp.nseg = pl.nseg; sp.seg_vecs = pl.seg_vecs; sp.partials = (aasd::WavePartial*)workspace;
-    int rc = dt == AASD_BF16 ? launch_sweep<AASD_BF16, false, false>(sp, pl, rows, 0, s)
-                             : launch_sweep<AASD_F32, false, false>(sp, pl, rows, 0, s);
+    int rc = dt == AASD_BF16 ? launch_sweep_used<AASD_BF16>(sp, pl, B, s) : launch_sweep_used<AASD_F32>(sp, pl, B, s);
     if (rc != AASD_OK) return rc;
 
     aasd::VerifyTreeParams tp{};
@@ -400,9 +435,9 @@ int aasd_verify_tree(const void* logits, int32_t dt, int32_t B, int32_t N, int32
     tp.row_entropy = row_entropy; tp.row_pmax = row_pmax; tp.row_argmax = row_argmax;
     tp.partials = (const aasd::WavePartial*)workspace; tp.npart = pl.npart;
     if (dt == AASD_BF16)
-        hipLaunchKernelGGL(aasd::verify_tree_kernel<AASD_BF16>, dim3((unsigned)B), dim3(aasd::kTreeBlock), 0, s, tp);
+        hipLaunchKernelGGL(aasd::verify_tree_kernel<AASD_BF16>, dim3((unsigned)B), dim3(aasd::kVerifyTreeBlock), 0, s, tp);
     else
-        hipLaunchKernelGGL(aasd::verify_tree_kernel<AASD_F32>, dim3((unsigned)B), dim3(aasd::kTreeBlock), 0, s, tp);
+        hipLaunchKernelGGL(aasd::verify_tree_kernel<AASD_F32>, dim3((unsigned)B), dim3(aasd::kVerifyTreeBlock), 0, s, tp);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(AASD_ERR_LAUNCH, "verify_tree launch failed: %s", hipGetErrorString(e));
     return AASD_OK;

@@ -485,18 +485,12 @@ __device__ __forceinline__ bool process_wave(const SweepParams& p, const SegShap
     return true;
 }
 
-// Streaming kernel: grid = rows x segments; every wave writes one WavePartial.
+// One unit of work: segment `seg` of row `row`; every wave writes one WavePartial.
 template <int DT, bool ALIGN, bool COUNT, int BLOCK, int U>
-__global__ __launch_bounds__(BLOCK) void row_sweep_kernel(SweepParams p, int64_t unit0)
+__device__ __forceinline__ void sweep_unit(const SweepParams& p, int64_t row, int seg, SweepShared<BLOCK / kWave>& sh,
+                                           unsigned char* cm)
 {
     constexpr int NW = BLOCK / kWave;
-    extern __shared__ __align__(16) unsigned char cm[];  // chunk maxima of this segment (alignment sampling only)
-    __shared__ SweepShared<ALIGN ? NW : 1> sh_store;
-    SweepShared<NW>& sh = *reinterpret_cast<SweepShared<NW>*>(&sh_store);  // not touched unless ALIGN
-
-    const int64_t unit = unit0 + blockIdx.x;
-    const int64_t row = unit / p.nseg;
-    const int seg = (int)(unit - row * p.nseg);
     const int64_t off = (row / p.rows_per_seq) * p.seq_stride + (row % p.rows_per_seq) * p.row_stride;
     const RowShape row_s = row_shape<DT>(p.logits, off, p.V);
     const SegShape rs = seg_shape<DT>(row_s, p.V, seg, p.nseg, p.seg_vecs);
@@ -506,9 +500,8 @@ __global__ __launch_bounds__(BLOCK) void row_sweep_kernel(SweepParams p, int64_t
     WavePartial* out = p.partials + slot;
     int32_t* out_list = ALIGN ? p.lists + slot * kListCap : nullptr;
 
-    // a wave whose lanes own no element at all, or whose row is not in use, leaves the neutral partial
-    bool owns = tid < rs.head_n || tid < rs.nvec || tid < rs.tail_n;
-    if (p.rows_used && (int)(row % p.rows_per_seq) >= max(p.rows_used[row / p.rows_per_seq], 1)) owns = false;
+    // a wave whose lanes own no element at all leaves the neutral partial
+    const bool owns = tid < rs.head_n || tid < rs.nvec || tid < rs.tail_n;
     if (__ballot(owns) == 0ull) {
         if (lane == 0) {
             WavePartial wp;
@@ -529,6 +522,69 @@ __global__ __launch_bounds__(BLOCK) void row_sweep_kernel(SweepParams p, int64_t
     unsigned char* cm_lane = cm + (size_t)tid * (size_t)p.cm_stride;
     if (!process_wave<DT, ALIGN, COUNT, false, BLOCK, U>(p, rs, has_next, znext, sh, cm_lane, row_s, out, out_list))
         process_wave<DT, ALIGN, COUNT, true, BLOCK, U>(p, rs, has_next, znext, sh, cm_lane, row_s, out, out_list);
+}
+
+// Streaming kernel: grid = rows x segments.
+template <int DT, bool ALIGN, bool COUNT, int BLOCK, int U>
+__global__ __launch_bounds__(BLOCK) void row_sweep_kernel(SweepParams p, int64_t unit0)
+{
+    constexpr int NW = BLOCK / kWave;
+    extern __shared__ __align__(16) unsigned char cm[];  // chunk maxima of this segment (alignment sampling only)
+    __shared__ SweepShared<ALIGN ? NW : 1> sh_store;
+    SweepShared<NW>& sh = *reinterpret_cast<SweepShared<NW>*>(&sh_store);  // not touched unless ALIGN
+
+    const int64_t unit = unit0 + blockIdx.x;
+    const int64_t row = unit / p.nseg;
+    sweep_unit<DT, ALIGN, COUNT, BLOCK, U>(p, row, (int)(unit - row * p.nseg), sh, cm);
+}
+
+// The same sweep for sequences that use only their first max(rows_used[seq], 1) rows (tree verification).
+// The launch covers at most BLOCK sequences.  Every workgroup first scans their row counts into LDS, which
+// numbers the used rows consecutively; the workgroups then share those rows x segments round robin, so the
+// work is spread evenly however uneven the sequences are.  Rows that are not in use are neither read nor
+// given partials.  The grid is sized to the machine, not to the input: a workgroup whose first unit lies
+// beyond the total ends at once.
+template <int DT, int BLOCK, int U>
+__global__ __launch_bounds__(BLOCK) void row_sweep_used_kernel(SweepParams p, int64_t seq0, int nseq)
+{
+    constexpr int NW = BLOCK / kWave;
+    __shared__ SweepShared<1> sh_store;
+    SweepShared<NW>& sh = *reinterpret_cast<SweepShared<NW>*>(&sh_store);  // never touched: no alignment sampling here
+    __shared__ int offs[BLOCK + 1];   // offs[s] = used rows of the sequences before s
+    __shared__ int wave_total[NW];
+
+    const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
+    int v = 0;
+    if (tid < nseq) {
+        v = p.rows_used[seq0 + tid];
+        v = v < 1 ? 1 : (v > p.rows_per_seq ? p.rows_per_seq : v);
+    }
+    int incl = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int up = __shfl_up(incl, o);
+        if (lane >= o) incl += up;
+    }
+    if (lane == 63) wave_total[wid] = incl;
+    __syncthreads();
+    int before = 0;
+#pragma unroll
+    for (int w2 = 0; w2 < NW; ++w2) before += (w2 < wid) ? wave_total[w2] : 0;
+    offs[tid + 1] = before + incl;
+    if (tid == 0) offs[0] = 0;
+    __syncthreads();
+
+    const int units = offs[nseq] * p.nseg;
+    for (int unit = blockIdx.x; unit < units; unit += gridDim.x) {
+        const int crow = unit / p.nseg;
+        int lo = 0, hi = nseq;   // the sequence s with offs[s] <= crow < offs[s + 1]
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (offs[mid] <= crow) lo = mid; else hi = mid;
+        }
+        const int64_t row = (seq0 + lo) * p.rows_per_seq + (crow - offs[lo]);
+        sweep_unit<DT, false, false, BLOCK, U>(p, row, unit - crow * p.nseg, sh, nullptr);
+    }
 }
 
 }  // namespace aasd

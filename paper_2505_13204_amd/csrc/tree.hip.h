@@ -27,39 +27,56 @@ struct BuildTreeParams {
     int32_t* cand_node;           // [B, C, k] or null
 };
 
-// One workgroup per sequence.  The tree grows layer by layer.  In layer j every (candidate, slot)
-// pair is an event (slot 0 = the candidate's j-th token, slots 1..m = its extras) with the key
-// (node at the end of the candidate's path, token).  An event whose key no earlier event of the
-// layer has opens a node; nodes are numbered in event order by a ballot/popcount prefix, which
-// is exactly the order a serial insertion into a (parent, token) dictionary would give.
+// One workgroup per sequence.  The candidates, their flags and their extras are first staged in LDS in one
+// coalesced pass, so that the layer loop touches no global memory.  The tree grows layer by layer.  In layer j
+// every (candidate, slot) pair is an event (slot 0 = the candidate's j-th token, slots 1..m = its extras) with
+// the key (node at the end of the candidate's path, token).  An event whose key no earlier event of the
+// layer has opens a node; nodes are numbered in event order by a ballot/popcount prefix, which is exactly
+// the order a serial insertion into a (parent, token) dictionary would give.  The mask row of a new node is
+// its parent's row plus its own bit.
 __global__ __launch_bounds__(kTreeBlock) void build_tree_kernel(BuildTreeParams p)
 {
-    __shared__ int ev_par[kMaxLayerEvents], ev_tok[kMaxLayerEvents], ev_node[kMaxLayerEvents];
-    __shared__ unsigned char ev_valid[kMaxLayerEvents], ev_flag[kMaxLayerEvents];
+    constexpr int kMaxW = AASD_MAX_TREE_NODES / 32;
+    constexpr int kMaxCK = AASD_MAX_CANDIDATES * AASD_MAX_DRAFT;
+    __shared__ int s_tok[kMaxCK];                       // drafts of this sequence
+    __shared__ int s_x[kMaxCK * AASD_MAX_EXTRAS];       // their extras
+    __shared__ unsigned char s_strict[kMaxCK];
+    __shared__ int s_cn[kMaxCK];                        // node of every candidate token
+    __shared__ int s_dl[AASD_MAX_CANDIDATES];
+    __shared__ unsigned long long ev_key[kMaxLayerEvents];   // (parent + 1, token); events without a token get a key of their own
+    __shared__ int ev_node[kMaxLayerEvents];
+    __shared__ unsigned char ev_flag[kMaxLayerEvents];
     __shared__ int cur[AASD_MAX_CANDIDATES];
     __shared__ int n_tok[AASD_MAX_TREE_NODES], n_par[AASD_MAX_TREE_NODES], n_dep[AASD_MAX_TREE_NODES];
     __shared__ unsigned char n_str[AASD_MAX_TREE_NODES];
+    __shared__ uint32_t n_mask[AASD_MAX_TREE_NODES * kMaxW];
     __shared__ int wave_cnt[kTreeBlock / kWave];
 
     const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
     const int C = p.C, k = p.k, m = p.draft_extras ? p.m_x : 0, N = p.max_nodes;
-    const int per = 1 + m, E = C * per;
-    const int e = tid, c = e / per, slot = e - c * per;
-    const size_t bc = (size_t)b * C + (e < E ? c : 0);
+    const int W = (N + 31) / 32;
+    const int per = 1 + m, E = C * per, CK = C * k;
+    const int e = tid, c = e < E ? e / per : 0, slot = e - (e / per) * per;
+    const size_t bck = (size_t)b * CK;
 
-    if (tid < C) cur[tid] = 0;
+    for (int i = tid; i < CK; i += kTreeBlock) {
+        s_tok[i] = p.drafts[bck + i];
+        s_strict[i] = p.strict ? (p.strict[bck + i] != 0) : 0;
+        s_cn[i] = -1;
+    }
+    for (int i = tid; i < CK * m; i += kTreeBlock) s_x[i] = p.draft_extras[bck * m + i];
+    if (tid < C) {
+        int dl = p.draft_len[(size_t)b * C + tid];
+        s_dl[tid] = dl < 0 ? 0 : (dl > k ? k : dl);
+        cur[tid] = 0;
+    }
     if (tid == 0) {
         n_tok[0] = p.root_tok ? p.root_tok[b] : -1;
         n_par[0] = -1; n_dep[0] = 0; n_str[0] = 0;
     }
-    if (p.cand_node)
-        for (int i = tid; i < C * k; i += kTreeBlock) p.cand_node[(size_t)b * C * k + i] = -1;
-    int dl = 0;
-    if (e < E) {
-        dl = p.draft_len[bc];
-        dl = dl < 0 ? 0 : (dl > k ? k : dl);
-    }
+    if (tid < W) n_mask[tid] = tid == 0 ? 1u : 0u;   // the root sees itself
     __syncthreads();
+    const int dl = e < E ? s_dl[c] : 0;
 
     int n = 1;  // nodes so far: the same value in every thread
     for (int j = 1; j <= k; ++j) {
@@ -68,24 +85,28 @@ __global__ __launch_bounds__(kTreeBlock) void build_tree_kernel(BuildTreeParams 
         if (e < E) {
             par = cur[c];
             if (par >= 0 && j <= dl) {
-                const int main_tok = p.drafts[bc * k + (j - 1)];
+                const int at = c * k + (j - 1);
+                const int main_tok = s_tok[at];
                 if (main_tok >= 0) {  // a missing token ends the candidate's path, extras included
                     if (slot == 0) {
                         tok = main_tok; valid = true;
-                        st = p.strict ? (p.strict[bc * k + (j - 1)] != 0) : 0;
+                        st = s_strict[at];
                     } else {
-                        const int x = p.draft_extras[(bc * k + (j - 1)) * m + (slot - 1)];
+                        const int x = s_x[at * m + (slot - 1)];
                         if (x >= 0) { tok = x; valid = true; }  // extras are verified conditionally
                     }
                 }
             }
-            ev_par[e] = par; ev_tok[e] = tok; ev_valid[e] = valid; ev_flag[e] = (unsigned char)st;
+            ev_key[e] = valid ? ((unsigned long long)(unsigned)(par + 1) << 32) | (unsigned)tok
+                              : ((unsigned long long)(0x10000u + (unsigned)e) << 32);
+            ev_flag[e] = (unsigned char)st;
         }
         __syncthreads();
-        int rep = e;  // earliest event of the layer with the same key
+        int rep = e;  // earliest event of the layer with the same key (the loads do not depend on one another)
         if (valid) {
-            for (int e2 = 0; e2 < e; ++e2)
-                if (ev_valid[e2] && ev_par[e2] == par && ev_tok[e2] == tok) { rep = e2; break; }
+            const unsigned long long key = ev_key[e];
+            for (int e2 = 0; e2 < E; ++e2)
+                if (ev_key[e2] == key && e2 < rep) rep = e2;
         }
         const bool first = valid && rep == e;
         const unsigned long long bal = __ballot(first);
@@ -102,7 +123,11 @@ __global__ __launch_bounds__(kTreeBlock) void build_tree_kernel(BuildTreeParams 
         if (first) {
             id = offset + before < N ? offset + before : -1;  // beyond the node budget: dropped
             ev_node[e] = id;
-            if (id >= 0) { n_tok[id] = tok; n_par[id] = par; n_dep[id] = j; }
+            if (id >= 0) {
+                n_tok[id] = tok; n_par[id] = par; n_dep[id] = j;
+                for (int wi = 0; wi < W; ++wi)   // the parent's row (an earlier layer) plus the node's own bit
+                    n_mask[id * W + wi] = n_mask[par * W + wi] | ((id >> 5) == wi ? 1u << (id & 31) : 0u);
+            }
         }
         __syncthreads();
         if (valid && !first && st == 0) ev_flag[rep] = 0;  // one conditional source makes the node conditional
@@ -111,14 +136,13 @@ __global__ __launch_bounds__(kTreeBlock) void build_tree_kernel(BuildTreeParams 
         if (e < E && slot == 0) {
             const int nid = valid ? ev_node[rep] : -1;
             cur[c] = nid;
-            if (valid && p.cand_node) p.cand_node[bc * k + (j - 1)] = nid;
+            if (valid) s_cn[c * k + (j - 1)] = nid;
         }
         n = n + total < N ? n + total : N;
         __syncthreads();
     }
 
     if (tid == 0) p.n_nodes[b] = n;
-    const int W = (N + 31) / 32;
     for (int i = tid; i < N; i += kTreeBlock) {
         const size_t bi = (size_t)b * N + i;
         const bool used = i < n;
@@ -126,15 +150,11 @@ __global__ __launch_bounds__(kTreeBlock) void build_tree_kernel(BuildTreeParams 
         p.node_parent[bi] = used ? n_par[i] : -1;
         p.node_depth[bi] = used ? n_dep[i] : 0;
         p.node_strict[bi] = used ? n_str[i] : 0;
-        if (p.mask) {
-            for (int wi = 0; wi < W; ++wi) {  // tree attention mask: the node and its ancestors
-                uint32_t word = 0;
-                for (int a = used ? i : -1; a >= 0; a = n_par[a])
-                    if ((a >> 5) == wi) word |= 1u << (a & 31);
-                p.mask[bi * W + wi] = word;
-            }
-        }
     }
+    if (p.mask)
+        for (int i = tid; i < N * W; i += kTreeBlock) p.mask[(size_t)b * N * W + i] = i < n * W ? n_mask[i] : 0u;
+    if (p.cand_node)
+        for (int i = tid; i < CK; i += kTreeBlock) p.cand_node[bck + i] = s_cn[i];
 }
 
 struct VerifyTreeParams {
@@ -163,29 +183,37 @@ struct VerifyTreeParams {
 
 // One workgroup per sequence, a thread per node.  Node i is decided against the row of its parent
 // (Eq. 4-6); it is accepted iff it and all its ancestors pass; the deepest accepted node wins.
+constexpr int kVerifyTreeBlock = 1024;  // many lanes so that the partials of a large tree arrive in few rounds of loads
+
 template <int DT>
-__global__ __launch_bounds__(kTreeBlock) void verify_tree_kernel(VerifyTreeParams p)
+__global__ __launch_bounds__(kVerifyTreeBlock) void verify_tree_kernel(VerifyTreeParams p)
 {
     __shared__ float4 stats[AASD_MAX_TREE_NODES];  // per row {max logit, S, H, bits of argmax}
     __shared__ int par_s[AASD_MAX_TREE_NODES];
     __shared__ unsigned char pass_s[AASD_MAX_TREE_NODES];
-    __shared__ unsigned red_key[kTreeBlock / kWave], red_near[kTreeBlock / kWave];
+    __shared__ unsigned red_key[kVerifyTreeBlock / kWave], red_near[kVerifyTreeBlock / kWave];
 
     const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
     const int N = p.N;
     int n = p.n_nodes[b];
     n = n < 1 ? 1 : (n > N ? N : n);
+    for (int r = n + tid; r < N; r += kVerifyTreeBlock) {   // rows that are not in use
+        const int64_t row = (int64_t)b * N + r;
+        if (p.row_entropy) p.row_entropy[row] = 0.f;
+        if (p.row_pmax) p.row_pmax[row] = 0.f;
+        if (p.row_argmax) p.row_argmax[row] = -1;
+    }
 
     // ---- statistics of the used rows from the sweep's partials: G lanes per row ----
     {
         int G = 1;
         while (G < p.npart) G <<= 1;
-        const int rows_per_pass = kTreeBlock / G;
+        const int rows_per_pass = kVerifyTreeBlock / G;
         const int sub = tid / G, s = tid - sub * G;
-        for (int r0 = 0; r0 < N; r0 += rows_per_pass) {
+        for (int r0 = 0; r0 < n; r0 += rows_per_pass) {
             const int r = r0 + sub;
             const bool have_row = r < n;
-            const int64_t row = (int64_t)b * N + (r < N ? r : 0);
+            const int64_t row = (int64_t)b * N + (have_row ? r : 0);
             WavePartial wp;
             wp.m = -INFINITY; wp.S = 0.f; wp.T = 0.f; wp.code = 0x7fffffff;
             if (have_row && s < p.npart) wp = p.partials[row * p.npart + s];
@@ -202,10 +230,10 @@ __global__ __launch_bounds__(kTreeBlock) void verify_tree_kernel(VerifyTreeParam
                 T2 += __shfl_xor(T2, o);
                 code = min(code, __shfl_xor(code, o));
             }
-            if (r < N && s == 0) {
+            if (have_row && s == 0) {
                 float H = 0.f, pmax = 0.f;
                 int am = -1;
-                if (have_row) {
+                {
                     const RowShape rs = row_shape<DT>(p.logits, (int64_t)b * p.seq_stride + (int64_t)r * p.row_stride, p.V);
                     am = 0;
                     if ((unsigned)code < (unsigned)p.V) {
@@ -290,7 +318,7 @@ __global__ __launch_bounds__(kTreeBlock) void verify_tree_kernel(VerifyTreeParam
     __syncthreads();
     if (tid == 0) {
         unsigned best_key = 0, near_total = 0;
-        for (int w = 0; w < kTreeBlock / kWave; ++w) { best_key = max(best_key, red_key[w]); near_total += red_near[w]; }
+        for (int w = 0; w < kVerifyTreeBlock / kWave; ++w) { best_key = max(best_key, red_key[w]); near_total += red_near[w]; }
         const int best = best_key ? (int)(0xffff - (best_key & 0xffff)) : 0;
         const int best_depth = (int)(best_key >> 16);
         p.accept_len[b] = best_depth;

@@ -46,6 +46,16 @@ class Backend:
     def verify(self, logits, drafts: np.ndarray, draft_len: np.ndarray, strict: np.ndarray, w: synth.Workload) -> dict:
         raise NotImplementedError
 
+    # ---- draft-tree path (Sec. 3.2): only needed by decode_tree
+    def build_tree(self, retrieved: dict, root_tok: np.ndarray, max_nodes: int) -> dict:
+        raise NotImplementedError
+
+    def make_tree_logits(self, w: synth.Workload, step: int, gs, length, tree: dict):
+        raise NotImplementedError
+
+    def verify_tree(self, logits, tree: dict, w: synth.Workload) -> dict:
+        raise NotImplementedError
+
 
 def decode(w: synth.Workload, backend: Backend, steps: Optional[int] = None, peaked: bool = False,
            extras=None, n_extras=None, keep_logits: bool = False,
@@ -73,6 +83,42 @@ def decode(w: synth.Workload, backend: Backend, steps: Optional[int] = None, pea
             a, c = int(v["accept_len"][b]), int(v["best_cand"][b])
             n = int(length[b])
             tokens[b, n:n + a] = r["drafts"][b, c, :a]
+            tokens[b, n + a] = v["next_token"][b]
+            length[b] = n + a + 1
+    trace.length = length
+    return trace
+
+
+def decode_tree(w: synth.Workload, backend: Backend, streams, extras, n_extras, steps: Optional[int] = None,
+                max_nodes: int = 64, keep_logits: bool = False,
+                on_step: Optional[Callable[[int, StepRecord], None]] = None) -> DecodeTrace:
+    """The same loop with the candidates and their alignment extras merged into a draft tree
+    (Sec. 3.2, Eq. 2): retrieve, build the tree, obtain one row per node, verify the tree, append
+    the accepted path and the next token.  `streams` = [synth.tree_stream(w, b) for b]; extras and
+    n_extras are the alignment-sampling outputs of the prefill rows ([B*L, m], [B*L])."""
+    steps = w.steps if steps is None else steps
+    gs = [s[0] for s in streams]
+    tokens = np.zeros((w.B, w.tok_cap), dtype=np.int32)
+    for b in range(w.B):
+        tokens[b, :w.L] = gs[b][:w.L]
+    length = np.full(w.B, w.L, dtype=np.int32)
+    prompt_len = np.full(w.B, w.L, dtype=np.int32)
+    trace = DecodeTrace(tokens=tokens, length=length)
+    for step in range(steps):
+        r = backend.retrieve(tokens, length, prompt_len, w, extras, n_extras)
+        root = tokens[np.arange(w.B), length - 1].copy()
+        t = backend.build_tree(r, root, max_nodes)
+        logits = backend.make_tree_logits(w, step, gs, length, t)
+        v = backend.verify_tree(logits, t, w)
+        rec = StepRecord(length=length.copy(), retrieved={**r, "tree": t}, verified=v,
+                         logits=logits if keep_logits else None)
+        trace.steps.append(rec)
+        if on_step is not None:
+            on_step(step, rec)
+        for b in range(w.B):
+            a, n = int(v["accept_len"][b]), int(length[b])
+            path = v["accept_path"][b, :a]
+            tokens[b, n:n + a] = t["node_token"][b, path]
             tokens[b, n + a] = v["next_token"][b]
             length[b] = n + a + 1
     trace.length = length

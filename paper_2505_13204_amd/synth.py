@@ -39,6 +39,8 @@ class Workload:
     alpha: float = 0.1     # Sec. 4.1: 0.1 (LLaMA-3.1), 0.2 (Qwen-2.5)
     beta: float = 0.1
     seed: int = 0
+    mis_rate: float = 0.3  # draft-tree workloads: fraction of misaligned prompt positions (Sec. 2.3 reports about 45 %
+                           # of the retrieved tokens; 0.3 of all positions gives a comparable share of the drafts)
 
     @property
     def R(self) -> int:
@@ -70,6 +72,11 @@ WORKLOADS = {
                                 q=0.6, q_copy=0.8, n_min=3, n_max=3, k=8, C=1, steps=256, coverage=0.30),
     "stress_tree": Workload("stress_tree", B=64, L=4096, V=152064, dtype="bf16", sigma2=1.0, bump=0.0, q=0.0,
                             q_copy=0.0, n_min=2, n_max=4, k=8, C=16, steps=128, coverage=0.50, motifs=8, alpha=0.2),
+    # Draft-tree form of the path (Sec. 3.2): the same model shapes, prompts made by tree_stream.
+    "tree_single": Workload("tree_single", B=1, L=2048, V=128256, dtype="bf16", sigma2=3.0, bump=0.0, q=0.0, q_copy=0.0,
+                            n_min=1, n_max=3, k=8, C=4, steps=256, coverage=0.80),
+    "tree_batch": Workload("tree_batch", B=64, L=4096, V=152064, dtype="bf16", sigma2=1.0, bump=0.0, q=0.0, q_copy=0.0,
+                           n_min=1, n_max=4, k=8, C=16, steps=64, coverage=0.80, motifs=8, alpha=0.2),
 }
 
 
@@ -137,11 +144,13 @@ def _generator(device, *key) -> torch.Generator:
 
 
 def logits_rows(w: Workload, targets: torch.Tensor, q: torch.Tensor, gen: torch.Generator, device,
-                peaked: bool = False, out: Optional[torch.Tensor] = None, chunk: int = 512) -> torch.Tensor:
+                peaked: bool = False, out: Optional[torch.Tensor] = None, chunk: int = 512,
+                slot: Optional[torch.Tensor] = None, lead: Optional[torch.Tensor] = None) -> torch.Tensor:
     """[n, V] logits: i.i.d. N(0, sigma2) noise, plus `bump` on targets[i] with probability q[i]
     (targets[i] < 0: no peak).  peaked=True instead plants LLM-like rows: four tokens at logits 24, 23,
     22, 21 (probabilities about 0.64, 0.24, 0.09, 0.03), the target being the first, second or third
-    of them with probability 0.80 / 0.14 / 0.06."""
+    of them with probability 0.80 / 0.14 / 0.06.  slot[i] in {0, 1, 2} fixes the target's rank instead of
+    drawing it, and lead[i] >= 0 names the best of the other three tokens (the row's top token when slot > 0)."""
     n = targets.numel()
     targets = targets.to(device=device, dtype=torch.long)
     q = q.to(device=device, dtype=torch.float32)
@@ -159,14 +168,19 @@ def logits_rows(w: Workload, targets: torch.Tensor, q: torch.Tensor, gen: torch.
             # probability 0.80, the runner-up with 0.14, the third with 0.06
             others = torch.randint(0, w.V, (hi - lo, 3), generator=gen, device=device)
             place = torch.rand(hi - lo, generator=gen, device=device)
-            slot = (place >= 0.80).long() + (place >= 0.94).long()  # 0, 1 or 2: rank of the target
+            slot_c = (place >= 0.80).long() + (place >= 0.94).long()  # 0, 1 or 2: rank of the target
+            if slot is not None:
+                slot_c = slot[lo:hi].to(device=device, dtype=torch.long)
+            if lead is not None:
+                ld = lead[lo:hi].to(device=device, dtype=torch.long)
+                others[:, 0] = torch.where(ld >= 0, ld, others[:, 0])
             levels = torch.tensor([24.0, 23.0, 22.0, 21.0], device=device)
             r = rows[has]
             for i in range(3):
                 # the i-th other token takes the i-th level that the target does not occupy
-                lvl = levels[(i + (i >= slot[has]).long())]
+                lvl = levels[(i + (i >= slot_c[has]).long())]
                 z[r, others[has, i]] = lvl
-            z[r, t[has]] = levels[slot[has]]
+            z[r, t[has]] = levels[slot_c[has]]
         else:
             hit = has & (torch.rand(hi - lo, generator=gen, device=device) < q[lo:hi])
             z[rows[hit], t[hit]] += w.bump
@@ -222,6 +236,104 @@ def verify_logits(w: Workload, step: int, gs, copieds, lengths, drafts, draft_le
     flat = None if out is None else out.view(w.B * w.R, w.V)
     z = logits_rows(w, targets, q, gen, device, peaked=peaked, out=flat)
     return z.view(w.B, w.R, w.V)
+
+
+# --------------------------------------------------------------------------- draft-tree workloads
+def tree_stream(w: Workload, b: int):
+    """Token stream for the draft-tree path (Sec. 3.2): returns (g, alt, slot).
+    g[:L] is the prompt and alt[i] the token the synthetic model prefers at prompt position i: g[i] itself
+    (aligned, slot[i] = 0) or another token, the prompt token being the model's second or third choice
+    (misaligned, slot[i] = 1 or 2; Sec. 2.3).  The continuation g[L:] repeats prompt material in the
+    model's wording (alt), covering w.coverage of it, with novel tokens in between.
+    w.motifs = 0: random prompt, a fraction w.mis_rate of its positions misaligned; the continuation copies
+    prompt segments of 8..24 tokens.
+    w.motifs > 0: the prompt holds instances of w.motifs 12-token motifs, each token of an instance
+    replaced with probability 0.1, so that one key has many occurrences whose continuations share prefixes
+    and then part; the model's wording of a motif differs from it at a fraction w.mis_rate of its offsets,
+    the same ones in every instance; the continuation strings motifs in the model's wording together."""
+    rng = np.random.default_rng([w.seed, b, 0x7EE])
+    n = w.stream_len
+    g = rng.integers(0, w.V, size=n, dtype=np.int64).astype(np.int32)
+    alt = g.copy()
+    rand_tokens = lambda k: rng.integers(0, w.V, size=k, dtype=np.int64).astype(np.int32)
+    if w.motifs > 0:
+        pool = rand_tokens(w.motifs * 12).reshape(w.motifs, 12)
+        wording = pool.copy()
+        differs = rng.random((w.motifs, 12)) < w.mis_rate
+        wording[differs] = rand_tokens(int(differs.sum()))
+        for pos in range(1, w.L - 12, 12):
+            if rng.random() < w.coverage:
+                mid = int(rng.integers(0, w.motifs))
+                inst = pool[mid].copy()
+                change = rng.random(12) < 0.1
+                inst[change] = rand_tokens(int(change.sum()))
+                g[pos:pos + 12] = inst
+                alt[pos:pos + 12] = wording[mid]
+        pos = w.L + 2
+        while pos + 12 <= n:
+            if rng.random() < w.coverage:
+                g[pos:pos + 12] = wording[int(rng.integers(0, w.motifs))]
+            pos += 12
+    else:
+        mis = rng.random(w.L) < w.mis_rate
+        mis[0] = False
+        alt[:w.L][mis] = rand_tokens(int(mis.sum()))
+        pos = w.L + 2
+        while pos < n:
+            ln = min(int(rng.integers(8, 25)), n - pos)
+            if rng.random() < w.coverage and w.L > ln + 2:
+                s0 = int(rng.integers(1, w.L - ln))
+                g[pos:pos + ln] = alt[s0:s0 + ln]
+            pos += ln
+    alt[0] = g[0]
+    alt[w.L:] = g[w.L:]
+    slot = np.where(alt != g, 1 + (rng.random(n) < 0.5), 0).astype(np.int64)
+    return g, alt, slot
+
+
+def tree_prefill_logits(w: Workload, b: int, g: np.ndarray, alt: np.ndarray, slot: np.ndarray, device,
+                        out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Prefill logits for tree_stream: row i predicts position i+1; the prompt token g[i+1] sits at rank
+    slot[i+1] and, where it is not the top one, the row's top token is alt[i+1]."""
+    idx = np.arange(w.L)
+    nxt = np.minimum(idx + 1, w.L - 1)
+    targets = torch.from_numpy(g[nxt].astype(np.int64))
+    sl = torch.from_numpy(slot[nxt])
+    lead = torch.from_numpy(np.where(slot[nxt] > 0, alt[nxt], -1).astype(np.int64))
+    gen = _generator(device, w.seed, b, 5)
+    return logits_rows(w, targets, torch.zeros(w.L), gen, device, peaked=True, out=out, slot=sl, lead=lead)
+
+
+def tree_verify_targets(g: np.ndarray, length: int, node_token: np.ndarray, node_parent: np.ndarray,
+                        node_depth: np.ndarray, n_nodes: int) -> np.ndarray:
+    """Target token of every tree row of one sequence: the row of a node whose path from the root has
+    followed the stream g predicts the stream's next token; any other row gets no peak (-1)."""
+    N = node_token.shape[0]
+    tg = np.full(N, -1, dtype=np.int64)
+    on = np.zeros(N, dtype=bool)
+    on[0] = True
+    tg[0] = g[length]
+    for i in range(1, n_nodes):
+        pa, d = int(node_parent[i]), int(node_depth[i])
+        on[i] = 0 <= pa < i and on[pa] and node_token[i] == g[length + d - 1]
+        if on[i]:
+            tg[i] = g[length + d]
+    return tg
+
+
+def tree_verify_logits(w: Workload, step: int, gs, lengths, tree: dict, device,
+                       out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """[B, N, V] logits of one tree-verification step; rows at or beyond n_nodes hold noise."""
+    B, N = tree["node_token"].shape
+    tg = [tree_verify_targets(gs[b], int(lengths[b]), tree["node_token"][b], tree["node_parent"][b],
+                              tree["node_depth"][b], int(tree["n_nodes"][b])) for b in range(B)]
+    targets = torch.from_numpy(np.concatenate(tg))
+    gen = _generator(device, w.seed, step, 6)
+    place = torch.rand(B * N, generator=gen, device=device)
+    slot = (place >= 0.90).long() + (place >= 0.97).long()   # the stream's token leads the row 9 times in 10
+    flat = None if out is None else out.view(B * N, w.V)
+    z = logits_rows(w, targets, torch.zeros(B * N), gen, device, peaked=True, out=flat, slot=slot)
+    return z.view(B, N, w.V)
 
 
 # --------------------------------------------------------------------------- host copies for the oracle

@@ -112,6 +112,38 @@ def compare_verify(got: dict, ref: dict, tally: Tally):
         assert ok[same].all()
 
 
+def compare_tree(got: dict, ref: dict):
+    for name in ("n_nodes", "node_token", "node_parent", "node_depth", "node_strict", "cand_node", "mask"):
+        np.testing.assert_array_equal(got[name], ref[name], err_msg=name)
+
+
+def compare_verify_tree(got: dict, ref: dict, tally: Tally):
+    np.testing.assert_array_equal(got["row_argmax"], ref["row_argmax"])
+    e_h = rel_err(got["row_entropy"], ref["row_entropy"], H_FLOOR)
+    e_p = rel_err(got["row_pmax"], ref["row_pmax"], P_FLOOR)
+    e_np = rel_err(got["node_p"], ref["node_p"], P_FLOOR)
+    e_nd = rel_err(got["node_delta"], ref["node_delta"], P_FLOOR)
+    for name, e in (("row entropy", e_h), ("row p_max", e_p), ("node p", e_np), ("node delta", e_nd)):
+        assert e.max(initial=0.0) <= REL_TOL, f"{name} rel err {e.max():.3e}"
+    tally.max_rel_h = max(tally.max_rel_h, float(e_h.max(initial=0.0)))
+    tally.max_rel_p = max(tally.max_rel_p, float(max(e_p.max(initial=0.0), e_np.max(initial=0.0), e_nd.max(initial=0.0))))
+    tally.rows += int((ref["row_argmax"] >= 0).sum())
+    ev = ref["node_margin"] >= 0                     # nodes that were evaluated: all ancestors accepted
+    tally.tokens += int(ev.sum())
+    B = len(ref["accept_len"])
+    near = (np.where(ev, ref["node_margin"], np.inf).reshape(B, -1).min(axis=1)) < NEAR
+    tally.near_decisions += int((ev & (ref["node_margin"] < NEAR)).sum())
+    same = ((got["accept_len"] == ref["accept_len"]) & (got["best_node"] == ref["best_node"])
+            & (got["next_token"] == ref["next_token"]) & (got["accept_path"] == ref["accept_path"]).all(axis=1))
+    assert same[~near].all(), f"tree decisions differ at sequences {np.nonzero(~same & ~near)[0][:8]}"
+    tally.near_disagreements += int((~same & near).sum())
+    if got.get("near_count") is not None:
+        lo = (ev & (ref["node_margin"] < 0.5 * NEAR)).reshape(B, -1).sum(axis=1)
+        hi = (ev & (ref["node_margin"] < 2.0 * NEAR)).reshape(B, -1).sum(axis=1)
+        ok = (got["near_count"] >= lo) & (got["near_count"] <= hi)
+        assert ok[same].all()
+
+
 # --------------------------------------------------------------------------- host/device helpers
 def to_np(d: dict) -> dict:
     return {k: (v.cpu().numpy() if isinstance(v, torch.Tensor) else v) for k, v in d.items() if k != "workspace"}
@@ -147,6 +179,18 @@ class OracleBackend(harness.Backend):
         return oracle.verify(logits, drafts, draft_len, strict, alpha=f32(w.alpha), beta=f32(w.beta))
 
 
+    def build_tree(self, r, root_tok, max_nodes):
+        return oracle.build_tree(r["drafts"], r["draft_len"], r["strict"], r.get("draft_extras"), root_tok=root_tok,
+                                 max_nodes=max_nodes)
+
+    def make_tree_logits(self, w, step, gs, length, tree):
+        return synth.to_host_bits(synth.tree_verify_logits(w, step, gs, length, tree, self.device))
+
+    def verify_tree(self, logits, tree, w):
+        return oracle.verify_tree(logits, tree["node_token"], tree["node_parent"], tree["node_strict"], tree["n_nodes"],
+                                  alpha=f32(w.alpha), beta=f32(w.beta))
+
+
 class HipBackend(harness.Backend):
     def __init__(self, device="cuda:0"):
         self.device = torch.device(device)
@@ -175,6 +219,27 @@ class HipBackend(harness.Backend):
         return to_np(out)
 
 
+    def build_tree(self, r, root_tok, max_nodes):
+        dx = r.get("draft_extras")
+        out = aasd.build_tree(self._dev(r["drafts"], torch.int32), self._dev(r["draft_len"], torch.int32),
+                              self._dev(r["strict"], torch.uint8), None if dx is None else self._dev(dx, torch.int32),
+                              self._dev(root_tok, torch.int32), max_nodes=max_nodes)
+        torch.cuda.synchronize()
+        t = to_np(out)
+        t["mask"] = t["mask"].view(np.uint32)
+        return t
+
+    def make_tree_logits(self, w, step, gs, length, tree):
+        return synth.tree_verify_logits(w, step, gs, length, tree, self.device)
+
+    def verify_tree(self, logits, tree, w):
+        out = aasd.verify_tree(logits, self._dev(tree["node_token"], torch.int32), self._dev(tree["node_parent"], torch.int32),
+                               self._dev(tree["n_nodes"], torch.int32), self._dev(tree["node_strict"], torch.uint8),
+                               alpha=w.alpha, beta=w.beta)
+        torch.cuda.synchronize()
+        return to_np(out)
+
+
 class ParityBackend(harness.Backend):
     """Runs both, asserts parity on every call, returns the oracle's results."""
 
@@ -198,4 +263,21 @@ class ParityBackend(harness.Backend):
         ref = self.orc.verify(bits, drafts, draft_len, strict, w)
         got = self.hip.verify(dev, drafts, draft_len, strict, w)
         compare_verify(got, ref, self.tally)
+        return ref
+
+    def build_tree(self, r, root_tok, max_nodes):
+        ref = self.orc.build_tree(r, root_tok, max_nodes)
+        got = self.hip.build_tree(r, root_tok, max_nodes)
+        compare_tree(got, ref)
+        return ref
+
+    def make_tree_logits(self, w, step, gs, length, tree):
+        dev = self.hip.make_tree_logits(w, step, gs, length, tree)
+        return dev, synth.to_host_bits(dev)
+
+    def verify_tree(self, logits, tree, w):
+        dev, bits = logits
+        ref = self.orc.verify_tree(bits, tree, w)
+        got = self.hip.verify_tree(dev, tree, w)
+        compare_verify_tree(got, ref, self.tally)
         return ref

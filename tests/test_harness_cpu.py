@@ -2,6 +2,8 @@
 import numpy as np
 import torch
 
+import oracle
+
 from paper_2505_13204_amd import harness, synth
 from tests import backends as bk
 
@@ -52,3 +54,33 @@ def test_decode_driver_with_oracle_backend():
     tr = harness.decode(batched, bk.OracleBackend(), peaked=True)
     assert tr.steps[0].retrieved["drafts"].shape == (3, 16, 8)
     assert any((s.retrieved["n_cand"] > 1).any() for s in tr.steps)
+
+
+def test_tree_decode_on_the_oracle_gains_from_alignment_extras():
+    """The draft-tree loop end to end on the CPU oracle: prefill alignment sampling finds the model's own
+    wording at the misaligned prompt positions, and the tree that carries those extras commits more tokens
+    per step than the tree without them (the effect Sec. 3.2 is after)."""
+    w = synth.scaled(synth.WORKLOADS["llama3_single"], B=2, L=400, V=3000, steps=30, n_min=1, n_max=3, C=4, k=6,
+                     coverage=0.9)
+    streams = [synth.tree_stream(w, b) for b in range(w.B)]
+    ex, nx = [], []
+    for b in range(w.B):
+        g, alt, slot = streams[b]
+        z = synth.tree_prefill_logits(w, b, g, alt, slot, "cpu")
+        out = oracle.align_sample(synth.to_host_bits(z), synth.next_tokens(w, g), m_x=w.m, c=w.c, mode=oracle.EXTRAS_TOP)
+        mis = slot[1:w.L] > 0
+        assert 0.2 < mis.mean() < 0.4
+        assert (out["misaligned"][:w.L - 1] == mis).all()
+        assert (out["extras"][:w.L - 1, 0][mis] == alt[1:w.L][mis]).all()
+        ex.append(out["extras"]); nx.append(out["n_extras"])
+    ob = bk.OracleBackend()
+    with_x = harness.decode_tree(w, ob, streams, np.concatenate(ex), np.concatenate(nx), max_nodes=1 + w.C * w.k * 3)
+    without = harness.decode_tree(w, ob, streams, None, None, max_nodes=1 + w.C * w.k)
+    assert with_x.mean_accept_len > without.mean_accept_len + 0.1
+    # every committed token came from the accepted path of that step's tree, then the model's next token
+    for s in with_x.steps:
+        t, v = s.retrieved["tree"], s.verified
+        for b in range(w.B):
+            a = int(v["accept_len"][b])
+            assert 0 <= a <= w.k and (v["accept_path"][b, a:] == -1).all()
+            assert a == 0 or t["node_depth"][b, v["best_node"][b]] == a
