@@ -425,10 +425,14 @@ def bench_tree(args, w, dev):
     row_bytes = w.V * elt
     align_gbs = prefill_rows * row_bytes / (align_sweep_ms * 1e-3) / 1e9
     tree_gbs = tree_rows * row_bytes / (tree_sweep_ms * 1e-3) / 1e9
+    measured = read_traffic(args.traffic_file)
+    traffic = None
+    if measured.get(f"{w.name}.tree_sweep.rows") == str(tree_rows):
+        traffic = int(float(measured[f"{w.name}.tree_sweep.hbm_bytes_per_launch"]))
     roofline = {
-        "bound": "hbm", "kernel": f"aasd::row_sweep_kernel (tree verification launch, {tree_rows} used rows of {BB * N})",
+        "bound": "hbm", "kernel": f"aasd::row_sweep_used_kernel (tree verification launch, {tree_rows} used rows of {BB * N})",
         "achieved": round(tree_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(tree_gbs / HBM_PEAK_GBS, 4),
-        "traffic": None, "bytes_per_launch": tree_rows * row_bytes, "avg_launch_ms": round(tree_sweep_ms, 4),
+        "traffic": traffic, "bytes_per_launch": tree_rows * row_bytes, "avg_launch_ms": round(tree_sweep_ms, 4),
         "align_sample": {"rows": prefill_rows, "sweep_kernel_ms": round(align_sweep_ms, 4), "GB/s": round(align_gbs, 1),
                          "frac": round(align_gbs / HBM_PEAK_GBS, 4), "call_ms": round(align_ms, 4)},
         "verify_tree": {"rows_used": tree_rows, "rows_launched": BB * N, "sweep_kernel_ms": round(tree_sweep_ms, 4),
