@@ -21,7 +21,7 @@ _SRC = os.path.join(_HERE, "aasd_oracle.c")
 _LIB = os.path.join(_HERE, "libaasd_oracle.so")
 
 F32, BF16 = 0, 1
-EXTRAS_TOP, EXTRAS_SAMPLE = 0, 1
+EXTRAS_TOP, EXTRAS_SAMPLE, EXTRAS_GUMBEL = 0, 1, 2
 VERIFY_NO_CLAMP = 1
 
 

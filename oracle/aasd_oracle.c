@@ -138,7 +138,7 @@ int orc_align_sample(const void *logits, int dtype, int64_t rows, int32_t V, int
     if (!logits || rows < 0 || V <= 0 || row_stride < V) return -1;
     if (dtype != ORC_F32 && dtype != ORC_BF16) return -1;
     if (m_x < 0 || m_x > 4 || c < m_x || c > 8 || c < 1) return -1;
-    if (mode != ORC_EXTRAS_TOP && mode != ORC_EXTRAS_SAMPLE) return -1;
+    if (mode != ORC_EXTRAS_TOP && mode != ORC_EXTRAS_SAMPLE && mode != ORC_EXTRAS_GUMBEL) return -1;
 
     double *z = (double *)malloc(sizeof(double) * 2 * (size_t)V);
     if (!z) return -2;
@@ -180,6 +180,53 @@ int orc_align_sample(const void *logits, int dtype, int64_t rows, int32_t V, int
         if (rank) rank[r] = rk;
         if (p_next) p_next[r] = exp(zstar - m) / S;
         if (!mis || m_x == 0) continue;
+
+        if (mode == ORC_EXTRAS_GUMBEL) {
+            /* Sec. 3.2 read literally: the extras are SAMPLED from the whole output distribution of
+             * the prefill row.  m_x draws without replacement, proportional to the softmax
+             * probability, over every token except the prompt token itself (it is the draft token
+             * already).  Drawing without replacement in proportion to p is the same as ranking the
+             * tokens by z_v + G_v with independent standard Gumbel G_v (Gumbel-top-k), which needs
+             * one uniform per token: token v uses word (v mod 4) of the Philox block with counter
+             * (row id, v div 4, tag).  x in (0,1) -> E = -ln(1-x) is Exp(1) -> G = -ln E. */
+            uint64_t row_id = row_id_base + (uint64_t)r;
+            uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+            double *kap = z + V; /* the keys z_v + G_v (the softmax scratch is free again) */
+            for (int32_t v0 = 0; v0 < V; v0 += 4) {
+                uint32_t ctr[4] = {(uint32_t)row_id, (uint32_t)(row_id >> 32), (uint32_t)(v0 >> 2),
+                                   0x47554D42u};
+                uint32_t rnd[4];
+                orc_philox4x32_10(ctr, key, rnd);
+                for (int32_t j = 0; j < 4 && v0 + j < V; ++j) {
+                    double x = ((double)(rnd[j] >> 9) + 0.5) * (1.0 / 8388608.0);
+                    double E = -log1p(-x);
+                    kap[v0 + j] = z[v0 + j] - log(E);
+                }
+            }
+            int32_t picked[5];
+            int n_picked = 0;
+            for (int pick = 0; pick <= m_x; ++pick) { /* one more than needed: it gives the last margin */
+                int32_t best = -1;
+                for (int32_t v = 0; v < V; ++v) {
+                    int taken = (v == nt);
+                    for (int q = 0; q < n_picked; ++q)
+                        if (picked[q] == v) taken = 1;
+                    if (taken) continue;
+                    if (best < 0 || better(kap[v], v, kap[best], best)) best = v;
+                }
+                if (best < 0) break;
+                picked[n_picked++] = best;
+            }
+            int n_out = n_picked < m_x ? n_picked : m_x;
+            for (int i = 0; i < n_out; ++i) {
+                if (extras) extras[r * m_x + i] = picked[i];
+                if (draw_margin)
+                    draw_margin[r * m_x + i] =
+                        i + 1 < n_picked ? kap[picked[i]] - kap[picked[i + 1]] : INFINITY;
+            }
+            if (n_extras) n_extras[r] = (uint8_t)n_out;
+            continue;
+        }
 
         /* Fig. 2: the tokens ranked above the prompt token are the extras.
          * Candidate list K = the top-c tokens of the row (logit descending,

@@ -35,6 +35,7 @@ extern "C" {
 /* extra-token selection modes for alignment sampling */
 #define ORC_EXTRAS_TOP 0
 #define ORC_EXTRAS_SAMPLE 1
+#define ORC_EXTRAS_GUMBEL 2 /* m_x seeded draws without replacement from the WHOLE row (Gumbel-top-k) */
 
 /* verification flags */
 #define ORC_VERIFY_NO_CLAMP 1u /* Eq. 3 style: threshold alpha*H+beta, no min with Delta */
@@ -60,14 +61,16 @@ int orc_row_stats(const void *row, int dtype, int32_t V, double *m, double *S, d
  *   next_tok[r]  prompt token that follows row r, or -1 (NULL pointer = all -1)
  *   m_x          max extra tokens per position (Sec. 4.1 uses 2), 0..4
  *   c            candidate-set size (top-c by logit), m_x..8
- *   mode         ORC_EXTRAS_TOP | ORC_EXTRAS_SAMPLE
+ *   mode         ORC_EXTRAS_TOP | ORC_EXTRAS_SAMPLE | ORC_EXTRAS_GUMBEL
  * Outputs (any may be NULL):
  *   argmax[rows], misaligned[rows], entropy[rows], p_next[rows], p_max[rows],
  *   rank[rows]   (#tokens with a strictly larger logit than next_tok; -1 if none)
  *   extras[rows,m_x] (-1 padded), n_extras[rows]
  *   draw_margin[rows,m_x]  SAMPLE mode: for each seeded draw the distance
  *                min_i |u*W - cum_i| / W to the nearest CDF edge; -1 where no
- *                random number was consumed.                                  */
+ *                random number was consumed.  GUMBEL mode: the gap between the
+ *                key z_v + G_v of the j-th pick and the next smaller key
+ *                (+inf if there is none).                                    */
 int orc_align_sample(const void *logits, int dtype, int64_t rows, int32_t V, int64_t row_stride,
                      const int32_t *next_tok, int32_t m_x, int32_t c, int mode, uint64_t seed,
                      uint64_t row_id_base, int32_t *argmax, uint8_t *misaligned, double *entropy,
