@@ -40,6 +40,9 @@ def parse():
     ap.add_argument("--decode-steps", type=int, default=None, help="override the workload's number of decode steps")
     ap.add_argument("--prefill-rows", type=int, default=None, help="cap on prefill rows held in HBM")
     ap.add_argument("--max-nodes", type=int, default=None, help="tree_* workloads: node budget per sequence (default min(256, 1 + C*k*(1+m)))")
+    ap.add_argument("--extras-mode", default="top", choices=["top", "sample", "gumbel"],
+                    help="how alignment sampling chooses the extras: best-ranked (Fig. 2), seeded draws among the top-c, "
+                         "or seeded draws from the whole row (a second, ALU-bound kernel over the misaligned rows)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-latency", action="store_true")
     ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "row_sweep_traffic.txt"),
@@ -101,6 +104,7 @@ def main():
     elt = 2 if w.dtype == "bf16" else 4
     if w.name.startswith("tree_"):
         return bench_tree(args, w, dev)
+    mode = {"top": aasd.EXTRAS_TOP, "sample": aasd.EXTRAS_SAMPLE, "gumbel": aasd.EXTRAS_GUMBEL}[args.extras_mode]
 
     # ---------------------------------------------------------------- setup (untimed)
     t_setup = time.time()
@@ -116,7 +120,7 @@ def main():
         synth.prefill_logits(w, b, g, copied, dev, out=prefill[b * w.L:(b + 1) * w.L])
         next_tok[b * w.L:(b + 1) * w.L] = synth.next_tokens(w, g)
     next_tok_d = torch.from_numpy(next_tok).to(dev)
-    align_out = aasd.align_sample(prefill, next_tok_d, m=w.m, c=w.c, mode=aasd.EXTRAS_TOP, seed=w.seed)
+    align_out = aasd.align_sample(prefill, next_tok_d, m=w.m, c=w.c, mode=mode, seed=w.seed)
 
     # run the synthetic decode loop once on the HIP path to obtain every step's inputs
     class Recorder(harness.Backend):
@@ -169,7 +173,7 @@ def main():
     rows_per_step = prefill_rows + verify_rows
 
     def one_pass():
-        aasd.align_sample(prefill, next_tok_d, m=w.m, c=w.c, mode=aasd.EXTRAS_TOP, seed=w.seed, out=align_out)
+        aasd.align_sample(prefill, next_tok_d, m=w.m, c=w.c, mode=mode, seed=w.seed, out=align_out)
         aasd.retrieve_drafts(tokens_b, len_b, plen_b, w.n_min, w.n_max, w.k, w.C, out=r_out)
         aasd.verify(verify_logits, r_out["drafts"], r_out["draft_len"], r_out["strict"], alpha=w.alpha, beta=w.beta,
                     workspace=ws, want_rows=False, want_tokens=False, out=v_out)
@@ -183,13 +187,15 @@ def main():
     # library's measurement hook) one pair around each row-sweep kernel alone.
     K = args.steps
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(K)]
-    kev = [[hip_event() for _ in range(4)] for _ in range(K)]
+    kev = [[hip_event() for _ in range(6)] for _ in range(K)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(K):
         ev[i][0].record()
         aasd.set_sweep_events(kev[i][0], kev[i][1])
-        aasd.align_sample(prefill, next_tok_d, m=w.m, c=w.c, mode=aasd.EXTRAS_TOP, seed=w.seed, out=align_out)
+        if mode == aasd.EXTRAS_GUMBEL:
+            aasd.set_draw_events(kev[i][4], kev[i][5])
+        aasd.align_sample(prefill, next_tok_d, m=w.m, c=w.c, mode=mode, seed=w.seed, out=align_out)
         ev[i][1].record()
         aasd.retrieve_drafts(tokens_b, len_b, plen_b, w.n_min, w.n_max, w.k, w.C, out=r_out)
         ev[i][2].record()
@@ -198,10 +204,26 @@ def main():
                     workspace=ws, want_rows=False, want_tokens=False, out=v_out)
         ev[i][3].record()
     aasd.set_sweep_events(None, None)
+    aasd.set_draw_events(None, None)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / K
     value = rows_per_step / (ms_per_step * 1e-3)
+    draws = None
+    if mode == aasd.EXTRAS_GUMBEL:
+        # the draw kernel is bound by instruction issue: 68 vector-lane cycles per token (197 vector instructions per
+        # four tokens, of which 17 64-bit multiplies and 8 logarithms run at quarter rate), against
+        # 256 CUs x 64 lanes x 2.4 GHz = 39.3e12 lane cycles per second
+        draw_ms = float(np.mean([hip_elapsed(kev[i][4], kev[i][5]) for i in range(K)]))
+        n_mis = int(align_out["misaligned"].sum().item())
+        tokens = n_mis * w.V
+        lane_cycles = 68.0
+        peak = 256 * 64 * 2.4e9 / 1e12
+        ach = tokens * lane_cycles / (draw_ms * 1e-3) / 1e12
+        draws = {"kernel": "aasd::gumbel_extras_kernel", "rows_drawn": n_mis, "tokens": tokens, "kernel_ms": round(draw_ms, 4),
+                 "Gtokens/s": round(tokens / (draw_ms * 1e-3) / 1e9, 1),
+                 "roofline": {"bound": "alu", "achieved": round(ach, 2), "peak": round(peak, 2), "unit": "T lane-cycles/s",
+                              "frac": round(ach / peak, 4), "lane_cycles_per_token": lane_cycles}}
     align_ms = float(np.mean([ev[i][0].elapsed_time(ev[i][1]) for i in range(K)]))
     retr_ms = float(np.mean([ev[i][1].elapsed_time(ev[i][2]) for i in range(K)]))
     verify_ms = float(np.mean([ev[i][2].elapsed_time(ev[i][3]) for i in range(K)]))
@@ -268,7 +290,7 @@ def main():
         len_h = len_b[:nb].cpu().numpy()
         plen_h = plen_b[:nb].cpu().numpy()
         tc = time.perf_counter()
-        oracle.align_sample(bits_a, next_tok[:n_a], m_x=w.m, c=w.c)
+        oracle.align_sample(bits_a, next_tok[:n_a], m_x=w.m, c=w.c, mode=mode)
         r = oracle.retrieve_drafts(tok_h, len_h, plen_h, w.n_min, w.n_max, w.k, w.C)
         oracle.verify(bits_v, r["drafts"], r["draft_len"], r["strict"], alpha=float(np.float32(w.alpha)),
                       beta=float(np.float32(w.beta)))
@@ -285,10 +307,12 @@ def main():
         "config": {"workload": w.name, "B": w.B, "prompt_len": w.L, "V": w.V, "logits_dtype": w.dtype, "k": w.k, "C": w.C,
                    "n_gram": [w.n_min, w.n_max], "decode_steps": S, "prefill_rows": prefill_rows,
                    "verify_rows": verify_rows, "rows_per_step": rows_per_step,
-                   "form": "all decode steps verified as one batch"},
+                   "form": "all decode steps verified as one batch", "extras_mode": args.extras_mode},
         "roofline": roofline, "cpu_baseline": cpu, "latency": latency,
         "tokens_per_decode_step": round(trace.mean_accept_len, 3), "setup_s": round(setup_s, 1),
     }
+    if draws is not None:
+        out["draws"] = draws
     print(json.dumps(out))
 
 

@@ -42,7 +42,8 @@ typedef enum { AASD_F32 = 0, AASD_BF16 = 1 } aasd_dtype;
 /* how the extra draft tokens of a misaligned position are chosen */
 typedef enum {
     AASD_EXTRAS_TOP = 0,   /* best-ranked first (Fig. 2: the rank-1 and rank-2 tokens) */
-    AASD_EXTRAS_SAMPLE = 1 /* seeded draws without replacement, proportional to probability */
+    AASD_EXTRAS_SAMPLE = 1, /* seeded draws without replacement, proportional to probability, among them */
+    AASD_EXTRAS_GUMBEL = 2  /* seeded draws without replacement from the whole row (Sec. 3.2 read literally) */
 } aasd_extras_mode;
 
 /* aasd_verify flags */
@@ -66,6 +67,8 @@ const char *aasd_last_error(void);
  * time that kernel alone.  Pass NULL, NULL to switch it off (the default).
  */
 void aasd_set_sweep_events(void *start, void *stop);
+/* The same around the kernel that makes the full-vocabulary draws of AASD_EXTRAS_GUMBEL. */
+void aasd_set_draw_events(void *start, void *stop);
 
 /*
  * Alignment sampling over the prefill logits (Sec. 2.3 for aligned/misaligned
@@ -90,6 +93,13 @@ void aasd_set_sweep_events(void *start, void *stop);
  *                 key = (lo32(seed), hi32(seed))), id = row_id_base + r, as u = (word >> 8) / 2^24
  *                 and picks the first remaining candidate whose running weight sum exceeds
  *                 u * (total remaining weight).  Unused slots hold -1.
+ *                 In GUMBEL mode the extras of a misaligned row are min(m, V-1) draws without
+ *                 replacement, with probability proportional to p, from ALL tokens of the row but
+ *                 next_tok[r] (c is not used): the tokens with the largest keys z_v + G_v, key
+ *                 descending, id ascending, where G_v = -ln(-ln(1 - x_v)) is a standard Gumbel
+ *                 variate, x_v = ((word >> 9) + 1/2) / 2^23 and word is word (v mod 4) of
+ *                 Philox4x32-10(counter = (lo32(id), hi32(id), v div 4, 0x47554D42), key as above).
+ *                 Keys are formed in fp32 (error below 1e-5).
  *   n_extras[r]   number of valid entries in extras[r,:]
  *   Rows with next_tok[r] < 0 (or >= V) get misaligned = 0, p_next = 0, rank = -1, no extras.
  *
@@ -99,8 +109,9 @@ void aasd_set_sweep_events(void *start, void *stop);
  *             p_max[rows] f32 (all required); rank[rows] i32 (NULL = not wanted);
  *             extras[rows, m] i32 and n_extras[rows] u8 (required when m > 0);
  *             near_count: one u32 that is INCREMENTED by the number of SAMPLE draws that fell
- *             within 1e-6 (relative to the total weight) of a boundary between two picks
- *             (NULL = not wanted; the caller zeroes it).
+ *             within 1e-6 (relative to the total weight) of a boundary between two picks, in
+ *             GUMBEL mode by the number of rows in which a pick's key is within 5e-5 of the next
+ *             smaller key (NULL = not wanted; the caller zeroes it).
  * workspace : DEVICE scratch of at least aasd_align_sample_workspace_bytes(rows, V, dt) bytes,
  *             16-byte aligned; it needs no initialisation and holds nothing of value afterwards.
  * Parameters: 0 <= m <= 4, max(m,1) <= c <= 8, rows >= 0, V >= 1, row_stride >= V.

@@ -208,7 +208,7 @@ int orc_align_sample(const void *logits, int dtype, int64_t rows, int32_t V, int
             for (int pick = 0; pick <= m_x; ++pick) { /* one more than needed: it gives the last margin */
                 int32_t best = -1;
                 for (int32_t v = 0; v < V; ++v) {
-                    int taken = (v == nt);
+                    int taken = (v == nt) || kap[v] == -INFINITY; /* p_v = 0 cannot be drawn */
                     for (int q = 0; q < n_picked; ++q)
                         if (picked[q] == v) taken = 1;
                     if (taken) continue;

@@ -14,7 +14,7 @@ import torch
 from . import _lib
 
 F32, BF16 = 0, 1
-EXTRAS_TOP, EXTRAS_SAMPLE = 0, 1
+EXTRAS_TOP, EXTRAS_SAMPLE, EXTRAS_GUMBEL = 0, 1, 2
 VERIFY_NO_CLAMP = 1
 
 MAX_EXTRAS, MAX_CANDSET, MAX_KEY, MAX_DRAFT, MAX_CANDIDATES = 4, 8, 8, 16, 32
@@ -40,6 +40,11 @@ def _check(rc: int):
 def set_sweep_events(start, stop):
     """Measurement hook: raw hipEvent_t handles (ints) recorded around the row-sweep kernel; None, None = off."""
     _lib.load().aasd_set_sweep_events(start, stop)
+
+
+def set_draw_events(start, stop):
+    """The same hook around the kernel that makes the full-vocabulary draws of EXTRAS_GUMBEL."""
+    _lib.load().aasd_set_draw_events(start, stop)
 
 
 def _dtype_code(t: torch.Tensor) -> int:

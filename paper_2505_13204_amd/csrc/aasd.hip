@@ -11,6 +11,7 @@
 
 #include "retrieve.hip.h"
 #include "row_finish.hip.h"
+#include "gumbel.hip.h"
 #include "row_sweep.hip.h"
 #include "tree.hip.h"
 #include "verify_tail.hip.h"
@@ -19,6 +20,7 @@ namespace {
 
 thread_local char g_err[512] = "";
 thread_local hipEvent_t g_sweep_start = nullptr, g_sweep_stop = nullptr;  // measurement hook
+thread_local hipEvent_t g_draw_start = nullptr, g_draw_stop = nullptr;
 
 int fail(int code, const char* fmt, ...)
 {
@@ -142,6 +144,24 @@ int launch_sweep_used(const aasd::SweepParams& p, const SweepPlan& pl, int64_t s
     return AASD_OK;
 }
 
+template <int DT>
+void launch_gumbel_dt(int m, unsigned grid, hipStream_t s, const aasd::GumbelParams& gp, int64_t r0)
+{
+    const dim3 g(grid), b(aasd::kGumbelBlock);
+    switch (m) {  // the kernel keeps m + 1 keys per lane
+    case 1: hipLaunchKernelGGL((aasd::gumbel_extras_kernel<DT, 2>), g, b, 0, s, gp, r0); break;
+    case 2: hipLaunchKernelGGL((aasd::gumbel_extras_kernel<DT, 3>), g, b, 0, s, gp, r0); break;
+    case 3: hipLaunchKernelGGL((aasd::gumbel_extras_kernel<DT, 4>), g, b, 0, s, gp, r0); break;
+    default: hipLaunchKernelGGL((aasd::gumbel_extras_kernel<DT, 5>), g, b, 0, s, gp, r0); break;
+    }
+}
+
+void launch_gumbel(int32_t dt, int m, unsigned grid, hipStream_t s, const aasd::GumbelParams& gp, int64_t r0)
+{
+    if (dt == AASD_BF16) launch_gumbel_dt<AASD_BF16>(m, grid, s, gp, r0);
+    else launch_gumbel_dt<AASD_F32>(m, grid, s, gp, r0);
+}
+
 size_t align16(size_t n) { return (n + 15) & ~(size_t)15; }
 
 }  // namespace
@@ -156,6 +176,12 @@ void aasd_set_sweep_events(void* start, void* stop)
 {
     g_sweep_start = (hipEvent_t)start;
     g_sweep_stop = (hipEvent_t)stop;
+}
+
+void aasd_set_draw_events(void* start, void* stop)
+{
+    g_draw_start = (hipEvent_t)start;
+    g_draw_stop = (hipEvent_t)stop;
 }
 
 size_t aasd_align_sample_workspace_bytes(int64_t rows, int32_t V, int32_t dt)
@@ -179,7 +205,7 @@ int aasd_align_sample(const void* logits, int32_t dt, int64_t rows, int32_t V, i
     if (m < 0 || m > AASD_MAX_EXTRAS) return fail(AASD_ERR_INVALID_ARG, "align_sample: m = %d outside [0,%d]", m, AASD_MAX_EXTRAS);
     if (c < 1 || c < m || c > AASD_MAX_CANDSET)
         return fail(AASD_ERR_INVALID_ARG, "align_sample: c = %d outside [max(m,1),%d]", c, AASD_MAX_CANDSET);
-    if (mode != AASD_EXTRAS_TOP && mode != AASD_EXTRAS_SAMPLE)
+    if (mode != AASD_EXTRAS_TOP && mode != AASD_EXTRAS_SAMPLE && mode != AASD_EXTRAS_GUMBEL)
         return fail(AASD_ERR_INVALID_ARG, "align_sample: unknown mode %d", mode);
     if (rows == 0) return AASD_OK;
     if (!logits || !argmax || !misaligned || !entropy || !p_next || !p_max)
@@ -197,6 +223,11 @@ int aasd_align_sample(const void* logits, int32_t dt, int64_t rows, int32_t V, i
     const SweepPlan pl = plan_sweep(true, rows, V, dt);
     aasd::WavePartial* partials = (aasd::WavePartial*)workspace;
     int32_t* lists = (int32_t*)((char*)workspace + (size_t)rows * pl.npart * sizeof(aasd::WavePartial));
+    // full-vocabulary draws are made by a pass of their own over the misaligned rows: the statistics pass
+    // then has no candidates to collect
+    const bool gumbel = mode == AASD_EXTRAS_GUMBEL && m > 0;
+    const int32_t m_draw = m;
+    if (gumbel) m = 0;
 
     aasd::SweepParams p{};
     p.logits = logits; p.V = V; p.row_stride = row_stride; p.seq_stride = row_stride; p.rows_per_seq = 1;
@@ -241,6 +272,20 @@ int aasd_align_sample(const void* logits, int32_t dt, int64_t rows, int32_t V, i
         else hipLaunchKernelGGL(aasd::align_finish_kernel<AASD_F32>, dim3(grid), dim3(aasd::kFinishBlock), 0, s, fc);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return fail(AASD_ERR_LAUNCH, "align finish launch failed: %s", hipGetErrorString(e));
+    }
+    if (gumbel) {
+        aasd::GumbelParams gp{};
+        gp.logits = logits; gp.V = V; gp.row_stride = row_stride; gp.next_tok = next_tok; gp.misaligned = misaligned;
+        gp.m_x = m_draw; gp.seed = seed; gp.row_id_base = row_id_base;
+        gp.extras = extras; gp.n_extras = n_extras; gp.extra_keys = nullptr; gp.near_count = near_count;
+        if (g_draw_start) (void)hipEventRecord(g_draw_start, s);
+        for (int64_t r0 = 0; r0 < rows; r0 += kMaxUnitsPerLaunch) {
+            const int64_t n = rows - r0 < kMaxUnitsPerLaunch ? rows - r0 : kMaxUnitsPerLaunch;
+            launch_gumbel(dt, m_draw, (unsigned)n, s, gp, r0);
+            const hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return fail(AASD_ERR_LAUNCH, "gumbel extras launch failed: %s", hipGetErrorString(e));
+        }
+        if (g_draw_stop) (void)hipEventRecord(g_draw_stop, s);
     }
     return AASD_OK;
 }

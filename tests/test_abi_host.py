@@ -43,7 +43,7 @@ def _align(lib, **kw):
 
 def test_align_sample_rejects_invalid_arguments(lib):
     for kw in [dict(dt=7), dict(rows=-1), dict(V=0), dict(row_stride=99), dict(m=5), dict(m=-1), dict(c=1), dict(c=9),
-               dict(m=0, c=0), dict(mode=2), dict(logits=None), dict(argmax=None), dict(ent=None), dict(extras=None),
+               dict(m=0, c=0), dict(mode=3), dict(mode=2, extras=None), dict(logits=None), dict(argmax=None), dict(ent=None), dict(extras=None),
                dict(nx=None)]:
         assert _align(lib, **kw) == INVALID, kw
         assert lib.aasd_last_error() != b""

@@ -449,3 +449,68 @@ def test_full_shapes_sampled(name, align_rows, seqs):
         assert (out["row_entropy"] >= 0).all() and (out["row_entropy"] <= math.log(w.V) + 1e-3).all()
         assert ((out["row_argmax"] >= 0) & (out["row_argmax"] < w.V)).all()
     print(name, "full shapes", tally)
+
+
+# --------------------------------------------------------------------------- full-vocabulary draws
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("V,m", [(2, 1), (5, 2), (9, 4), (1000, 2), (4099, 3), (32000, 2), (128256, 2)])
+def test_gumbel_extras_parity(dtype, V, m):
+    """EXTRAS_GUMBEL: the draws are the m largest keys z + G over the whole row; same picks as the oracle
+    unless two neighbouring keys are closer than the fp32 keys can tell apart (counted)."""
+    rng = np.random.default_rng(V * 7 + m)
+    rows = 48 if V > 20000 else 200
+    zd = _random_rows(rng, rows, V, dtype)
+    nt = rng.integers(0, V, size=rows).astype(np.int32)
+    nt[::7] = -1
+    tally = bk.Tally()
+    for seed, base in [(1, 0), ((5 << 32) | 9, (1 << 32) + 3)]:
+        ref = bk.oracle_align(zd, nt, m, max(m, 1), oracle.EXTRAS_GUMBEL, seed=seed, row_id_base=base)
+        got = bk.hip_align(zd, nt, m, max(m, 1), oracle.EXTRAS_GUMBEL, seed=seed, row_id_base=base)
+        bk.compare_align(got, ref, tally, oracle.EXTRAS_GUMBEL)
+        mis = ref["misaligned"] == 1
+        assert (ref["n_extras"][mis] == min(m, V - 1)).all() and (ref["n_extras"][~mis] == 0).all()
+    assert tally.near_disagreements <= tally.near_decisions
+    print("gumbel", dtype, V, m, tally)
+
+
+def test_gumbel_extras_unaligned_rows_peaked_rows_and_near_counter():
+    rng = np.random.default_rng(31)
+    rows, V = 300, 5003
+    big = torch.zeros((rows, V + 5), dtype=torch.bfloat16, device=DEV)   # odd stride: rows start at any 2-byte offset
+    z = rng.standard_normal((rows, V)).astype(np.float32) * 2
+    z[:, 17] = 16.0                                                      # one dominant token: it is (nearly) always drawn first
+    big[:, :V] = torch.from_numpy(z).to(DEV).to(torch.bfloat16)
+    view = big[:, :V]
+    nt = rng.integers(0, V, size=rows).astype(np.int32)
+    tally = bk.Tally()
+    ref = bk.oracle_align(view, nt, 3, 3, oracle.EXTRAS_GUMBEL, seed=4)
+    near = torch.zeros(1, dtype=torch.int32, device=DEV)
+    out = aasd.align_sample(view, torch.from_numpy(nt).to(DEV), m=3, c=3, mode=aasd.EXTRAS_GUMBEL, seed=4, near_count=near)
+    torch.cuda.synchronize()
+    bk.compare_align(bk.to_np(out), ref, tally, oracle.EXTRAS_GUMBEL)
+    assert (ref["extras"][nt != 17, 0] == 17).mean() > 0.97
+    margin = np.where(ref["draw_margin"] < 0, np.inf, ref["draw_margin"]).min(axis=1)
+    lo, hi = int((margin < 0.5 * bk.NEAR_GUMBEL).sum()), int((margin < 2 * bk.NEAR_GUMBEL).sum())
+    assert lo <= int(near.item()) <= hi
+
+
+def test_gumbel_extras_many_rows_hit_near_decisions_and_zero_probability_tokens():
+    """Enough draws that some neighbouring keys fall within the fp32 resolution: those rows are counted, all
+    others must agree exactly, and the kernel's own counter brackets the oracle's.  Some tokens have p = 0."""
+    rng = np.random.default_rng(9)
+    rows, V, m = 40000, 24, 4
+    z = (rng.standard_normal((rows, V)) * 1.5).astype(np.float32)
+    z[rng.random((rows, V)) < 0.1] = -np.inf
+    zd = _dev_logits(z, "f32")
+    nt = rng.integers(0, V, size=rows).astype(np.int32)
+    tally = bk.Tally()
+    ref = bk.oracle_align(zd, nt, m, m, oracle.EXTRAS_GUMBEL, seed=77)
+    near = torch.zeros(1, dtype=torch.int32, device=DEV)
+    out = aasd.align_sample(zd, torch.from_numpy(nt).to(DEV), m=m, c=m, mode=aasd.EXTRAS_GUMBEL, seed=77, near_count=near)
+    torch.cuda.synchronize()
+    bk.compare_align(bk.to_np(out), ref, tally, oracle.EXTRAS_GUMBEL)
+    assert tally.near_decisions >= 2, tally
+    margin = np.where(ref["draw_margin"] < 0, np.inf, ref["draw_margin"]).min(axis=1)
+    lo, hi = int((margin < 0.5 * bk.NEAR_GUMBEL).sum()), int((margin < 2 * bk.NEAR_GUMBEL).sum())
+    assert lo <= int(near.item()) <= hi, (lo, int(near.item()), hi)
+    print("gumbel many rows", tally, "kernel near", int(near.item()), "oracle bracket", lo, hi)

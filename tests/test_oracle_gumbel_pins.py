@@ -93,6 +93,12 @@ def test_partition_shift_invariance_and_degenerate_rows():
     assert np.isinf(two["draw_margin"][0, 0]) and two["draw_margin"][0, 1] == -1
     one = oracle.align_sample(np.array([[0.3]], np.float32), [0], m_x=1, c=1, mode=G, seed=1)
     assert one["n_extras"].tolist() == [0]
+    # tokens of probability zero (-inf logits) are never drawn
+    zi = np.full((50, 8), -np.inf, np.float32)
+    zi[:, 2], zi[:, 5], zi[:, 6] = 0.0, 1.0, -1.0
+    out = oracle.align_sample(zi, np.full(50, 6), m_x=4, c=4, mode=G, seed=2)
+    assert (out["n_extras"] == 2).all() and (np.sort(out["extras"][:, :2], axis=1) == [2, 5]).all()
+    assert (out["extras"][:, 2:] == -1).all()
 
 
 def test_a_dominant_token_is_drawn_first_almost_surely():
