@@ -180,6 +180,27 @@ def verify(logits: np.ndarray, drafts, draft_len, strict=None, alpha: float = 0.
     return out
 
 
+def verify_topk(logits: np.ndarray, drafts, draft_len, topk: int = 5, V: int | None = None):
+    """Top-k verification (Sec. 4.4): logits [B, R, row_stride], R = 1 + C*k; drafts [B,C,k]; draft_len [B,C]."""
+    assert logits.ndim == 3 and logits.flags["C_CONTIGUOUS"]
+    B, R, row_stride = logits.shape
+    V = row_stride if V is None else V
+    drafts = np.ascontiguousarray(drafts, dtype=np.int32)
+    draft_len = np.ascontiguousarray(draft_len, dtype=np.int32)
+    _, C, k = drafts.shape
+    assert R == 1 + C * k, (R, C, k)
+    out = dict(accept_len=np.empty(B, np.int32), best_cand=np.empty(B, np.int32), next_token=np.empty(B, np.int32),
+               row_argmax=np.empty((B, R), np.int32), tok_rank=np.empty((B, C, k), np.int32))
+    rc = lib().orc_verify_topk(
+        c_void_p(logits.ctypes.data), _dtype_of(logits), c_int32(B), c_int32(C), c_int32(k), c_int32(V),
+        c_int64(row_stride), c_int64(R * row_stride), _ptr(drafts, c_int32), _ptr(draft_len, c_int32), c_int32(topk),
+        _ptr(out["accept_len"], c_int32), _ptr(out["best_cand"], c_int32), _ptr(out["next_token"], c_int32),
+        _ptr(out["row_argmax"], c_int32), _ptr(out["tok_rank"], c_int32))
+    if rc != 0:
+        raise ValueError(f"orc_verify_topk rc={rc}")
+    return out
+
+
 def build_tree(drafts, draft_len, strict=None, draft_extras=None, root_tok=None, max_nodes: int = 64):
     """drafts [B,C,k], draft_len [B,C], strict [B,C,k] or None, draft_extras [B,C,k,m] or None."""
     drafts = np.ascontiguousarray(drafts, dtype=np.int32)

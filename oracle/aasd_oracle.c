@@ -459,6 +459,74 @@ int orc_verify(const void *logits, int dtype, int32_t B, int32_t C, int32_t k, i
 }
 
 /* ------------------------------------------------------------------------- */
+/* top-k verification (the ablation of Sec. 4.4)                              */
+/* ------------------------------------------------------------------------- */
+int orc_verify_topk(const void *logits, int dtype, int32_t B, int32_t C, int32_t k, int32_t V,
+                    int64_t row_stride, int64_t seq_stride, const int32_t *drafts,
+                    const int32_t *draft_len, int32_t topk, int32_t *accept_len,
+                    int32_t *best_cand, int32_t *next_token, int32_t *row_argmax,
+                    int32_t *tok_rank)
+{
+    if (!logits || !drafts || !draft_len || B < 0 || V <= 0 || topk < 1) return -1;
+    if (dtype != ORC_F32 && dtype != ORC_BF16) return -1;
+    if (k < 1 || k > 16 || C < 1 || C > 32) return -1;
+    const int32_t R = 1 + C * k;
+    if (row_stride < V || seq_stride < (int64_t)R * row_stride) return -1;
+
+    double *z = (double *)malloc(sizeof(double) * (size_t)V);
+    if (!z) return -2;
+    for (int32_t b = 0; b < B; ++b) {
+        const char *seq = (const char *)logits + (size_t)b * (size_t)seq_stride * elt_bytes(dtype);
+        int32_t best_c = 0, best_a = 0;
+        for (int32_t c = 0; c < C; ++c) {
+            size_t bc = (size_t)b * (size_t)C + (size_t)c;
+            int32_t dl = draft_len[bc];
+            if (dl < 0) dl = 0;
+            if (dl > k) dl = k;
+            int32_t a = 0;
+            int rejected = 0;
+            for (int32_t j = 1; j <= k; ++j) {
+                size_t idx = bc * k + (size_t)(j - 1);
+                int32_t rk = -1;
+                if (j <= dl) {
+                    /* the draft token is accepted iff it is among the topk most likely tokens of
+                     * the row that verifies it: fewer than topk tokens are strictly more likely */
+                    int32_t rho = (j == 1) ? 0 : 1 + c * k + (j - 2);
+                    const char *row = seq + (size_t)rho * (size_t)row_stride * elt_bytes(dtype);
+                    int32_t t = drafts[idx];
+                    int pass = 0;
+                    if (t >= 0 && t < V) {
+                        orc_widen_row(row, dtype, V, z);
+                        rk = 0;
+                        for (int32_t v = 0; v < V; ++v)
+                            if (z[v] > z[t]) ++rk;
+                        pass = rk < topk;
+                    }
+                    if (!rejected) { if (pass) ++a; else rejected = 1; }
+                }
+                if (tok_rank) tok_rank[idx] = rk;
+            }
+            if (a > best_a) { best_a = a; best_c = c; } /* lowest c on ties */
+        }
+        if (accept_len) accept_len[b] = best_a;
+        if (best_cand) best_cand[b] = best_c;
+        for (int32_t r = 0; r < R; ++r) {
+            int need = row_argmax != NULL || (next_token && r == (best_a == 0 ? 0 : 1 + best_c * k + (best_a - 1)));
+            if (!need) continue;
+            const char *row = seq + (size_t)r * (size_t)row_stride * elt_bytes(dtype);
+            orc_widen_row(row, dtype, V, z);
+            int32_t am = 0;
+            for (int32_t v = 1; v < V; ++v)
+                if (z[v] > z[am]) am = v;
+            if (row_argmax) row_argmax[(size_t)b * R + r] = am;
+            if (next_token && r == (best_a == 0 ? 0 : 1 + best_c * k + (best_a - 1))) next_token[b] = am;
+        }
+    }
+    free(z);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------- */
 /* draft tree and tree attention mask                                         */
 /* ------------------------------------------------------------------------- */
 int orc_build_tree(const int32_t *drafts, const int32_t *draft_len, const uint8_t *strict,

@@ -103,6 +103,17 @@ int orc_verify(const void *logits, int dtype, int32_t B, int32_t C, int32_t k, i
                double *row_entropy, double *row_pmax, int32_t *row_argmax, double *tok_p,
                double *tok_delta, double *tok_margin, uint32_t *near_count);
 
+/* Top-k verification, the ablation of Sec. 4.4 (k = 5 there): a draft token is accepted iff fewer than
+ * `topk` tokens of the row that verifies it have a strictly larger logit; rows, cascade, longest
+ * candidate and next token as in orc_verify.  Outputs (any may be NULL): accept_len[B], best_cand[B],
+ * next_token[B], row_argmax[B,R], tok_rank[B,C,k] (number of strictly larger logits; -1 beyond
+ * draft_len or for a token id outside the vocabulary).                                          */
+int orc_verify_topk(const void *logits, int dtype, int32_t B, int32_t C, int32_t k, int32_t V,
+                    int64_t row_stride, int64_t seq_stride, const int32_t *drafts,
+                    const int32_t *draft_len, int32_t topk, int32_t *accept_len,
+                    int32_t *best_cand, int32_t *next_token, int32_t *row_argmax,
+                    int32_t *tok_rank);
+
 /* Draft tree (Sec. 3.2, Eq. 2): the candidate n-grams and the alignment extras of their positions
  * merged into one tree under the last committed token, plus the tree attention mask.
  *   Node 0 is the root.  Layer j (depth j) is built from the j-th tokens of the candidates in the
