@@ -43,6 +43,9 @@ def parse():
     ap.add_argument("--extras-mode", default="top", choices=["top", "sample", "gumbel"],
                     help="how alignment sampling chooses the extras: best-ranked (Fig. 2), seeded draws among the top-c, "
                          "or seeded draws from the whole row (a second, ALU-bound kernel over the misaligned rows)")
+    ap.add_argument("--verifier", default="adaptive", choices=["adaptive", "topk"],
+                    help="conditional verification with the entropy-adaptive threshold (Eq. 4-6), or the top-k ablation (Sec. 4.4)")
+    ap.add_argument("--topk", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-latency", action="store_true")
     ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "row_sweep_traffic.txt"),
@@ -105,6 +108,19 @@ def main():
     if w.name.startswith("tree_"):
         return bench_tree(args, w, dev)
     mode = {"top": aasd.EXTRAS_TOP, "sample": aasd.EXTRAS_SAMPLE, "gumbel": aasd.EXTRAS_GUMBEL}[args.extras_mode]
+    dt_code = aasd.BF16 if w.dtype == "bf16" else aasd.F32
+    topk = args.verifier == "topk"
+
+    def verify_ws(nseq):
+        nbytes = (aasd.verify_topk_workspace_bytes if topk else aasd.verify_workspace_bytes)(nseq, w.C, w.k, w.V, dt_code)
+        return torch.empty(max(16, nbytes), dtype=torch.uint8, device=dev)
+
+    def do_verify(logits, drafts, draft_len, strict, workspace=None, out=None):
+        if topk:
+            return aasd.verify_topk(logits, drafts, draft_len, topk=args.topk, want_rows=False, want_tokens=False,
+                                    workspace=workspace, out=out)
+        return aasd.verify(logits, drafts, draft_len, strict, alpha=w.alpha, beta=w.beta, want_rows=False,
+                           want_tokens=False, want_near=False, workspace=workspace, out=out)
 
     # ---------------------------------------------------------------- setup (untimed)
     t_setup = time.time()
@@ -141,9 +157,8 @@ def main():
             return z
 
         def verify(self, logits, drafts, draft_len, strict, w_):
-            out = aasd.verify(logits, self._d(drafts, torch.int32), self._d(draft_len, torch.int32),
-                              self._d(strict, torch.uint8), alpha=w_.alpha, beta=w_.beta, want_rows=False,
-                              want_tokens=False, want_near=False)
+            out = do_verify(logits, self._d(drafts, torch.int32), self._d(draft_len, torch.int32),
+                            self._d(strict, torch.uint8))
             return {k: v.cpu().numpy() for k, v in out.items() if v is not None and k != "workspace"}
 
     # hold at most ~24 GiB of verify logits: later steps reuse the buffers of earlier ones in rotation
@@ -160,9 +175,8 @@ def main():
     len_b = torch.from_numpy(np.concatenate([s.length for s in trace.steps]).astype(np.int32)).to(dev)
     plen_b = torch.full((BB,), w.L, dtype=torch.int32, device=dev)
     r_out = aasd.retrieve_drafts(tokens_b, len_b, plen_b, w.n_min, w.n_max, w.k, w.C)
-    ws = torch.empty(max(16, aasd.verify_workspace_bytes(BB, w.C, w.k, w.V, aasd.BF16 if w.dtype == 'bf16' else aasd.F32)), dtype=torch.uint8, device=dev)
-    v_out = aasd.verify(verify_logits, r_out["drafts"], r_out["draft_len"], r_out["strict"], alpha=w.alpha, beta=w.beta,
-                        workspace=ws, want_rows=False, want_tokens=False)
+    ws = verify_ws(BB)
+    v_out = do_verify(verify_logits, r_out["drafts"], r_out["draft_len"], r_out["strict"], workspace=ws)
     torch.cuda.synchronize()
     # the batched pass must reproduce the sequential loop it stands for
     seq_accept = np.concatenate([s.verified["accept_len"] for s in trace.steps])
@@ -175,8 +189,7 @@ def main():
     def one_pass():
         aasd.align_sample(prefill, next_tok_d, m=w.m, c=w.c, mode=mode, seed=w.seed, out=align_out)
         aasd.retrieve_drafts(tokens_b, len_b, plen_b, w.n_min, w.n_max, w.k, w.C, out=r_out)
-        aasd.verify(verify_logits, r_out["drafts"], r_out["draft_len"], r_out["strict"], alpha=w.alpha, beta=w.beta,
-                    workspace=ws, want_rows=False, want_tokens=False, out=v_out)
+        do_verify(verify_logits, r_out["drafts"], r_out["draft_len"], r_out["strict"], workspace=ws, out=v_out)
 
     for _ in range(args.warmup):
         one_pass()
@@ -200,8 +213,7 @@ def main():
         aasd.retrieve_drafts(tokens_b, len_b, plen_b, w.n_min, w.n_max, w.k, w.C, out=r_out)
         ev[i][2].record()
         aasd.set_sweep_events(kev[i][2], kev[i][3])
-        aasd.verify(verify_logits, r_out["drafts"], r_out["draft_len"], r_out["strict"], alpha=w.alpha, beta=w.beta,
-                    workspace=ws, want_rows=False, want_tokens=False, out=v_out)
+        do_verify(verify_logits, r_out["drafts"], r_out["draft_len"], r_out["strict"], workspace=ws, out=v_out)
         ev[i][3].record()
     aasd.set_sweep_events(None, None)
     aasd.set_draw_events(None, None)
@@ -260,17 +272,15 @@ def main():
     if not args.no_latency and w.B * w.R <= 512:
         n_lat = min(S, 256)
         outs_r = aasd.retrieve_drafts(tokens_b[:w.B], len_b[:w.B], plen_b[:w.B], w.n_min, w.n_max, w.k, w.C)
-        ws1 = torch.empty(max(16, aasd.verify_workspace_bytes(w.B, w.C, w.k, w.V, aasd.BF16 if w.dtype == 'bf16' else aasd.F32)), dtype=torch.uint8, device=dev)
-        outs_v = aasd.verify(verify_logits[:w.B], outs_r["drafts"], outs_r["draft_len"], outs_r["strict"],
-                             workspace=ws1, want_rows=False, want_tokens=False)
+        ws1 = verify_ws(w.B)
+        outs_v = do_verify(verify_logits[:w.B], outs_r["drafts"], outs_r["draft_len"], outs_r["strict"], workspace=ws1)
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         for s in range(n_lat):
             sl = slice(s * w.B, (s + 1) * w.B)
             aasd.retrieve_drafts(tokens_b[sl], len_b[sl], plen_b[sl], w.n_min, w.n_max, w.k, w.C, out=outs_r)
-            aasd.verify(verify_logits[sl], outs_r["drafts"], outs_r["draft_len"], outs_r["strict"], alpha=w.alpha,
-                        beta=w.beta, workspace=ws1, want_rows=False, want_tokens=False, out=outs_v)
+            do_verify(verify_logits[sl], outs_r["drafts"], outs_r["draft_len"], outs_r["strict"], workspace=ws1, out=outs_v)
         e1.record()
         torch.cuda.synchronize()
         latency = {"decode_steps": n_lat, "rows_per_step": w.B * w.R,
@@ -292,8 +302,11 @@ def main():
         tc = time.perf_counter()
         oracle.align_sample(bits_a, next_tok[:n_a], m_x=w.m, c=w.c, mode=mode)
         r = oracle.retrieve_drafts(tok_h, len_h, plen_h, w.n_min, w.n_max, w.k, w.C)
-        oracle.verify(bits_v, r["drafts"], r["draft_len"], r["strict"], alpha=float(np.float32(w.alpha)),
-                      beta=float(np.float32(w.beta)))
+        if topk:
+            oracle.verify_topk(bits_v, r["drafts"], r["draft_len"], topk=args.topk)
+        else:
+            oracle.verify(bits_v, r["drafts"], r["draft_len"], r["strict"], alpha=float(np.float32(w.alpha)),
+                          beta=float(np.float32(w.beta)))
         dt = time.perf_counter() - tc
         cpu = {"value": round((n_a + nb * w.R) / dt, 1), "unit": "rows/s", "cores": 1, "kind": "oracle",
                "sample": f"first {n_a} prefill rows + first {n_s} decode steps ({nb * w.R} verify rows) of the same "
@@ -307,7 +320,8 @@ def main():
         "config": {"workload": w.name, "B": w.B, "prompt_len": w.L, "V": w.V, "logits_dtype": w.dtype, "k": w.k, "C": w.C,
                    "n_gram": [w.n_min, w.n_max], "decode_steps": S, "prefill_rows": prefill_rows,
                    "verify_rows": verify_rows, "rows_per_step": rows_per_step,
-                   "form": "all decode steps verified as one batch", "extras_mode": args.extras_mode},
+                   "form": "all decode steps verified as one batch", "extras_mode": args.extras_mode,
+                   "verifier": "top-%d" % args.topk if topk else "adaptive threshold"},
         "roofline": roofline, "cpu_baseline": cpu, "latency": latency,
         "tokens_per_decode_step": round(trace.mean_accept_len, 3), "setup_s": round(setup_s, 1),
     }

@@ -201,6 +201,26 @@ int aasd_verify(const void *logits, int32_t dt, int32_t B, int32_t C, int32_t k,
                 void *stream);
 
 /*
+ * Top-k verification, the ablation of Sec. 4.4 (topk = 5 there): same rows, cascade, longest candidate
+ * and next token as aasd_verify, but a draft token is accepted iff fewer than `topk` tokens of the row
+ * that verifies it have a strictly larger logit (ties with the topk-th largest logit pass).  No
+ * probabilities are formed: comparisons of logits only, so every output is exact.
+ *
+ * DEVICE in : logits[B, 1 + C*k, V] (layout as aasd_verify), drafts[B,C,k], draft_len[B,C]
+ * DEVICE out: accept_len[B], best_cand[B], next_token[B] i32 (required); row_argmax[B, 1 + C*k] i32 and
+ *             tok_pass[B,C,k] u8 (1 = within the top `topk`; 0 otherwise and beyond draft_len) (NULL = not wanted)
+ * workspace : DEVICE scratch of at least aasd_verify_topk_workspace_bytes(B, C, k, V, dt) bytes, 16-byte
+ *             aligned; needs no initialisation.
+ * Parameters: 1 <= topk <= 8; the others as for aasd_verify.
+ */
+size_t aasd_verify_topk_workspace_bytes(int32_t B, int32_t C, int32_t k, int32_t V, int32_t dt);
+int aasd_verify_topk(const void *logits, int32_t dt, int32_t B, int32_t C, int32_t k, int32_t V,
+                     int64_t row_stride, int64_t seq_stride, const int32_t *drafts,
+                     const int32_t *draft_len, int32_t topk, int32_t *accept_len, int32_t *best_cand,
+                     int32_t *next_token, int32_t *row_argmax, uint8_t *tok_pass, void *workspace,
+                     size_t workspace_bytes, void *stream);
+
+/*
  * Draft tree and tree attention mask (Sec. 3.2, Eq. 2): the retrieved candidates and the
  * alignment extras of their positions are merged into one tree under the last committed token,
  * so that one forward pass of the target model can verify all of them.

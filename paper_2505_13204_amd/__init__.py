@@ -215,6 +215,53 @@ def verify(logits: torch.Tensor, drafts: torch.Tensor, draft_len: torch.Tensor, 
     return o
 
 
+def verify_topk_workspace_bytes(B: int, C: int, k: int, V: int, dt: int) -> int:
+    return int(_lib.load().aasd_verify_topk_workspace_bytes(B, C, k, V, dt))
+
+
+def verify_topk(logits: torch.Tensor, drafts: torch.Tensor, draft_len: torch.Tensor, topk: int = 5,
+                V: Optional[int] = None, want_rows: bool = True, want_tokens: bool = True,
+                workspace: Optional[torch.Tensor] = None, out: Optional[dict] = None):
+    """aasd_verify_topk over logits[B, R, row_stride], R = 1 + C*k, drafts [B,C,k], draft_len [B,C].
+
+    Returns a dict of device tensors: accept_len, best_cand, next_token [B]; row_argmax [B,R]; tok_pass [B,C,k]."""
+    _dev_check(logits, drafts, draft_len, workspace)
+    assert logits.dim() == 3 and logits.stride(2) == 1
+    B, R = logits.shape[0], logits.shape[1]
+    assert drafts.dtype == torch.int32 and drafts.is_contiguous() and draft_len.dtype == torch.int32
+    _, C, k = drafts.shape
+    assert R == 1 + C * k, (R, C, k)
+    row_stride = logits.stride(1)
+    seq_stride = logits.stride(0) if B > 1 else R * row_stride
+    V = logits.shape[2] if V is None else V
+    dev = logits.device
+    o = dict(out or {})
+    def need(name, shape, dtype, wanted=True):
+        if not wanted:
+            o[name] = None
+        elif o.get(name) is None:
+            o[name] = torch.empty(shape, dtype=dtype, device=dev)
+    need("accept_len", (B,), torch.int32)
+    need("best_cand", (B,), torch.int32)
+    need("next_token", (B,), torch.int32)
+    need("row_argmax", (B, R), torch.int32, want_rows)
+    need("tok_pass", (B, C, k), torch.uint8, want_tokens)
+    ws_bytes = verify_topk_workspace_bytes(B, C, k, V, _dtype_code(logits))
+    if workspace is None:
+        workspace = o.get("workspace")
+    if workspace is None or workspace.numel() * workspace.element_size() < ws_bytes:
+        workspace = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
+    rc = _lib.load().aasd_verify_topk(
+        logits.data_ptr(), _dtype_code(logits), B, C, k, V, row_stride, seq_stride,
+        drafts.data_ptr(), draft_len.data_ptr(), int(topk),
+        o["accept_len"].data_ptr(), o["best_cand"].data_ptr(), o["next_token"].data_ptr(),
+        _ptr(o["row_argmax"]), _ptr(o["tok_pass"]), workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+        _stream(dev))
+    _check(rc)
+    o["workspace"] = workspace
+    return o
+
+
 def build_tree(drafts: torch.Tensor, draft_len: torch.Tensor, strict: Optional[torch.Tensor] = None,
                draft_extras: Optional[torch.Tensor] = None, root_tok: Optional[torch.Tensor] = None,
                max_nodes: int = 64, want_mask: bool = True, want_cand_node: bool = True, out: Optional[dict] = None):

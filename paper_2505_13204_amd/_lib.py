@@ -54,6 +54,12 @@ def load():
         c_void_p, c_void_p, c_void_p, c_float, c_float, c_uint32,
         c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
         c_void_p, c_size_t, c_void_p]
+    lib.aasd_verify_topk_workspace_bytes.restype = c_size_t
+    lib.aasd_verify_topk_workspace_bytes.argtypes = [c_int32, c_int32, c_int32, c_int32, c_int32]
+    lib.aasd_verify_topk.restype = c_int32
+    lib.aasd_verify_topk.argtypes = [
+        c_void_p, c_int32, c_int32, c_int32, c_int32, c_int32, c_int64, c_int64,
+        c_void_p, c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
     lib.aasd_build_tree.restype = c_int32
     lib.aasd_build_tree.argtypes = [
         c_void_p, c_void_p, c_void_p, c_void_p, c_int32, c_void_p, c_int32, c_int32, c_int32, c_int32,

@@ -15,6 +15,7 @@
 #include "row_sweep.hip.h"
 #include "tree.hip.h"
 #include "verify_tail.hip.h"
+#include "verify_topk.hip.h"
 
 namespace {
 
@@ -396,6 +397,91 @@ int aasd_verify(const void* logits, int32_t dt, int32_t B, int32_t C, int32_t k,
         hipLaunchKernelGGL(aasd::verify_tail_kernel<AASD_F32>, dim3((unsigned)B), dim3(aasd::kTailBlock), 0, s, tp);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(AASD_ERR_LAUNCH, "verify tail launch failed: %s", hipGetErrorString(e));
+    return AASD_OK;
+}
+
+size_t aasd_verify_topk_workspace_bytes(int32_t B, int32_t C, int32_t k, int32_t V, int32_t dt)
+{
+    if (B < 0 || C < 1 || C > AASD_MAX_CANDIDATES || k < 1 || k > AASD_MAX_DRAFT || V <= 0 || !valid_dtype(dt)) return 0;
+    const int64_t rows = (int64_t)B * (1 + C * k);
+    const SweepPlan pl = plan_sweep(true, rows, V, dt);
+    // per-wave partials and candidate lists of the alignment-style sweep, then the K-th largest logit and the greedy pick of every row
+    return align16((size_t)rows * pl.npart * (sizeof(aasd::WavePartial) + aasd::kListCap * sizeof(int32_t))) +
+           (size_t)rows * (sizeof(float) + sizeof(int32_t));
+}
+
+int aasd_verify_topk(const void* logits, int32_t dt, int32_t B, int32_t C, int32_t k, int32_t V,
+                     int64_t row_stride, int64_t seq_stride, const int32_t* drafts,
+                     const int32_t* draft_len, int32_t topk, int32_t* accept_len, int32_t* best_cand,
+                     int32_t* next_token, int32_t* row_argmax, uint8_t* tok_pass, void* workspace,
+                     size_t workspace_bytes, void* stream)
+{
+    if (!valid_dtype(dt)) return fail(AASD_ERR_INVALID_ARG, "verify_topk: unknown dtype %d", dt);
+    if (B < 0) return fail(AASD_ERR_INVALID_ARG, "verify_topk: B = %d < 0", B);
+    if (C < 1 || C > AASD_MAX_CANDIDATES) return fail(AASD_ERR_INVALID_ARG, "verify_topk: C = %d outside [1,%d]", C, AASD_MAX_CANDIDATES);
+    if (k < 1 || k > AASD_MAX_DRAFT) return fail(AASD_ERR_INVALID_ARG, "verify_topk: k = %d outside [1,%d]", k, AASD_MAX_DRAFT);
+    if (V <= 0) return fail(AASD_ERR_INVALID_ARG, "verify_topk: V = %d <= 0", V);
+    if (topk < 1 || topk > AASD_MAX_CANDSET)
+        return fail(AASD_ERR_INVALID_ARG, "verify_topk: topk = %d outside [1,%d]", topk, AASD_MAX_CANDSET);
+    const int32_t R = 1 + C * k;
+    if (row_stride < V) return fail(AASD_ERR_INVALID_ARG, "verify_topk: row_stride %lld < V %d", (long long)row_stride, V);
+    if (seq_stride < (int64_t)R * row_stride)
+        return fail(AASD_ERR_INVALID_ARG, "verify_topk: seq_stride %lld < R*row_stride %lld", (long long)seq_stride, (long long)((int64_t)R * row_stride));
+    if (B == 0) return AASD_OK;
+    if (!logits || !drafts || !draft_len || !accept_len || !best_cand || !next_token)
+        return fail(AASD_ERR_INVALID_ARG, "verify_topk: null required pointer");
+    if (((uintptr_t)logits % elt_size(dt)) != 0)
+        return fail(AASD_ERR_UNSUPPORTED, "verify_topk: logits pointer is not aligned to its element size");
+    const size_t need = aasd_verify_topk_workspace_bytes(B, C, k, V, dt);
+    if (!workspace || workspace_bytes < need)
+        return fail(AASD_ERR_WORKSPACE, "verify_topk: workspace of %zu bytes needed, %zu given", need, workspace ? workspace_bytes : (size_t)0);
+    if (((uintptr_t)workspace % 16) != 0) return fail(AASD_ERR_WORKSPACE, "verify_topk: workspace is not 16-byte aligned");
+
+    hipStream_t s = (hipStream_t)stream;
+    const int64_t rows = (int64_t)B * R;
+    const SweepPlan pl = plan_sweep(true, rows, V, dt);
+    aasd::WavePartial* partials = (aasd::WavePartial*)workspace;
+    int32_t* lists = (int32_t*)((char*)workspace + (size_t)rows * pl.npart * sizeof(aasd::WavePartial));
+    char* after = (char*)workspace + align16((size_t)rows * pl.npart * (sizeof(aasd::WavePartial) + aasd::kListCap * sizeof(int32_t)));
+    float* kth = (float*)after;
+    int32_t* am = (int32_t*)(after + (size_t)rows * sizeof(float));
+
+    aasd::SweepParams sp{};
+    sp.logits = logits; sp.V = V; sp.row_stride = row_stride; sp.seq_stride = seq_stride; sp.rows_per_seq = R;
+    sp.next_tok = nullptr; sp.want_cand = 1; sp.cand_all = 1; sp.c = topk;
+    sp.nseg = pl.nseg; sp.seg_vecs = pl.seg_vecs; sp.partials = partials; sp.lists = lists;
+    size_t dyn = 0;
+    {
+        const size_t per_lane = (size_t)(pl.seg_vecs / pl.block) * elt_size(dt);
+        size_t stride = (per_lane + 15) / 16 * 16;
+        if ((stride / 16) % 2 == 0) stride += 16;
+        if (stride * pl.block <= kMaxChunkMaxLds) { dyn = stride * pl.block; sp.cm_enabled = 1; sp.cm_stride = (int32_t)stride; }
+    }
+    int rc = dt == AASD_BF16 ? launch_sweep<AASD_BF16, true, false>(sp, pl, rows, dyn, s)
+                             : launch_sweep<AASD_F32, true, false>(sp, pl, rows, dyn, s);
+    if (rc != AASD_OK) return rc;
+
+    aasd::RowKthParams kp{};
+    kp.f.logits = logits; kp.f.V = V; kp.f.row_stride = row_stride; kp.f.rows = rows; kp.f.c = topk;
+    kp.f.partials = partials; kp.f.lists = lists; kp.f.npart = pl.npart;
+    kp.rows_per_seq = R; kp.seq_stride = seq_stride; kp.kth = kth; kp.argmax = am;
+    const int rows_per_block = aasd::kFinishBlock / aasd::kWave;
+    if (rows > kMaxUnitsPerLaunch * rows_per_block) return fail(AASD_ERR_UNSUPPORTED, "verify_topk: too many rows for one launch");
+    const unsigned grid = (unsigned)((rows + rows_per_block - 1) / rows_per_block);
+    if (dt == AASD_BF16) hipLaunchKernelGGL(aasd::row_kth_kernel<AASD_BF16>, dim3(grid), dim3(aasd::kFinishBlock), 0, s, kp);
+    else hipLaunchKernelGGL(aasd::row_kth_kernel<AASD_F32>, dim3(grid), dim3(aasd::kFinishBlock), 0, s, kp);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(AASD_ERR_LAUNCH, "row_kth launch failed: %s", hipGetErrorString(e));
+
+    aasd::VerifyTopkTailParams tp{};
+    tp.logits = logits; tp.B = B; tp.C = C; tp.k = k; tp.V = V; tp.row_stride = row_stride; tp.seq_stride = seq_stride;
+    tp.drafts = drafts; tp.draft_len = draft_len; tp.kth = kth; tp.argmax = am;
+    tp.accept_len = accept_len; tp.best_cand = best_cand; tp.next_token = next_token;
+    tp.row_argmax = row_argmax; tp.tok_pass = tok_pass;
+    if (dt == AASD_BF16) hipLaunchKernelGGL(aasd::verify_topk_tail_kernel<AASD_BF16>, dim3((unsigned)B), dim3(aasd::kWave), 0, s, tp);
+    else hipLaunchKernelGGL(aasd::verify_topk_tail_kernel<AASD_F32>, dim3((unsigned)B), dim3(aasd::kWave), 0, s, tp);
+    e = hipGetLastError();
+    if (e != hipSuccess) return fail(AASD_ERR_LAUNCH, "verify_topk tail launch failed: %s", hipGetErrorString(e));
     return AASD_OK;
 }
 

@@ -133,6 +133,92 @@ __device__ __forceinline__ void visit_listed_chunk(const AlignFinishParams& p, c
     }
 }
 
+// Exact top-c (logit descending, id ascending) of one row among the tokens above `znext`, from the chunk
+// positions that the sweep listed; called by all 64 lanes of the wave that owns the row.  `wp` is the lane's
+// partial (lane s holds partial s), thr2 the row's lower bound on its c-th largest logit.  cand_z / cand_i /
+// cand_n: kFinishCandCap LDS slots and a counter owned by this wave.
+template <int DT>
+__device__ __forceinline__ void row_topc_from_lists(const AlignFinishParams& p, const RowShape& rs, int64_t row,
+                                                    const WavePartial& wp, float znext, float thr2, int lane,
+                                                    float* cand_z, int* cand_i, unsigned* cand_n,
+                                                    float (&kz)[AASD_MAX_CANDSET], int (&ki)[AASD_MAX_CANDSET], int& nK)
+{
+    const int np = p.npart;
+    // inclusive prefix of the list lengths: entry e of the row belongs to the first partial whose prefix exceeds e
+    int incl = lane < np ? wp.nlist : 0;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int up = __shfl_up(incl, o);
+        if (lane >= o) incl += up;
+    }
+    const int total = __shfl(incl, 63);
+    auto locate = [&](int e, int& part, int& entry) {  // all lanes call it together
+        // binary search for the number of partials whose inclusive prefix is <= e
+        int pos = 0;
+#pragma unroll
+        for (int step = 32; step > 0; step >>= 1) {
+            const int probe = pos + step;
+            const int v = __shfl(incl, probe - 1 < 63 ? probe - 1 : 63);
+            if (probe <= np && v <= e) pos = probe;
+        }
+        part = pos < np ? pos : np - 1;
+        const int before = __shfl(incl, pos > 0 ? pos - 1 : 0);
+        entry = e - (pos > 0 ? before : 0);
+    };
+    if (lane == 0) *cand_n = 0;
+    for (int e0 = 0; e0 < total; e0 += kWave) {
+        const int e = e0 + lane;
+        int part, entry;
+        locate(e, part, entry);
+        if (e < total) {
+            visit_listed_chunk<DT>(p, rs, row, part, entry, [&](float z, int idx) {
+                if (z > znext && z >= thr2) {
+                    const unsigned pos = atomicAdd(&*cand_n, 1u);
+                    if (pos < (unsigned)kFinishCandCap) { cand_z[pos] = z; cand_i[pos] = idx; }
+                }
+            });
+        }
+    }
+    __threadfence_block();
+    const unsigned n = *cand_n;
+    if (n <= (unsigned)kFinishCandCap) {
+        constexpr int kPerLane = kFinishCandCap / kWave;
+        float lz[kPerLane];
+        int li[kPerLane];
+#pragma unroll
+        for (int q = 0; q < kPerLane; ++q) {
+            const int e = lane + q * kWave;
+            lz[q] = e < (int)n ? cand_z[e] : -INFINITY;
+            li[q] = e < (int)n ? cand_i[e] : 0x7fffffff;
+        }
+        wave_topc<kPerLane>(lz, li, p.c, kz, ki, nK);
+    } else {
+        // very many ties near the top: c exact rounds of "best token after the previous pick"
+        float pz = INFINITY;
+        int pi = -1;
+        for (int r = 0; r < p.c; ++r) {
+            float bz = -INFINITY;
+            int bi = 0x7fffffff;
+            for (int e0 = 0; e0 < total; e0 += kWave) {
+                const int e = e0 + lane;
+                int part, entry;
+                locate(e, part, entry);
+                if (e < total) {
+                    visit_listed_chunk<DT>(p, rs, row, part, entry, [&](float z, int idx) {
+                        const bool after_prev = (r == 0) || z < pz || (z == pz && idx > pi);
+                        if (z > znext && after_prev && better(z, idx, bz, bi)) { bz = z; bi = idx; }
+                    });
+                }
+            }
+            wave_best(bz, bi);
+            if (bi == 0x7fffffff) break;
+            pz = bz; pi = bi;
+            set_pick(kz, ki, r, bz, bi);
+            nK = r + 1;
+        }
+    }
+}
+
 template <int DT>
 __global__ __launch_bounds__(kFinishBlock) void align_finish_kernel(AlignFinishParams p)
 {
@@ -179,81 +265,8 @@ __global__ __launch_bounds__(kFinishBlock) void align_finish_kernel(AlignFinishP
     int nK = 0;
 #pragma unroll
     for (int q = 0; q < AASD_MAX_CANDSET; ++q) { kz[q] = 0.f; ki[q] = -1; }
-    if (mis && p.m_x > 0) {
-        // inclusive prefix of the list lengths: entry e of the row belongs to the first partial whose prefix exceeds e
-        int incl = lane < np ? wp.nlist : 0;
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            const int up = __shfl_up(incl, o);
-            if (lane >= o) incl += up;
-        }
-        const int total = __shfl(incl, 63);
-        auto locate = [&](int e, int& part, int& entry) {  // all lanes call it together
-            // binary search for the number of partials whose inclusive prefix is <= e
-            int pos = 0;
-#pragma unroll
-            for (int step = 32; step > 0; step >>= 1) {
-                const int probe = pos + step;
-                const int v = __shfl(incl, probe - 1 < 63 ? probe - 1 : 63);
-                if (probe <= np && v <= e) pos = probe;
-            }
-            part = pos < np ? pos : np - 1;
-            const int before = __shfl(incl, pos > 0 ? pos - 1 : 0);
-            entry = e - (pos > 0 ? before : 0);
-        };
-        if (lane == 0) cand_n[wid] = 0;
-        for (int e0 = 0; e0 < total; e0 += kWave) {
-            const int e = e0 + lane;
-            int part, entry;
-            locate(e, part, entry);
-            if (e < total) {
-                visit_listed_chunk<DT>(p, rs, row, part, entry, [&](float z, int idx) {
-                    if (z > znext && z >= thr2) {
-                        const unsigned pos = atomicAdd(&cand_n[wid], 1u);
-                        if (pos < (unsigned)kFinishCandCap) { cand_z[wid][pos] = z; cand_i[wid][pos] = idx; }
-                    }
-                });
-            }
-        }
-        __threadfence_block();
-        const unsigned n = cand_n[wid];
-        if (n <= (unsigned)kFinishCandCap) {
-            constexpr int kPerLane = kFinishCandCap / kWave;
-            float lz[kPerLane];
-            int li[kPerLane];
-#pragma unroll
-            for (int q = 0; q < kPerLane; ++q) {
-                const int e = lane + q * kWave;
-                lz[q] = e < (int)n ? cand_z[wid][e] : -INFINITY;
-                li[q] = e < (int)n ? cand_i[wid][e] : 0x7fffffff;
-            }
-            wave_topc<kPerLane>(lz, li, p.c, kz, ki, nK);
-        } else {
-            // very many ties near the top: c exact rounds of "best token after the previous pick"
-            float pz = INFINITY;
-            int pi = -1;
-            for (int r = 0; r < p.c; ++r) {
-                float bz = -INFINITY;
-                int bi = 0x7fffffff;
-                for (int e0 = 0; e0 < total; e0 += kWave) {
-                    const int e = e0 + lane;
-                    int part, entry;
-                    locate(e, part, entry);
-                    if (e < total) {
-                        visit_listed_chunk<DT>(p, rs, row, part, entry, [&](float z, int idx) {
-                            const bool after_prev = (r == 0) || z < pz || (z == pz && idx > pi);
-                            if (z > znext && after_prev && better(z, idx, bz, bi)) { bz = z; bi = idx; }
-                        });
-                    }
-                }
-                wave_best(bz, bi);
-                if (bi == 0x7fffffff) break;
-                pz = bz; pi = bi;
-                set_pick(kz, ki, r, bz, bi);
-                nK = r + 1;
-            }
-        }
-    }
+    if (mis && p.m_x > 0)
+        row_topc_from_lists<DT>(p, rs, row, wp, znext, thr2, lane, cand_z[wid], cand_i[wid], &cand_n[wid], kz, ki, nK);
 
     if (lane == 0) {
         p.argmax[row] = am;

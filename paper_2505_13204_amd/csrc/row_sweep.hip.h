@@ -53,6 +53,7 @@ struct SweepParams {
     int64_t row_stride;    // elements
     int64_t seq_stride;    // elements, verification only (rows_per_seq rows per sequence)
     int32_t rows_per_seq;  // 1 for prefill rows
+    int32_t cand_all;      // alignment sweep: list the top-c candidates of EVERY row (as if the next token had logit -inf)
     const int32_t* rows_used;  // optional [sequences]: rows of a sequence at or beyond max(this count, 1) are skipped
     const int32_t* next_tok;  // alignment sampling only
     int32_t want_cand;     // candidates are wanted (m > 0)
@@ -517,8 +518,9 @@ __device__ __forceinline__ void sweep_unit(const SweepParams& p, int64_t row, in
         nt = p.next_tok ? p.next_tok[row] : -1;
         if (nt >= p.V) nt = -1;
         if (nt >= 0) znext = load_elt<DT>(row_s.base, nt);
+        if (p.cand_all) znext = -INFINITY;
     }
-    const bool has_next = ALIGN && nt >= 0;
+    const bool has_next = ALIGN && (nt >= 0 || p.cand_all);
     unsigned char* cm_lane = cm + (size_t)tid * (size_t)p.cm_stride;
     if (!process_wave<DT, ALIGN, COUNT, false, BLOCK, U>(p, rs, has_next, znext, sh, cm_lane, row_s, out, out_list))
         process_wave<DT, ALIGN, COUNT, true, BLOCK, U>(p, rs, has_next, znext, sh, cm_lane, row_s, out, out_list);

@@ -151,3 +151,26 @@ def test_verify_tree_rejects_invalid_arguments(lib):
     assert lib.aasd_verify_tree_workspace_bytes(64, 64, 128256, 1) == 64 * 64 * 16 * 32   # 4096 rows, 16 waves per row
     assert lib.aasd_verify_tree_workspace_bytes(1, 0, 100, 1) == 0
     assert lib.aasd_verify_tree_workspace_bytes(1, 257, 100, 1) == 0
+
+
+def _verify_topk(lib, **kw):
+    a = dict(logits=FAKE, dt=1, B=2, C=2, k=4, V=100, rs=100, ss=900, drafts=FAKE, dl=FAKE, topk=5, al=FAKE, bc=FAKE,
+             nt=FAKE, ra=None, tp=None, ws=FAKE, wsb=1 << 20, stream=None)
+    a.update(kw)
+    return lib.aasd_verify_topk(a["logits"], a["dt"], a["B"], a["C"], a["k"], a["V"], a["rs"], a["ss"], a["drafts"],
+                                a["dl"], a["topk"], a["al"], a["bc"], a["nt"], a["ra"], a["tp"], a["ws"], a["wsb"],
+                                a["stream"])
+
+
+def test_verify_topk_rejects_invalid_arguments(lib):
+    for kw in [dict(dt=3), dict(B=-1), dict(C=0), dict(C=33), dict(k=0), dict(k=17), dict(V=0), dict(rs=99), dict(ss=899),
+               dict(topk=0), dict(topk=9), dict(logits=None), dict(drafts=None), dict(dl=None), dict(al=None),
+               dict(bc=None), dict(nt=None)]:
+        assert _verify_topk(lib, **kw) == INVALID, kw
+        assert b"verify_topk" in lib.aasd_last_error()
+    assert _verify_topk(lib, logits=FAKE + 1) == UNSUPPORTED
+    assert _verify_topk(lib, ws=None) == WORKSPACE
+    assert _verify_topk(lib, wsb=lib.aasd_verify_topk_workspace_bytes(2, 2, 4, 100, 1) - 1) == WORKSPACE
+    assert _verify_topk(lib, B=0) == 0
+    assert lib.aasd_verify_topk_workspace_bytes(2, 2, 4, 100, 1) > lib.aasd_verify_workspace_bytes(2, 2, 4, 100, 1)
+    assert lib.aasd_verify_topk_workspace_bytes(2, 0, 4, 100, 1) == 0

@@ -514,3 +514,70 @@ def test_gumbel_extras_many_rows_hit_near_decisions_and_zero_probability_tokens(
     lo, hi = int((margin < 0.5 * bk.NEAR_GUMBEL).sum()), int((margin < 2 * bk.NEAR_GUMBEL).sum())
     assert lo <= int(near.item()) <= hi, (lo, int(near.item()), hi)
     print("gumbel many rows", tally, "kernel near", int(near.item()), "oracle bracket", lo, hi)
+
+
+# --------------------------------------------------------------------------- top-k verification (Sec. 4.4 ablation)
+def _topk_case(rng, B, C, k, V, dtype, ties):
+    R = 1 + C * k
+    z = rng.standard_normal((B, R, V)).astype(np.float32) * 1.5
+    if ties:
+        z = np.round(z * 2) / 2
+    zd = _dev_logits(z.reshape(B * R, V), dtype).view(B, R, V)
+    zf = zd.float().cpu().numpy()
+    order = np.argsort(-zf, axis=2, kind="stable")
+    drafts = np.empty((B, C, k), np.int32)
+    for b in range(B):
+        for c in range(C):
+            for j in range(k):
+                rho = 0 if j == 0 else 1 + c * k + (j - 1)
+                drafts[b, c, j] = order[b, rho, min(V - 1, int(rng.geometric(0.25)) - 1)]
+    drafts[rng.random((B, C, k)) < 0.02] = V + 3
+    dl = rng.integers(0, k + 1, size=(B, C)).astype(np.int32)
+    return zd, drafts, dl
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("B,C,k,V", [(1, 1, 1, 3), (3, 1, 4, 32000), (2, 3, 5, 4099), (5, 16, 8, 1000), (2, 32, 16, 300),
+                                     (600, 1, 8, 2000)])
+def test_verify_topk_parity(dtype, B, C, k, V):
+    rng = np.random.default_rng(B * 100 + C + k)
+    t = lambda a, dt: torch.as_tensor(np.ascontiguousarray(a), device=DEV).to(dt)
+    for ties in (False, True):
+        zd, drafts, dl = _topk_case(rng, B, C, k, V, dtype, ties)
+        bits = synth.to_host_bits(zd)
+        for topk in (1, 2, 5, 8):
+            ref = oracle.verify_topk(bits, drafts, dl, topk=topk)
+            got = bk.to_np(aasd.verify_topk(zd, t(drafts, torch.int32), t(dl, torch.int32), topk=topk))
+            torch.cuda.synchronize()
+            for name in ("accept_len", "best_cand", "next_token", "row_argmax"):
+                np.testing.assert_array_equal(got[name], ref[name], err_msg=f"{name} topk={topk} ties={ties}")
+            want = ((ref["tok_rank"] >= 0) & (ref["tok_rank"] < topk)).astype(np.uint8)
+            np.testing.assert_array_equal(got["tok_pass"], want, err_msg=f"tok_pass topk={topk} ties={ties}")
+        assert ref["accept_len"].max() >= min(1, dl.max())
+
+
+def test_verify_topk_top1_equals_strict_verification_and_full_shape():
+    """k = 1 is strict verification (same decisions as aasd_verify with every token strict); also the benched
+    shape of config 2 (512 x 9 rows of V = 128256 bf16) against the oracle on sampled sequences."""
+    w = synth.WORKLOADS["llama3_single"]
+    rng = np.random.default_rng(6)
+    B = 512
+    g = torch.Generator(device=DEV).manual_seed(2)
+    zd = (torch.randn((B, w.R, w.V), generator=g, device=DEV) * 1.7).to(torch.bfloat16)
+    top = torch.topk(zd.float(), 6, dim=2).indices.cpu().numpy()
+    drafts = np.empty((B, 1, w.k), np.int32)
+    for j in range(w.k):
+        drafts[:, 0, j] = top[np.arange(B), j, rng.geometric(0.5, size=B).clip(1, 6) - 1]
+    dl = np.full((B, 1), w.k, np.int32)
+    t = lambda a, dt: torch.as_tensor(np.ascontiguousarray(a), device=DEV).to(dt)
+    one = bk.to_np(aasd.verify_topk(zd, t(drafts, torch.int32), t(dl, torch.int32), topk=1))
+    strict = bk.to_np(aasd.verify(zd, t(drafts, torch.int32), t(dl, torch.int32), t(np.ones_like(drafts), torch.uint8)))
+    five = bk.to_np(aasd.verify_topk(zd, t(drafts, torch.int32), t(dl, torch.int32), topk=5))
+    torch.cuda.synchronize()
+    for name in ("accept_len", "best_cand", "next_token", "row_argmax"):
+        np.testing.assert_array_equal(one[name], strict[name], err_msg=name)
+    assert (five["accept_len"] >= one["accept_len"]).all() and five["accept_len"].mean() > one["accept_len"].mean() + 1
+    for b in rng.choice(B, 4, replace=False):
+        ref = oracle.verify_topk(synth.to_host_bits(zd[b:b + 1]), drafts[b:b + 1], dl[b:b + 1], topk=5)
+        assert ref["accept_len"][0] == five["accept_len"][b] and ref["next_token"][0] == five["next_token"][b]
+        assert (((ref["tok_rank"] >= 0) & (ref["tok_rank"] < 5)) == five["tok_pass"][b:b + 1].astype(bool)).all()
