@@ -43,6 +43,9 @@ def parse():
     ap.add_argument("--extras-mode", default="top", choices=["top", "sample", "gumbel"],
                     help="how alignment sampling chooses the extras: best-ranked (Fig. 2), seeded draws among the top-c, "
                          "or seeded draws from the whole row (a second, ALU-bound kernel over the misaligned rows)")
+    ap.add_argument("--retrieval", default="scan", choices=["scan", "pool"],
+                    help="n-gram retrieval by the stateless scan of the token buffer, or through the persistent draft pool "
+                         "(built in set-up; the latency loop then does an incremental update and a lookup per step)")
     ap.add_argument("--verifier", default="adaptive", choices=["adaptive", "topk"],
                     help="conditional verification with the entropy-adaptive threshold (Eq. 4-6), or the top-k ablation (Sec. 4.4)")
     ap.add_argument("--topk", type=int, default=5)
@@ -174,7 +177,22 @@ def main():
     tokens_b = torch.from_numpy(np.tile(trace.tokens, (S, 1))).to(dev).contiguous()          # [S*B, cap]
     len_b = torch.from_numpy(np.concatenate([s.length for s in trace.steps]).astype(np.int32)).to(dev)
     plen_b = torch.full((BB,), w.L, dtype=torch.int32, device=dev)
-    r_out = aasd.retrieve_drafts(tokens_b, len_b, plen_b, w.n_min, w.n_max, w.k, w.C)
+    use_pool = args.retrieval == "pool"
+    pool = None
+    if use_pool:   # one pool per sequence of the batch, indexed up to the final length of the token buffers
+        pool = aasd.DraftPool(BB, tok_cap, w.n_min, w.n_max, dev)
+        full_len = torch.from_numpy(np.tile(trace.length, S).astype(np.int32)).to(dev)
+        t_build = time.perf_counter()
+        pool.update(tokens_b, full_len, reset=True)
+        torch.cuda.synchronize()
+        pool_build_ms = (time.perf_counter() - t_build) * 1e3
+
+    def do_retrieve(out=None):
+        if use_pool:
+            return pool.retrieve(tokens_b, len_b, plen_b, w.k, w.C, out=out)
+        return aasd.retrieve_drafts(tokens_b, len_b, plen_b, w.n_min, w.n_max, w.k, w.C, out=out)
+
+    r_out = do_retrieve()
     ws = verify_ws(BB)
     v_out = do_verify(verify_logits, r_out["drafts"], r_out["draft_len"], r_out["strict"], workspace=ws)
     torch.cuda.synchronize()
@@ -188,7 +206,7 @@ def main():
 
     def one_pass():
         aasd.align_sample(prefill, next_tok_d, m=w.m, c=w.c, mode=mode, seed=w.seed, out=align_out)
-        aasd.retrieve_drafts(tokens_b, len_b, plen_b, w.n_min, w.n_max, w.k, w.C, out=r_out)
+        do_retrieve(out=r_out)
         do_verify(verify_logits, r_out["drafts"], r_out["draft_len"], r_out["strict"], workspace=ws, out=v_out)
 
     for _ in range(args.warmup):
@@ -210,7 +228,7 @@ def main():
             aasd.set_draw_events(kev[i][4], kev[i][5])
         aasd.align_sample(prefill, next_tok_d, m=w.m, c=w.c, mode=mode, seed=w.seed, out=align_out)
         ev[i][1].record()
-        aasd.retrieve_drafts(tokens_b, len_b, plen_b, w.n_min, w.n_max, w.k, w.C, out=r_out)
+        do_retrieve(out=r_out)
         ev[i][2].record()
         aasd.set_sweep_events(kev[i][2], kev[i][3])
         do_verify(verify_logits, r_out["drafts"], r_out["draft_len"], r_out["strict"], workspace=ws, out=v_out)
@@ -263,7 +281,8 @@ def main():
                          "frac": round(align_gbs / HBM_PEAK_GBS, 4), "call_ms": round(align_ms, 4)},
         "verify": {"rows": verify_rows, "sweep_kernel_ms": round(verify_sweep_ms, 4), "GB/s": round(verify_gbs, 1),
                    "frac": round(verify_gbs / HBM_PEAK_GBS, 4), "call_ms": round(verify_ms, 4)},
-        "retrieve_drafts": {"sequences": BB, "call_ms": round(retr_ms, 4)},
+        "retrieve_drafts": {"sequences": BB, "call_ms": round(retr_ms, 4), "through": args.retrieval,
+                            **({"pool_build_ms": round(pool_build_ms, 3), "pool_MB": round(pool.nbytes / 1e6, 1)} if use_pool else {})},
         "note": "kernel times: HIP events recorded by the library around the sweep kernel alone; call times include the finish kernels",
     }
 
@@ -272,6 +291,9 @@ def main():
     if not args.no_latency and w.B * w.R <= 512:
         n_lat = min(S, 256)
         outs_r = aasd.retrieve_drafts(tokens_b[:w.B], len_b[:w.B], plen_b[:w.B], w.n_min, w.n_max, w.k, w.C)
+        if use_pool:
+            pool1 = aasd.DraftPool(w.B, tok_cap, w.n_min, w.n_max, dev)
+            pool1.update(tokens_b[:w.B], plen_b[:w.B], reset=True)      # the prompt; every step then adds its new tokens
         ws1 = verify_ws(w.B)
         outs_v = do_verify(verify_logits[:w.B], outs_r["drafts"], outs_r["draft_len"], outs_r["strict"], workspace=ws1)
         torch.cuda.synchronize()
@@ -279,13 +301,17 @@ def main():
         e0.record()
         for s in range(n_lat):
             sl = slice(s * w.B, (s + 1) * w.B)
-            aasd.retrieve_drafts(tokens_b[sl], len_b[sl], plen_b[sl], w.n_min, w.n_max, w.k, w.C, out=outs_r)
+            if use_pool:
+                pool1.step(tokens_b[sl], len_b[sl], plen_b[sl], w.k, w.C, out=outs_r)
+            else:
+                aasd.retrieve_drafts(tokens_b[sl], len_b[sl], plen_b[sl], w.n_min, w.n_max, w.k, w.C, out=outs_r)
             do_verify(verify_logits[sl], outs_r["drafts"], outs_r["draft_len"], outs_r["strict"], workspace=ws1, out=outs_v)
         e1.record()
         torch.cuda.synchronize()
         latency = {"decode_steps": n_lat, "rows_per_step": w.B * w.R,
                    "us_per_decode_step": round(e0.elapsed_time(e1) * 1e3 / n_lat, 2),
-                   "note": "retrieve + verify launched back to back per decode step, no host sync"}
+                   "note": ("pool step (incremental update + lookup in one launch) + verify" if use_pool else "retrieve + verify") +
+                           " launched back to back per decode step, no host sync"}
 
     # ---------------------------------------------------------------- CPU oracle on a bounded sample (context)
     cpu = None
@@ -321,7 +347,7 @@ def main():
                    "n_gram": [w.n_min, w.n_max], "decode_steps": S, "prefill_rows": prefill_rows,
                    "verify_rows": verify_rows, "rows_per_step": rows_per_step,
                    "form": "all decode steps verified as one batch", "extras_mode": args.extras_mode,
-                   "verifier": "top-%d" % args.topk if topk else "adaptive threshold"},
+                   "verifier": "top-%d" % args.topk if topk else "adaptive threshold", "retrieval": args.retrieval},
         "roofline": roofline, "cpu_baseline": cpu, "latency": latency,
         "tokens_per_decode_step": round(trace.mean_accept_len, 3), "setup_s": round(setup_s, 1),
     }

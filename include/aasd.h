@@ -201,6 +201,43 @@ int aasd_verify(const void *logits, int32_t dt, int32_t B, int32_t C, int32_t k,
                 void *stream);
 
 /*
+ * Persistent draft pool (Sec. 3.1; Algorithm 1: the dictionary from n-grams to the positions after their
+ * occurrences, initialised over the prompt and then extended by the windows that end in the new tokens).
+ * aasd_pool_retrieve returns exactly what aasd_retrieve_drafts returns for the same arguments, but
+ * follows hash chains kept in `pool` instead of scanning the context.
+ *
+ * `pool` is DEVICE memory owned by the caller, at least aasd_pool_bytes(B, capacity, n_min, n_max) bytes,
+ * 16-byte aligned; the same B, capacity, n_min, n_max must be passed to every call on one pool.  It needs
+ * no initialisation before the first aasd_pool_update with reset != 0.
+ *
+ * aasd_pool_update: with reset != 0, forget everything and index tokens[b, 0 .. len[b]) for every key length
+ * in [n_min, n_max]; with reset == 0, index the positions added since the previous call (len[b] may only
+ * grow between calls, and tokens that were indexed must not change).  len[b] beyond capacity is cut there.
+ * aasd_pool_retrieve: the context tokens[b, 0 .. len[b]) must have been indexed at least up to len[b]; it may
+ * be called with a smaller len[b] than was indexed (later positions are ignored).  All other arguments,
+ * outputs and limits are those of aasd_retrieve_drafts.
+ * aasd_pool_step: one decode step in one launch, aasd_pool_update(reset = 0) followed by aasd_pool_retrieve.
+ * Calls on one pool must be ordered (same stream, or synchronised by the caller).
+ * Parameters: 1 <= capacity <= 2^24 tokens per sequence, 1 <= n_min <= n_max <= 8, B >= 0.
+ */
+size_t aasd_pool_bytes(int32_t B, int32_t capacity, int32_t n_min, int32_t n_max);
+int aasd_pool_update(void *pool, size_t pool_bytes, int32_t B, int32_t capacity, int32_t n_min,
+                     int32_t n_max, const int32_t *tokens, int64_t tok_stride, const int32_t *len,
+                     int32_t reset, void *stream);
+int aasd_pool_retrieve(const void *pool, size_t pool_bytes, int32_t B, int32_t capacity, int32_t n_min,
+                       int32_t n_max, const int32_t *tokens, int64_t tok_stride, const int32_t *len,
+                       const int32_t *prompt_len, int32_t k, int32_t C, const int32_t *extras,
+                       const uint8_t *n_extras, int32_t m, int64_t extras_stride, int32_t *drafts,
+                       int32_t *draft_len, int32_t *src_pos, int32_t *n_cand, int32_t *key_len,
+                       int32_t *draft_extras, uint8_t *strict, void *stream);
+int aasd_pool_step(void *pool, size_t pool_bytes, int32_t B, int32_t capacity, int32_t n_min,
+                   int32_t n_max, const int32_t *tokens, int64_t tok_stride, const int32_t *len,
+                   const int32_t *prompt_len, int32_t k, int32_t C, const int32_t *extras,
+                   const uint8_t *n_extras, int32_t m, int64_t extras_stride, int32_t *drafts,
+                   int32_t *draft_len, int32_t *src_pos, int32_t *n_cand, int32_t *key_len,
+                   int32_t *draft_extras, uint8_t *strict, void *stream);
+
+/*
  * Top-k verification, the ablation of Sec. 4.4 (topk = 5 there): same rows, cascade, longest candidate
  * and next token as aasd_verify, but a draft token is accepted iff fewer than `topk` tokens of the row
  * that verifies it have a strictly larger logit (ties with the topk-th largest logit pass).  No

@@ -160,6 +160,74 @@ def retrieve_drafts(tokens: torch.Tensor, length: torch.Tensor, prompt_len: torc
     return o
 
 
+class DraftPool:
+    """Persistent draft pool (aasd_pool_*): device memory plus the parameters that every call repeats."""
+
+    def __init__(self, B: int, capacity: int, n_min: int, n_max: int, device):
+        self.B, self.capacity, self.n_min, self.n_max = B, capacity, n_min, n_max
+        nbytes = int(_lib.load().aasd_pool_bytes(B, capacity, n_min, n_max))
+        if nbytes == 0 and B > 0:
+            raise ValueError("invalid pool parameters")
+        self.mem = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=device)
+
+    @property
+    def nbytes(self) -> int:
+        return self.mem.numel()
+
+    def update(self, tokens: torch.Tensor, length: torch.Tensor, reset: bool = False):
+        """Index tokens[b, :length[b]]: everything (reset) or the positions added since the last call."""
+        _dev_check(tokens, length)
+        assert tokens.dim() == 2 and tokens.dtype == torch.int32 and tokens.stride(1) == 1 and tokens.shape[0] == self.B
+        assert length.dtype == torch.int32 and length.shape == (self.B,)
+        tok_stride = tokens.stride(0) if self.B > 1 else tokens.shape[1]
+        rc = _lib.load().aasd_pool_update(self.mem.data_ptr(), self.nbytes, self.B, self.capacity, self.n_min, self.n_max,
+                                          tokens.data_ptr(), tok_stride, length.data_ptr(), 1 if reset else 0,
+                                          _stream(tokens.device))
+        _check(rc)
+
+    def step(self, *args, **kw):
+        """aasd_pool_step: index the tokens added since the last call, then look up (one launch)."""
+        return self.retrieve(*args, _update_first=True, **kw)
+
+    def retrieve(self, tokens: torch.Tensor, length: torch.Tensor, prompt_len: torch.Tensor, k: int, C: int,
+                 extras: Optional[torch.Tensor] = None, n_extras: Optional[torch.Tensor] = None, m: int = 0,
+                 extras_stride: int = 0, want_draft_extras: Optional[bool] = None, out: Optional[dict] = None,
+                 _update_first: bool = False):
+        """aasd_pool_retrieve: the outputs of retrieve_drafts, found through the pool."""
+        _dev_check(tokens, length, prompt_len, extras, n_extras)
+        assert tokens.dim() == 2 and tokens.dtype == torch.int32 and tokens.stride(1) == 1 and tokens.shape[0] == self.B
+        B = self.B
+        tok_stride = tokens.stride(0) if B > 1 else tokens.shape[1]
+        assert length.dtype == torch.int32 and prompt_len.dtype == torch.int32
+        dev = tokens.device
+        have_table = extras is not None
+        if want_draft_extras is None:
+            want_draft_extras = have_table
+        o = dict(out or {})
+        def need(name, shape, dtype):
+            if o.get(name) is None:
+                o[name] = torch.empty(shape, dtype=dtype, device=dev)
+        need("drafts", (B, C, k), torch.int32)
+        need("draft_len", (B, C), torch.int32)
+        need("src_pos", (B, C), torch.int32)
+        need("n_cand", (B,), torch.int32)
+        need("key_len", (B,), torch.int32)
+        need("strict", (B, C, k), torch.uint8)
+        if want_draft_extras:
+            need("draft_extras", (B, C, k, m), torch.int32)
+        else:
+            o["draft_extras"] = None
+        fn = _lib.load().aasd_pool_step if _update_first else _lib.load().aasd_pool_retrieve
+        rc = fn(
+            self.mem.data_ptr(), self.nbytes, B, self.capacity, self.n_min, self.n_max,
+            tokens.data_ptr(), tok_stride, length.data_ptr(), prompt_len.data_ptr(), k, C,
+            _ptr(extras), _ptr(n_extras), m, extras_stride,
+            o["drafts"].data_ptr(), o["draft_len"].data_ptr(), o["src_pos"].data_ptr(), o["n_cand"].data_ptr(),
+            o["key_len"].data_ptr(), _ptr(o["draft_extras"]), o["strict"].data_ptr(), _stream(dev))
+        _check(rc)
+        return o
+
+
 def verify_workspace_bytes(B: int, C: int, k: int, V: int, dt: int) -> int:
     return int(_lib.load().aasd_verify_workspace_bytes(B, C, k, V, dt))
 

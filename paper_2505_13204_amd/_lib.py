@@ -54,6 +54,18 @@ def load():
         c_void_p, c_void_p, c_void_p, c_float, c_float, c_uint32,
         c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
         c_void_p, c_size_t, c_void_p]
+    lib.aasd_pool_bytes.restype = c_size_t
+    lib.aasd_pool_bytes.argtypes = [c_int32, c_int32, c_int32, c_int32]
+    lib.aasd_pool_update.restype = c_int32
+    lib.aasd_pool_update.argtypes = [c_void_p, c_size_t, c_int32, c_int32, c_int32, c_int32, c_void_p, c_int64, c_void_p,
+                                     c_int32, c_void_p]
+    lib.aasd_pool_retrieve.restype = c_int32
+    lib.aasd_pool_retrieve.argtypes = [
+        c_void_p, c_size_t, c_int32, c_int32, c_int32, c_int32, c_void_p, c_int64, c_void_p, c_void_p, c_int32, c_int32,
+        c_void_p, c_void_p, c_int32, c_int64,
+        c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
+    lib.aasd_pool_step.restype = c_int32
+    lib.aasd_pool_step.argtypes = list(lib.aasd_pool_retrieve.argtypes)
     lib.aasd_verify_topk_workspace_bytes.restype = c_size_t
     lib.aasd_verify_topk_workspace_bytes.argtypes = [c_int32, c_int32, c_int32, c_int32, c_int32]
     lib.aasd_verify_topk.restype = c_int32

@@ -12,6 +12,7 @@
 #include "retrieve.hip.h"
 #include "row_finish.hip.h"
 #include "gumbel.hip.h"
+#include "pool.hip.h"
 #include "row_sweep.hip.h"
 #include "tree.hip.h"
 #include "verify_tail.hip.h"
@@ -164,6 +165,23 @@ void launch_gumbel(int32_t dt, int m, unsigned grid, hipStream_t s, const aasd::
 }
 
 size_t align16(size_t n) { return (n + 15) & ~(size_t)15; }
+
+constexpr int32_t kMaxPoolCapacity = 1 << 24;
+
+// Where the parts of a draft pool lie in the caller's buffer.
+bool pool_layout(int32_t B, int32_t capacity, int32_t n_min, int32_t n_max, aasd::PoolLayout& lay, size_t& bytes)
+{
+    if (B < 0 || capacity < 1 || capacity > kMaxPoolCapacity || n_min < 1 || n_min > n_max || n_max > AASD_MAX_KEY) return false;
+    const int NL = n_max - n_min + 1;
+    int lg = 6;
+    while (((int64_t)1 << lg) < 2 * ((int64_t)capacity + 1)) ++lg;   // load factor at most one half
+    lay.B = B; lay.capacity = capacity; lay.n_min = n_min; lay.n_max = n_max; lay.log2_table = lg;
+    lay.counters = 0;
+    lay.tables = align16((size_t)B * NL * sizeof(int32_t));
+    lay.table_stride = align16((((size_t)1 << lg) + (size_t)capacity + 1) * sizeof(int32_t));
+    bytes = lay.tables + (size_t)B * NL * lay.table_stride;
+    return true;
+}
 
 }  // namespace
 
@@ -398,6 +416,100 @@ int aasd_verify(const void* logits, int32_t dt, int32_t B, int32_t C, int32_t k,
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(AASD_ERR_LAUNCH, "verify tail launch failed: %s", hipGetErrorString(e));
     return AASD_OK;
+}
+
+size_t aasd_pool_bytes(int32_t B, int32_t capacity, int32_t n_min, int32_t n_max)
+{
+    aasd::PoolLayout lay;
+    size_t bytes = 0;
+    return pool_layout(B, capacity, n_min, n_max, lay, bytes) ? bytes : 0;
+}
+
+int aasd_pool_update(void* pool, size_t pool_bytes, int32_t B, int32_t capacity, int32_t n_min, int32_t n_max,
+                     const int32_t* tokens, int64_t tok_stride, const int32_t* len, int32_t reset, void* stream)
+{
+    aasd::PoolLayout lay;
+    size_t need = 0;
+    if (!pool_layout(B, capacity, n_min, n_max, lay, need))
+        return fail(AASD_ERR_INVALID_ARG, "pool_update: need B >= 0, 1 <= capacity <= %d, 1 <= n_min <= n_max <= %d (got %d, %d, %d, %d)",
+                    kMaxPoolCapacity, AASD_MAX_KEY, B, capacity, n_min, n_max);
+    if (tok_stride < 1 || tok_stride > 0x7fffffffLL) return fail(AASD_ERR_INVALID_ARG, "pool_update: tok_stride = %lld out of range", (long long)tok_stride);
+    if (B == 0) return AASD_OK;
+    if (!tokens || !len) return fail(AASD_ERR_INVALID_ARG, "pool_update: null required pointer");
+    if (!pool || pool_bytes < need)
+        return fail(AASD_ERR_WORKSPACE, "pool_update: pool of %zu bytes needed, %zu given", need, pool ? pool_bytes : (size_t)0);
+    if (((uintptr_t)pool % 16) != 0) return fail(AASD_ERR_WORKSPACE, "pool_update: pool is not 16-byte aligned");
+    aasd::PoolUpdateParams q{};
+    q.pool = (char*)pool; q.lay = lay; q.tokens = tokens; q.tok_stride = tok_stride; q.len = len; q.reset = reset ? 1 : 0;
+    const int64_t grid = (int64_t)B * (n_max - n_min + 1);
+    if (grid > kMaxUnitsPerLaunch) return fail(AASD_ERR_UNSUPPORTED, "pool_update: too many sequences for one launch");
+    hipLaunchKernelGGL(aasd::pool_update_kernel, dim3((unsigned)grid), dim3(aasd::kWave), 0, (hipStream_t)stream, q);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(AASD_ERR_LAUNCH, "pool_update launch failed: %s", hipGetErrorString(e));
+    return AASD_OK;
+}
+
+static int pool_lookup(bool update_first, const void* pool, size_t pool_bytes, int32_t B, int32_t capacity, int32_t n_min,
+                       int32_t n_max, const int32_t* tokens, int64_t tok_stride, const int32_t* len,
+                       const int32_t* prompt_len, int32_t k, int32_t C, const int32_t* extras, const uint8_t* n_extras,
+                       int32_t m, int64_t extras_stride, int32_t* drafts, int32_t* draft_len, int32_t* src_pos,
+                       int32_t* n_cand, int32_t* key_len, int32_t* draft_extras, uint8_t* strict, void* stream)
+{
+    aasd::PoolLayout lay;
+    size_t need = 0;
+    if (!pool_layout(B, capacity, n_min, n_max, lay, need))
+        return fail(AASD_ERR_INVALID_ARG, "pool_retrieve: need B >= 0, 1 <= capacity <= %d, 1 <= n_min <= n_max <= %d (got %d, %d, %d, %d)",
+                    kMaxPoolCapacity, AASD_MAX_KEY, B, capacity, n_min, n_max);
+    if (tok_stride < 1 || tok_stride > 0x7fffffffLL) return fail(AASD_ERR_INVALID_ARG, "pool_retrieve: tok_stride = %lld out of range", (long long)tok_stride);
+    if (k < 1 || k > AASD_MAX_DRAFT) return fail(AASD_ERR_INVALID_ARG, "pool_retrieve: k = %d outside [1,%d]", k, AASD_MAX_DRAFT);
+    if (C < 1 || C > AASD_MAX_CANDIDATES) return fail(AASD_ERR_INVALID_ARG, "pool_retrieve: C = %d outside [1,%d]", C, AASD_MAX_CANDIDATES);
+    const bool have_table = extras != nullptr || n_extras != nullptr;
+    if (have_table && (!extras || !n_extras || m < 1 || m > AASD_MAX_EXTRAS || extras_stride < 0))
+        return fail(AASD_ERR_INVALID_ARG, "pool_retrieve: an extras table needs extras, n_extras, 1 <= m <= %d and extras_stride >= 0", AASD_MAX_EXTRAS);
+    if (draft_extras && !have_table) return fail(AASD_ERR_INVALID_ARG, "pool_retrieve: draft_extras wanted but no extras table given");
+    if (B == 0) return AASD_OK;
+    if (!tokens || !len || !prompt_len || !drafts || !draft_len || !src_pos || !n_cand || !key_len || !strict)
+        return fail(AASD_ERR_INVALID_ARG, "pool_retrieve: null required pointer");
+    if (!pool || pool_bytes < need)
+        return fail(AASD_ERR_WORKSPACE, "pool_retrieve: pool of %zu bytes needed, %zu given", need, pool ? pool_bytes : (size_t)0);
+    if (((uintptr_t)pool % 16) != 0) return fail(AASD_ERR_WORKSPACE, "pool_retrieve: pool is not 16-byte aligned");
+    aasd::PoolRetrieveParams q{};
+    q.pool = (const char*)pool; q.lay = lay;
+    aasd::RetrieveParams& p = q.r;
+    p.tokens = tokens; p.tok_stride = tok_stride; p.len = len; p.prompt_len = prompt_len;
+    p.B = B; p.n_min = n_min; p.n_max = n_max; p.k = k; p.C = C;
+    p.extras = extras; p.n_extras = n_extras; p.m_x = have_table ? m : 0; p.extras_stride = extras_stride;
+    p.drafts = drafts; p.draft_len = draft_len; p.src_pos = src_pos; p.n_cand = n_cand; p.key_len = key_len;
+    p.draft_extras = draft_extras; p.strict = strict;
+    if (update_first)
+        hipLaunchKernelGGL(aasd::pool_step_kernel, dim3((unsigned)B), dim3((n_max - n_min + 1) * aasd::kWave), 0, (hipStream_t)stream, q);
+    else
+        hipLaunchKernelGGL(aasd::pool_retrieve_kernel, dim3((unsigned)B), dim3(aasd::kWave), 0, (hipStream_t)stream, q);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(AASD_ERR_LAUNCH, "pool_retrieve launch failed: %s", hipGetErrorString(e));
+    return AASD_OK;
+}
+
+int aasd_pool_retrieve(const void* pool, size_t pool_bytes, int32_t B, int32_t capacity, int32_t n_min, int32_t n_max,
+                       const int32_t* tokens, int64_t tok_stride, const int32_t* len, const int32_t* prompt_len,
+                       int32_t k, int32_t C, const int32_t* extras, const uint8_t* n_extras, int32_t m,
+                       int64_t extras_stride, int32_t* drafts, int32_t* draft_len, int32_t* src_pos,
+                       int32_t* n_cand, int32_t* key_len, int32_t* draft_extras, uint8_t* strict, void* stream)
+{
+    return pool_lookup(false, pool, pool_bytes, B, capacity, n_min, n_max, tokens, tok_stride, len, prompt_len, k, C,
+                       extras, n_extras, m, extras_stride, drafts, draft_len, src_pos, n_cand, key_len, draft_extras,
+                       strict, stream);
+}
+
+int aasd_pool_step(void* pool, size_t pool_bytes, int32_t B, int32_t capacity, int32_t n_min, int32_t n_max,
+                   const int32_t* tokens, int64_t tok_stride, const int32_t* len, const int32_t* prompt_len,
+                   int32_t k, int32_t C, const int32_t* extras, const uint8_t* n_extras, int32_t m,
+                   int64_t extras_stride, int32_t* drafts, int32_t* draft_len, int32_t* src_pos,
+                   int32_t* n_cand, int32_t* key_len, int32_t* draft_extras, uint8_t* strict, void* stream)
+{
+    return pool_lookup(true, pool, pool_bytes, B, capacity, n_min, n_max, tokens, tok_stride, len, prompt_len, k, C,
+                       extras, n_extras, m, extras_stride, drafts, draft_len, src_pos, n_cand, key_len, draft_extras,
+                       strict, stream);
 }
 
 size_t aasd_verify_topk_workspace_bytes(int32_t B, int32_t C, int32_t k, int32_t V, int32_t dt)

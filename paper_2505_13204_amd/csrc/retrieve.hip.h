@@ -38,6 +38,43 @@ struct RetrieveParams {
     int32_t tile;  // positions per tile = kRetrieveBlock * run
 };
 
+// Write the outputs of one sequence from the candidate positions pos[0 .. ncand) (latest first): the
+// continuations, their lengths and source flags, and the alignment extras of the copied prompt positions.
+template <int BLOCK>
+__device__ __forceinline__ void write_candidates(const RetrieveParams& p, int b, const int32_t* tok, int len, int plen,
+                                                 const int32_t* pos, int ncand, int n_star, int tid)
+{
+    const int C = p.C, k = p.k;
+    for (int i = tid; i < C * k; i += BLOCK) {
+        const int c = i / k, j = i - c * k;
+        const size_t bc = (size_t)b * C + c;
+        const int pp = c < ncand ? pos[c] : -1;
+        const int dl = pp >= 0 ? min(k, len - pp) : 0;
+        const bool in = j < dl;
+        p.drafts[bc * k + j] = in ? tok[pp + j] : -1;
+        p.strict[bc * k + j] = (in && pp + j >= plen) ? 1 : 0;  // copied from generated context
+        if (p.draft_extras) {
+            for (int e = 0; e < p.m_x; ++e) {
+                int32_t val = -1;
+                // prefill row pp+j-1 predicted the token at pp+j; it has a next prompt token iff pp+j <= plen-1
+                if (in && pp + j <= plen - 1 && (int64_t)(pp + j - 1) < p.extras_stride) {
+                    const size_t row = (size_t)b * p.extras_stride + (size_t)(pp + j - 1);
+                    if (e < (int)p.n_extras[row]) val = p.extras[row * p.m_x + e];
+                }
+                p.draft_extras[(bc * k + j) * p.m_x + e] = val;
+            }
+        }
+        if (j == 0) {
+            p.draft_len[bc] = dl;
+            p.src_pos[bc] = pp;
+        }
+    }
+    if (tid == 0) {
+        p.n_cand[b] = ncand;
+        p.key_len[b] = ncand > 0 ? n_star : 0;
+    }
+}
+
 __global__ __launch_bounds__(kRetrieveBlock) void retrieve_kernel(RetrieveParams p)
 {
     constexpr int BLOCK = kRetrieveBlock;
@@ -155,35 +192,7 @@ __global__ __launch_bounds__(kRetrieveBlock) void retrieve_kernel(RetrieveParams
     }
     __syncthreads();
 
-    const int ncand = min(count, C);
-    for (int i = tid; i < C * k; i += BLOCK) {
-        const int c = i / k, j = i - c * k;
-        const size_t bc = (size_t)b * C + c;
-        const int pp = c < ncand ? pos[c] : -1;
-        const int dl = pp >= 0 ? min(k, len - pp) : 0;
-        const bool in = j < dl;
-        p.drafts[bc * k + j] = in ? tok[pp + j] : -1;
-        p.strict[bc * k + j] = (in && pp + j >= plen) ? 1 : 0;  // copied from generated context
-        if (p.draft_extras) {
-            for (int e = 0; e < p.m_x; ++e) {
-                int32_t val = -1;
-                // prefill row pp+j-1 predicted the token at pp+j; it has a next prompt token iff pp+j <= plen-1
-                if (in && pp + j <= plen - 1 && (int64_t)(pp + j - 1) < p.extras_stride) {
-                    const size_t row = (size_t)b * p.extras_stride + (size_t)(pp + j - 1);
-                    if (e < (int)p.n_extras[row]) val = p.extras[row * p.m_x + e];
-                }
-                p.draft_extras[(bc * k + j) * p.m_x + e] = val;
-            }
-        }
-        if (j == 0) {
-            p.draft_len[bc] = dl;
-            p.src_pos[bc] = pp;
-        }
-    }
-    if (tid == 0) {
-        p.n_cand[b] = ncand;
-        p.key_len[b] = ncand > 0 ? n_star : 0;
-    }
+    write_candidates<BLOCK>(p, b, tok, len, plen, pos, min(count, C), n_star, tid);
 }
 
 }  // namespace aasd

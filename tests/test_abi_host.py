@@ -174,3 +174,33 @@ def test_verify_topk_rejects_invalid_arguments(lib):
     assert _verify_topk(lib, B=0) == 0
     assert lib.aasd_verify_topk_workspace_bytes(2, 2, 4, 100, 1) > lib.aasd_verify_workspace_bytes(2, 2, 4, 100, 1)
     assert lib.aasd_verify_topk_workspace_bytes(2, 0, 4, 100, 1) == 0
+
+
+def test_pool_rejects_invalid_arguments(lib):
+    need = lib.aasd_pool_bytes(2, 1000, 2, 4)
+    # counters, then per (sequence, key length) a table of 2048 heads (load factor <= 1/2) and 1001 links
+    assert need == 32 + 2 * 3 * ((2048 + 1001) * 4 + 12)
+    for args in [(-1, 10, 1, 1), (1, 0, 1, 1), (1, (1 << 24) + 1, 1, 1), (1, 10, 0, 1), (1, 10, 3, 2), (1, 10, 1, 9)]:
+        assert lib.aasd_pool_bytes(*args) == 0
+    def upd(**kw):
+        a = dict(pool=FAKE, nb=need, B=2, cap=1000, n_min=2, n_max=4, tok=FAKE, stride=1000, len=FAKE, reset=1, stream=None)
+        a.update(kw)
+        return lib.aasd_pool_update(a["pool"], a["nb"], a["B"], a["cap"], a["n_min"], a["n_max"], a["tok"], a["stride"],
+                                    a["len"], a["reset"], a["stream"])
+    for kw in [dict(B=-1), dict(cap=0), dict(n_min=0), dict(n_max=9), dict(n_min=5), dict(stride=0), dict(tok=None), dict(len=None)]:
+        assert upd(**kw) == INVALID, kw
+    assert upd(pool=None) == WORKSPACE and upd(nb=need - 1) == WORKSPACE and upd(pool=FAKE + 8) == WORKSPACE
+    assert upd(B=0) == 0
+    def ret(**kw):
+        a = dict(pool=FAKE, nb=need, B=2, cap=1000, n_min=2, n_max=4, tok=FAKE, stride=1000, len=FAKE, plen=FAKE, k=8, C=4,
+                 extras=None, nx=None, m=0, xs=0, drafts=FAKE, dl=FAKE, sp=FAKE, nc=FAKE, kl=FAKE, dx=None, strict=FAKE,
+                 stream=None)
+        a.update(kw)
+        return lib.aasd_pool_retrieve(a["pool"], a["nb"], a["B"], a["cap"], a["n_min"], a["n_max"], a["tok"], a["stride"],
+                                      a["len"], a["plen"], a["k"], a["C"], a["extras"], a["nx"], a["m"], a["xs"], a["drafts"],
+                                      a["dl"], a["sp"], a["nc"], a["kl"], a["dx"], a["strict"], a["stream"])
+    for kw in [dict(B=-1), dict(cap=0), dict(k=0), dict(k=17), dict(C=0), dict(C=33), dict(tok=None), dict(plen=None),
+               dict(drafts=None), dict(strict=None), dict(extras=FAKE), dict(extras=FAKE, nx=FAKE, m=5), dict(dx=FAKE)]:
+        assert ret(**kw) == INVALID, kw
+    assert ret(pool=None) == WORKSPACE and ret(nb=need - 1) == WORKSPACE
+    assert ret(B=0) == 0

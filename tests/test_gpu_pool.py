@@ -1,0 +1,132 @@
+"""The persistent draft pool (Algorithm 1's dictionary with incremental update) on the GPU returns exactly
+what the stateless oracle retrieval returns, after a full build and after every incremental update."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2505_13204_amd as aasd
+from paper_2505_13204_amd import harness, synth
+from tests import backends as bk
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _t(a, dt):
+    return None if a is None else torch.as_tensor(np.ascontiguousarray(a), device=DEV).to(dt)
+
+
+def _check(pool, toks_d, toks, lens, plens, n_min, n_max, k, C, extras=None, n_extras=None, m=0, xs=0):
+    ref = oracle.retrieve_drafts(toks, lens, plens, n_min, n_max, k, C, extras=extras, n_extras=n_extras, m_x=m,
+                                 extras_stride=xs)
+    out = pool.retrieve(toks_d, _t(lens, torch.int32), _t(plens, torch.int32), k, C, extras=_t(extras, torch.int32),
+                        n_extras=_t(n_extras, torch.uint8), m=m, extras_stride=xs)
+    torch.cuda.synchronize()
+    bk.compare_retrieve(bk.to_np(out), ref)
+    return ref
+
+
+@pytest.mark.parametrize("n_min,n_max,k,C", [(1, 1, 1, 1), (1, 6, 6, 4), (3, 3, 4, 2), (2, 4, 8, 16), (1, 8, 16, 32)])
+@pytest.mark.parametrize("cap", [1, 90, 1500, 30011])
+def test_pool_full_build_random_small_alphabet(n_min, n_max, k, C, cap):
+    rng = np.random.default_rng(cap + n_max)
+    B = 12
+    alphabet = 3 if cap < 2000 else 40
+    toks = rng.integers(0, alphabet, size=(B, cap)).astype(np.int32)
+    lens = rng.integers(0, cap + 1, size=B).astype(np.int32)
+    lens[0], lens[1] = cap, 0
+    plens = np.minimum(lens, rng.integers(0, cap + 1, size=B)).astype(np.int32)
+    pool = aasd.DraftPool(B, cap, n_min, n_max, DEV)
+    toks_d = _t(toks, torch.int32)
+    pool.update(toks_d, _t(lens, torch.int32), reset=True)
+    ref = _check(pool, toks_d, toks, lens, plens, n_min, n_max, k, C)
+    if cap >= 1500:
+        assert (ref["n_cand"] > 0).any()
+    # a lookup at a shorter context than was indexed ignores the later positions
+    shorter = (lens * 0.7).astype(np.int32)
+    _check(pool, toks_d, toks, shorter, np.minimum(plens, shorter), n_min, n_max, k, C)
+    # a second full build over the same memory starts from nothing
+    toks2 = rng.integers(0, alphabet, size=(B, cap)).astype(np.int32)
+    toks2_d = _t(toks2, torch.int32)
+    pool.update(toks2_d, _t(lens, torch.int32), reset=True)
+    _check(pool, toks2_d, toks2, lens, plens, n_min, n_max, k, C)
+
+
+def test_pool_incremental_updates_with_extras():
+    """Prompt indexed once, then 60 steps that append 1..9 tokens each; after every update the pool answers
+    like the oracle on the context of that step.  Updates cross the 64-position batches of the insert kernel."""
+    rng = np.random.default_rng(21)
+    B, L0, cap, m = 5, 700, 1400, 2
+    n_min, n_max, k, C = 2, 5, 8, 8
+    stream = rng.integers(0, 6, size=(B, cap)).astype(np.int32)
+    for b in range(B):          # planted repeats so that long keys occur
+        for dst in range(100, cap - 40, 97):
+            src = int(rng.integers(0, dst - 30))
+            stream[b, dst:dst + 30] = stream[b, src:src + 30]
+    extras = rng.integers(0, 50, size=(B * L0, m)).astype(np.int32)
+    n_extras = rng.integers(0, m + 1, size=B * L0).astype(np.uint8)
+    extras[np.arange(m)[None, :] >= n_extras[:, None]] = -1
+    toks_d = _t(stream, torch.int32)
+    pool = aasd.DraftPool(B, cap, n_min, n_max, DEV)
+    lens = np.full(B, L0, np.int32)
+    plens = np.full(B, L0, np.int32)
+    pool.update(toks_d, _t(lens, torch.int32), reset=True)
+    hits = 0
+    for step in range(60):
+        ref = _check(pool, toks_d, stream, lens, plens, n_min, n_max, k, C, extras, n_extras, m, L0)
+        hits += int((ref["n_cand"] > 0).sum())
+        lens = np.minimum(lens + rng.integers(1, 10, size=B), cap).astype(np.int32)
+        if step % 2:
+            pool.update(toks_d, _t(lens, torch.int32))
+        else:      # the fused form: update and lookup in one launch
+            got = pool.step(toks_d, _t(lens, torch.int32), _t(plens, torch.int32), k, C, extras=_t(extras, torch.int32),
+                            n_extras=_t(n_extras, torch.uint8), m=m, extras_stride=L0)
+            torch.cuda.synchronize()
+            bk.compare_retrieve(bk.to_np(got), oracle.retrieve_drafts(stream, lens, plens, n_min, n_max, k, C, extras=extras,
+                                                                      n_extras=n_extras, m_x=m, extras_stride=L0))
+    assert hits > 100
+
+
+def test_pool_colliding_ngrams_are_told_apart_and_capacity_cuts():
+    step = (1 << 32) - aasd.HASH_BASE   # (a+1)*B + (b+step) == a*B + b (mod 2^32): same window hash, same bucket
+    a, b = 1000, 2000
+    toks = np.array([[5, a + 1, b + step, 77, 6, a, b, 88, 9, a, b]], np.int32)
+    pool = aasd.DraftPool(1, 16, 2, 2, DEV)
+    td = _t(toks, torch.int32)
+    pool.update(td, _t([11], torch.int32), reset=True)
+    ref = _check(pool, td, toks, np.array([11], np.int32), np.array([11], np.int32), 2, 2, 3, 4)
+    assert ref["src_pos"][0].tolist() == [7, -1, -1, -1]
+    # a context longer than the pool's capacity is indexed up to the capacity only
+    rng = np.random.default_rng(2)
+    long = rng.integers(0, 3, size=(1, 300)).astype(np.int32)
+    small = aasd.DraftPool(1, 200, 1, 3, DEV)
+    ld = _t(long, torch.int32)
+    small.update(ld, _t([300], torch.int32), reset=True)
+    _check(small, ld, long, np.array([200], np.int32), np.array([200], np.int32), 1, 3, 4, 6)
+
+
+def test_decode_loop_with_the_pool_matches_the_oracle():
+    """The synthetic decode loop with retrieval served by the pool (one full build, then an update per step)."""
+    w = synth.scaled(synth.WORKLOADS["llama3_single"], B=3, L=300, V=3000, steps=30, n_min=2, n_max=4, C=4, coverage=0.9)
+
+    class PoolParity(bk.ParityBackend):
+        def __init__(self, dev):
+            super().__init__(dev)
+            self.pool = aasd.DraftPool(w.B, w.tok_cap, w.n_min, w.n_max, dev)
+            self.first = True
+
+        def retrieve(self, tokens, length, prompt_len, w_, extras, n_extras):
+            ref = self.orc.retrieve(tokens, length, prompt_len, w_, extras, n_extras)
+            td = _t(tokens, torch.int32)
+            if self.first:
+                self.pool.update(td, _t(length, torch.int32), reset=True)
+            self.first = False
+            got = self.pool.step(td, _t(length, torch.int32), _t(prompt_len, torch.int32), w_.k, w_.C)   # update + lookup
+            torch.cuda.synchronize()
+            bk.compare_retrieve(bk.to_np(got), ref)
+            return ref
+
+    pb = PoolParity(DEV)
+    trace = harness.decode(w, pb, peaked=True)
+    assert trace.mean_accept_len > 1.5

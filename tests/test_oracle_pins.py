@@ -323,6 +323,34 @@ def test_retrieval_equals_dictionary_pool_of_algorithm_1():
                     assert (out["drafts"][b, c] == -1).all() and (out["strict"][b, c] == 0).all()
 
 
+def test_incrementally_updated_pool_returns_what_a_rebuilt_pool_returns():
+    """Algorithm 1 keeps one dictionary and adds, after every step, the windows that end in the new tokens.
+    A dictionary grown that way, looked up at every step, gives what the oracle's stateless retrieval gives
+    for the context of that step (so a persistent index may be checked against the stateless oracle)."""
+    rng = np.random.default_rng(11)
+    n_min, n_max, k, C = 1, 4, 5, 6
+    stream = rng.integers(0, 3, size=140).astype(np.int32)
+    pool, indexed = {}, 0
+    L = 40
+    while L <= len(stream):
+        tok = stream[:L].tolist()
+        for end in range(indexed + 1, L + 1):            # windows that end in a new token: tok[end-klen:end]
+            for klen in range(1, min(n_max, end) + 1):
+                pool.setdefault(tuple(tok[end - klen:end]), []).append(end)
+        indexed = L
+        ref = oracle.retrieve_drafts(stream[None, :], [L], [40], n_min, n_max, k, C)
+        klen_found, hits = 0, []
+        for klen in range(n_max, n_min - 1, -1):
+            if klen >= L:
+                continue
+            hits = sorted((p for p in pool.get(tuple(tok[L - klen:]), []) if p <= L - 1), reverse=True)[:C]
+            if hits:
+                klen_found = klen
+                break
+        assert ref["key_len"][0] == klen_found and ref["src_pos"][0].tolist() == hits + [-1] * (C - len(hits))
+        L += int(rng.integers(1, 7))
+
+
 def test_retrieval_planted_span_and_fallback():
     # context: noise, SPAN, noise, SPAN[:5] -> the suffix SPAN[2:5] occurs once before, continuation SPAN[5:]
     span = [101, 102, 103, 104, 105, 106, 107, 108]
