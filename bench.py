@@ -308,8 +308,32 @@ def main():
             do_verify(verify_logits[sl], outs_r["drafts"], outs_r["draft_len"], outs_r["strict"], workspace=ws1, out=outs_v)
         e1.record()
         torch.cuda.synchronize()
+        # the same launches captured once in a HIP graph and replayed: no per-launch host cost
+        def lat_steps():
+            for s in range(n_lat):
+                sl = slice(s * w.B, (s + 1) * w.B)
+                aasd.retrieve_drafts(tokens_b[sl], len_b[sl], plen_b[sl], w.n_min, w.n_max, w.k, w.C, out=outs_r)
+                do_verify(verify_logits[sl], outs_r["drafts"], outs_r["draft_len"], outs_r["strict"], workspace=ws1, out=outs_v)
+        graph_us = None
+        if not use_pool:   # (the pool's update changes state: a replay would index nothing new, so it is not replayed here)
+            eager_last = outs_v["accept_len"].clone()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                lat_steps()
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert (outs_v["accept_len"] == eager_last).all(), "graph replay differs from the eager loop"
+            g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            g0.record()
+            for _ in range(3):
+                graph.replay()
+            g1.record()
+            torch.cuda.synchronize()
+            graph_us = round(g0.elapsed_time(g1) * 1e3 / (3 * n_lat), 2)
         latency = {"decode_steps": n_lat, "rows_per_step": w.B * w.R,
                    "us_per_decode_step": round(e0.elapsed_time(e1) * 1e3 / n_lat, 2),
+                   "hip_graph_us_per_decode_step": graph_us,
                    "note": ("pool step (incremental update + lookup in one launch) + verify" if use_pool else "retrieve + verify") +
                            " launched back to back per decode step, no host sync"}
 

@@ -581,3 +581,46 @@ def test_verify_topk_top1_equals_strict_verification_and_full_shape():
         ref = oracle.verify_topk(synth.to_host_bits(zd[b:b + 1]), drafts[b:b + 1], dl[b:b + 1], topk=5)
         assert ref["accept_len"][0] == five["accept_len"][b] and ref["next_token"][0] == five["next_token"][b]
         assert (((ref["tok_rank"] >= 0) & (ref["tok_rank"] < 5)) == five["tok_pass"][b:b + 1].astype(bool)).all()
+
+
+def test_decode_steps_captured_in_a_hip_graph_match_the_eager_launches():
+    """Retrieval and verification of several decode steps captured once and replayed: every replay, with eager
+    work and synchronisations in between, gives the eager results (the library launches kernels only: no
+    allocation, no memset, no host synchronisation inside its calls)."""
+    rng = np.random.default_rng(41)
+    w = synth.scaled(synth.WORKLOADS["llama3_single"], V=6000, L=300, steps=12, coverage=0.9)
+    g, cp = synth.token_stream(w, 0)
+    S = 8
+    toks = torch.from_numpy(g[:w.tok_cap].astype(np.int32)[None]).to(DEV)
+    z = [_verify_case(rng, 1, w.C, w.k, w.V, "bf16")[0] for _ in range(S)]
+    lens = [torch.tensor([w.L + 5 * s], dtype=torch.int32, device=DEV) for s in range(S)]
+    plen = torch.tensor([w.L], dtype=torch.int32, device=DEV)
+    r = aasd.retrieve_drafts(toks, lens[0], plen, w.n_min, w.n_max, w.k, w.C)
+    ws = torch.empty(aasd.verify_workspace_bytes(1, w.C, w.k, w.V, aasd.BF16), dtype=torch.uint8, device=DEV)
+    v = aasd.verify(z[0], r["drafts"], r["draft_len"], r["strict"], workspace=ws)
+    rec = [torch.zeros(4, dtype=torch.int32, device=DEV) for _ in range(S)]
+
+    def steps():
+        for s in range(S):
+            aasd.retrieve_drafts(toks, lens[s], plen, w.n_min, w.n_max, w.k, w.C, out=r)
+            aasd.verify(z[s], r["drafts"], r["draft_len"], r["strict"], workspace=ws, out=v)
+            rec[s][0:1].copy_(v["accept_len"]); rec[s][1:2].copy_(v["next_token"]); rec[s][2:3].copy_(r["n_cand"])
+            rec[s][3:4].copy_(r["src_pos"][0, :1])
+
+    steps()
+    torch.cuda.synchronize()
+    eager = [x.clone() for x in rec]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        steps()
+    torch.cuda.synchronize()
+    for i in range(4):
+        for x in rec:
+            x.fill_(-9)
+        other = aasd.verify(z[(i + 1) % S], r["drafts"], r["draft_len"], r["strict"])   # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for s in range(S):
+            assert (rec[s] == eager[s]).all(), (i, s, rec[s].tolist(), eager[s].tolist())
+    assert any(int(e[2]) > 0 for e in eager)
