@@ -228,13 +228,15 @@ def test_verify_tree_strided_rows_and_determinism():
             assert a[name].tobytes() == b[name].tobytes() == c[name].tobytes(), name
 
 
-def test_verify_tree_full_size_stress_shape_sampled():
-    """The stress workload's shape as benched: B = 64 sequences, trees of up to 129 nodes, V = 152064 bf16.
-    Row statistics are checked on sampled rows; decisions on every sequence whose rows the oracle recomputes."""
+@pytest.mark.parametrize("N", [129, 256])
+def test_verify_tree_full_size_stress_shape_sampled(N):
+    """The batch shapes as benched: B = 64 sequences, V = 152064 bf16, trees of up to 129 nodes (1 + C*k) or with
+    the node budget of 256 that the tree workloads use.  Decisions and statistics are checked on sampled
+    sequences whose rows the oracle recomputes, structural properties on all."""
     w = synth.WORKLOADS["stress_tree"]
-    rng = np.random.default_rng(21)
-    B, N, V = w.B, 1 + w.C * w.k, w.V
-    drafts, dl, strict, dx = _random_candidates(rng, B, w.C, w.k, 2, alphabet=6)
+    rng = np.random.default_rng(21 + N)
+    B, V = w.B, w.V
+    drafts, dl, strict, dx = _random_candidates(rng, B, w.C, w.k, 2, alphabet=6 if N == 129 else 12)
     tree = oracle.build_tree(drafts, dl, strict, dx, root_tok=np.zeros(B, np.int32), max_nodes=N)
     g = torch.Generator(device=DEV).manual_seed(4)
     zd = torch.randn((B, N, V), generator=g, device=DEV, dtype=torch.float32).to(torch.bfloat16)
