@@ -553,6 +553,54 @@ def bench_tree(args, w, dev):
                 "alone, over a repeat of the K timed steps with the events switched on",
     }
 
+    # ---------------------------------------------------------------- sequential per-step latency (context)
+    latency = None
+    if not args.no_latency and w.B * N <= 512:
+        n_lat = min(S, 256)
+        sl0 = slice(0, w.B)
+        ws1 = torch.empty(max(16, aasd.verify_tree_workspace_bytes(w.B, N, w.V, dt_code)), dtype=torch.uint8, device=dev)
+        r1 = aasd.retrieve_drafts(tokens_b[sl0], len_b[sl0], plen_b[sl0], w.n_min, w.n_max, w.k, w.C, extras=extras,
+                                  n_extras=n_extras, m=w.m, extras_stride=w.L)
+        t1_ = aasd.build_tree(r1["drafts"], r1["draft_len"], r1["strict"], r1["draft_extras"], root_b[sl0], max_nodes=N)
+        v1 = aasd.verify_tree(tree_logits[sl0], t1_["node_token"], t1_["node_parent"], t1_["n_nodes"], t1_["node_strict"],
+                              alpha=w.alpha, beta=w.beta, workspace=ws1, want_rows=False, want_nodes=False, want_near=False)
+
+        def lat_steps():
+            for s_ in range(n_lat):
+                sl = slice(s_ * w.B, (s_ + 1) * w.B)
+                aasd.retrieve_drafts(tokens_b[sl], len_b[sl], plen_b[sl], w.n_min, w.n_max, w.k, w.C, extras=extras,
+                                     n_extras=n_extras, m=w.m, extras_stride=w.L, out=r1)
+                aasd.build_tree(r1["drafts"], r1["draft_len"], r1["strict"], r1["draft_extras"], root_b[sl], max_nodes=N, out=t1_)
+                aasd.verify_tree(tree_logits[sl], t1_["node_token"], t1_["node_parent"], t1_["n_nodes"], t1_["node_strict"],
+                                 alpha=w.alpha, beta=w.beta, workspace=ws1, want_rows=False, want_nodes=False,
+                                 want_near=False, out=v1)
+
+        lat_steps()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        lat_steps()
+        e1.record()
+        torch.cuda.synchronize()
+        eager_last = v1["accept_len"].clone()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            lat_steps()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert (v1["accept_len"] == eager_last).all(), "graph replay differs from the eager loop"
+        g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        g0.record()
+        for _ in range(3):
+            graph.replay()
+        g1.record()
+        torch.cuda.synchronize()
+        latency = {"decode_steps": n_lat, "rows_per_step": "%d of %d" % (int(n_nodes_h[:n_lat * w.B].sum()) // n_lat, w.B * N),
+                   "us_per_decode_step": round(e0.elapsed_time(e1) * 1e3 / n_lat, 2),
+                   "hip_graph_us_per_decode_step": round(g0.elapsed_time(g1) * 1e3 / (3 * n_lat), 2),
+                   "note": "retrieve + build_tree + verify_tree launched back to back per decode step, no host sync"}
+
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
@@ -585,7 +633,7 @@ def bench_tree(args, w, dev):
                    "k": w.k, "C": w.C, "m": w.m, "n_gram": [w.n_min, w.n_max], "max_nodes": N, "decode_steps": S,
                    "prefill_rows": prefill_rows, "tree_rows": tree_rows, "rows_per_step": rows_per_step,
                    "form": "all decode steps built and verified as one batch of trees"},
-        "roofline": roofline, "cpu_baseline": cpu, "latency": None,
+        "roofline": roofline, "cpu_baseline": cpu, "latency": latency,
         "tokens_per_decode_step": round(trace.mean_accept_len, 3), "setup_s": round(setup_s, 1),
     }
     print(json.dumps(out))

@@ -101,7 +101,7 @@ __global__ __launch_bounds__(kTreeBlock) void build_tree_kernel(BuildTreeParams 
                               : ((unsigned long long)(0x10000u + (unsigned)e) << 32);
             ev_flag[e] = (unsigned char)st;
         }
-        __syncthreads();
+        if (__syncthreads_or(valid) == 0) break;   // no candidate reaches this layer: the tree is complete (same in every thread)
         int rep = e;  // earliest event of the layer with the same key (the loads do not depend on one another)
         if (valid) {
             const unsigned long long key = ev_key[e];
