@@ -251,13 +251,13 @@ def main():
     ms_per_step_instrumented = (time.perf_counter() - ti0) * 1e3 / K
     draws = None
     if mode == aasd.EXTRAS_GUMBEL:
-        # the draw kernel is bound by instruction issue: 68 vector-lane cycles per token (197 vector instructions per
-        # four tokens, of which 17 64-bit multiplies and 8 logarithms run at quarter rate), against
-        # 256 CUs x 64 lanes x 2.4 GHz = 39.3e12 lane cycles per second
+        # the draw kernel is bound by instruction issue: its inner loop has 197 vector instructions per four tokens
+        # (counted in the ISA), at least one lane cycle each, against 256 CUs x 64 lanes x 2.4 GHz = 39.3e12 lane
+        # cycles per second
         draw_ms = float(np.mean([hip_elapsed(kev[i][4], kev[i][5]) for i in range(K)]))
         n_mis = int(align_out["misaligned"].sum().item())
         tokens = n_mis * w.V
-        lane_cycles = 68.0
+        lane_cycles = 197.0 / 4.0
         peak = 256 * 64 * 2.4e9 / 1e12
         ach = tokens * lane_cycles / (draw_ms * 1e-3) / 1e12
         draws = {"kernel": "aasd::gumbel_extras_kernel", "rows_drawn": n_mis, "tokens": tokens, "kernel_ms": round(draw_ms, 4),

@@ -147,21 +147,32 @@ int launch_sweep_used(const aasd::SweepParams& p, const SweepPlan& pl, int64_t s
 }
 
 template <int DT>
-void launch_gumbel_dt(int m, unsigned grid, hipStream_t s, const aasd::GumbelParams& gp, int64_t r0)
+void launch_gumbel_dt(int m, unsigned grid, hipStream_t s, const aasd::GumbelParams& gp, int64_t u0)
 {
     const dim3 g(grid), b(aasd::kGumbelBlock);
     switch (m) {  // the kernel keeps m + 1 keys per lane
-    case 1: hipLaunchKernelGGL((aasd::gumbel_extras_kernel<DT, 2>), g, b, 0, s, gp, r0); break;
-    case 2: hipLaunchKernelGGL((aasd::gumbel_extras_kernel<DT, 3>), g, b, 0, s, gp, r0); break;
-    case 3: hipLaunchKernelGGL((aasd::gumbel_extras_kernel<DT, 4>), g, b, 0, s, gp, r0); break;
-    default: hipLaunchKernelGGL((aasd::gumbel_extras_kernel<DT, 5>), g, b, 0, s, gp, r0); break;
+    case 1: hipLaunchKernelGGL((aasd::gumbel_extras_kernel<DT, 2>), g, b, 0, s, gp, u0); break;
+    case 2: hipLaunchKernelGGL((aasd::gumbel_extras_kernel<DT, 3>), g, b, 0, s, gp, u0); break;
+    case 3: hipLaunchKernelGGL((aasd::gumbel_extras_kernel<DT, 4>), g, b, 0, s, gp, u0); break;
+    default: hipLaunchKernelGGL((aasd::gumbel_extras_kernel<DT, 5>), g, b, 0, s, gp, u0); break;
     }
 }
 
-void launch_gumbel(int32_t dt, int m, unsigned grid, hipStream_t s, const aasd::GumbelParams& gp, int64_t r0)
+void launch_gumbel(int32_t dt, int m, unsigned grid, hipStream_t s, const aasd::GumbelParams& gp, int64_t u0)
 {
-    if (dt == AASD_BF16) launch_gumbel_dt<AASD_BF16>(m, grid, s, gp, r0);
-    else launch_gumbel_dt<AASD_F32>(m, grid, s, gp, r0);
+    if (dt == AASD_BF16) launch_gumbel_dt<AASD_BF16>(m, grid, s, gp, u0);
+    else launch_gumbel_dt<AASD_F32>(m, grid, s, gp, u0);
+}
+
+void launch_gumbel_merge(int m, int64_t rows, hipStream_t s, const aasd::GumbelParams& gp)
+{
+    const dim3 g((unsigned)((rows + aasd::kGumbelBlock - 1) / aasd::kGumbelBlock)), b(aasd::kGumbelBlock);
+    switch (m) {
+    case 1: hipLaunchKernelGGL((aasd::gumbel_merge_kernel<2>), g, b, 0, s, gp, rows); break;
+    case 2: hipLaunchKernelGGL((aasd::gumbel_merge_kernel<3>), g, b, 0, s, gp, rows); break;
+    case 3: hipLaunchKernelGGL((aasd::gumbel_merge_kernel<4>), g, b, 0, s, gp, rows); break;
+    default: hipLaunchKernelGGL((aasd::gumbel_merge_kernel<5>), g, b, 0, s, gp, rows); break;
+    }
 }
 
 size_t align16(size_t n) { return (n + 15) & ~(size_t)15; }
@@ -297,12 +308,28 @@ int aasd_align_sample(const void* logits, int32_t dt, int64_t rows, int32_t V, i
         gp.logits = logits; gp.V = V; gp.row_stride = row_stride; gp.next_tok = next_tok; gp.misaligned = misaligned;
         gp.m_x = m_draw; gp.seed = seed; gp.row_id_base = row_id_base;
         gp.extras = extras; gp.n_extras = n_extras; gp.extra_keys = nullptr; gp.near_count = near_count;
+        // several workgroups per row while the rows are few; their best keys go through the workspace, which the
+        // finish kernel no longer needs (at least 896 bytes per row; 16 shares x 5 keys need 640)
+        int64_t nseg = (8192 + rows - 1) / rows;
+        const int64_t nquad = ((int64_t)V + 3) / 4;
+        if (nseg > 16) nseg = 16;
+        if (nseg > nquad / aasd::kGumbelBlock) nseg = nquad / aasd::kGumbelBlock;
+        if (nseg < 1) nseg = 1;
+        gp.nseg = (int32_t)nseg;
+        gp.part_z = (float*)workspace;
+        gp.part_i = (int32_t*)((char*)workspace + align16((size_t)rows * nseg * (m_draw + 1) * sizeof(float)));
         if (g_draw_start) (void)hipEventRecord(g_draw_start, s);
-        for (int64_t r0 = 0; r0 < rows; r0 += kMaxUnitsPerLaunch) {
-            const int64_t n = rows - r0 < kMaxUnitsPerLaunch ? rows - r0 : kMaxUnitsPerLaunch;
-            launch_gumbel(dt, m_draw, (unsigned)n, s, gp, r0);
+        const int64_t units = rows * nseg;
+        for (int64_t u0 = 0; u0 < units; u0 += kMaxUnitsPerLaunch) {
+            const int64_t n = units - u0 < kMaxUnitsPerLaunch ? units - u0 : kMaxUnitsPerLaunch;
+            launch_gumbel(dt, m_draw, (unsigned)n, s, gp, u0);
             const hipError_t e = hipGetLastError();
             if (e != hipSuccess) return fail(AASD_ERR_LAUNCH, "gumbel extras launch failed: %s", hipGetErrorString(e));
+        }
+        launch_gumbel_merge(m_draw, rows, s, gp);
+        {
+            const hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return fail(AASD_ERR_LAUNCH, "gumbel merge launch failed: %s", hipGetErrorString(e));
         }
         if (g_draw_stop) (void)hipEventRecord(g_draw_stop, s);
     }

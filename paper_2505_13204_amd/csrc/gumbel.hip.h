@@ -24,6 +24,9 @@ struct GumbelParams {
     uint8_t* n_extras;           // [rows]
     float* extra_keys;           // [rows, m_x] or null: the keys of the picks
     uint32_t* near_count;        // or null
+    int32_t nseg;                // workgroups per row: each takes a contiguous share of the row's groups of four tokens
+    float* part_z;               // [rows, nseg, K] best keys of every share, descending (scratch)
+    int32_t* part_i;             // [rows, nseg, K] their tokens (INT_MAX = empty)
 };
 
 // Standard Gumbel variate from 23 random bits: x = (bits + 1/2) / 2^23 in (0, 1), E = -ln(1 - x) is a
@@ -69,10 +72,11 @@ __device__ __forceinline__ void keep_merge(float (&kz)[K], int (&ki)[K], float z
     }
 }
 
-// One workgroup per row; rows that are not misaligned end at once with empty outputs.  Tokens are handled
-// four at a time (one Philox block); a lane keeps its K = m + 1 best keys in registers (the extra one gives
-// the last pick's margin); waves merge by "best head" rounds, the workgroup through LDS.  Tokens with a
-// logit of -inf have probability zero and are never drawn.
+// nseg workgroups per row, each over a contiguous share of the row (few misaligned rows would otherwise leave
+// most of the GPU idle); workgroups of rows that are not misaligned end at once.  Tokens are handled four at
+// a time (one Philox block); a lane keeps its K = m + 1 best keys in registers (the extra one gives the last
+// pick's margin); waves merge by "best head" rounds, the workgroup through LDS, and the K best of the share go
+// to scratch for gumbel_merge_kernel.  Tokens with a logit of -inf have probability zero and are never drawn.
 template <int DT, int K>
 __global__ __launch_bounds__(kGumbelBlock) void gumbel_extras_kernel(GumbelParams p, int64_t row0)
 {
@@ -80,16 +84,11 @@ __global__ __launch_bounds__(kGumbelBlock) void gumbel_extras_kernel(GumbelParam
     __shared__ float s_z[NW][K];
     __shared__ int s_i[NW][K];
 
-    const int64_t row = row0 + blockIdx.x;
+    const int64_t unit = row0 + blockIdx.x;
+    const int64_t row = unit / p.nseg;
+    const int seg = (int)(unit - row * p.nseg);
     const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
-    if (!p.misaligned[row]) {   // aligned (or no next token): no extras
-        if (tid < p.m_x) {
-            p.extras[row * p.m_x + tid] = -1;
-            if (p.extra_keys) p.extra_keys[row * p.m_x + tid] = 0.f;
-        }
-        if (tid == 0) p.n_extras[row] = 0;
-        return;
-    }
+    if (!p.misaligned[row]) return;   // aligned (or no next token): the merge kernel writes the empty outputs
     const int V = p.V;
     const int nt = p.next_tok ? p.next_tok[row] : -1;
     const char* base = (const char*)p.logits + (size_t)row * (size_t)p.row_stride * Elt<DT>::kBytes;
@@ -105,7 +104,9 @@ __global__ __launch_bounds__(kGumbelBlock) void gumbel_extras_kernel(GumbelParam
     for (int q = 0; q < K; ++q) { kz[q] = -INFINITY; ki[q] = 0x7fffffff; }
 
     const int nquad = (V + 3) >> 2;
-    for (int q = tid; q < nquad; q += kGumbelBlock) {
+    const int per_seg = (nquad + p.nseg - 1) / p.nseg;
+    const int q_end = min(nquad, (seg + 1) * per_seg);
+    for (int q = seg * per_seg + tid; q < q_end; q += kGumbelBlock) {
         const int v0 = q << 2;
         float z[4];
         if (wide && v0 + 3 < V) {
@@ -160,21 +161,45 @@ __global__ __launch_bounds__(kGumbelBlock) void gumbel_extras_kernel(GumbelParam
         for (int w = 0; w < NW; ++w)
             for (int r = 0; r < K; ++r)
                 if (s_i[w][r] != 0x7fffffff) keep_merge<K>(fz, fi, s_z[w][r], s_i[w][r]);
-        int n_out = 0;
-        bool near = false;
+        const size_t slot = ((size_t)row * p.nseg + seg) * K;
 #pragma unroll
-        for (int j = 0; j < K - 1; ++j) {
-            const bool have = fi[j] != 0x7fffffff;
-            p.extras[row * p.m_x + j] = have ? fi[j] : -1;
-            if (p.extra_keys) p.extra_keys[row * p.m_x + j] = have ? fz[j] : 0.f;
-            if (have) {
-                ++n_out;
-                if (fi[j + 1] != 0x7fffffff && fz[j] - fz[j + 1] < kGumbelNear) near = true;
+        for (int j = 0; j < K; ++j) { p.part_z[slot + j] = fz[j]; p.part_i[slot + j] = fi[j]; }
+    }
+}
+
+// A thread per row merges the shares' best keys and writes the picks, best first.
+template <int K>
+__global__ __launch_bounds__(kGumbelBlock) void gumbel_merge_kernel(GumbelParams p, int64_t rows)
+{
+    const int64_t row = (int64_t)blockIdx.x * kGumbelBlock + threadIdx.x;
+    if (row >= rows) return;
+    float fz[K];
+    int fi[K];
+#pragma unroll
+    for (int q = 0; q < K; ++q) { fz[q] = -INFINITY; fi[q] = 0x7fffffff; }
+    if (p.misaligned[row]) {
+        for (int s = 0; s < p.nseg; ++s) {
+            const size_t slot = ((size_t)row * p.nseg + s) * K;
+            for (int j = 0; j < K; ++j) {
+                const int i = p.part_i[slot + j];
+                if (i != 0x7fffffff) keep_merge<K>(fz, fi, p.part_z[slot + j], i);
             }
         }
-        p.n_extras[row] = (uint8_t)n_out;
-        if (near && p.near_count) atomicAdd(p.near_count, 1u);
     }
+    int n_out = 0;
+    bool near = false;
+#pragma unroll
+    for (int j = 0; j < K - 1; ++j) {
+        const bool have = fi[j] != 0x7fffffff;
+        p.extras[row * p.m_x + j] = have ? fi[j] : -1;
+        if (p.extra_keys) p.extra_keys[row * p.m_x + j] = have ? fz[j] : 0.f;
+        if (have) {
+            ++n_out;
+            if (fi[j + 1] != 0x7fffffff && fz[j] - fz[j + 1] < kGumbelNear) near = true;
+        }
+    }
+    p.n_extras[row] = (uint8_t)n_out;
+    if (near && p.near_count) atomicAdd(p.near_count, 1u);
 }
 
 }  // namespace aasd
