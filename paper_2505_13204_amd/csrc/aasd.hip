@@ -110,13 +110,23 @@ int launch_sweep(const aasd::SweepParams& p, const SweepPlan& pl, int64_t rows, 
     return AASD_OK;
 }
 
-// Sweep of the first rows_used[seq] rows of every sequence.  One launch covers `block` sequences and has as
-// many workgroups as the GPU holds at once (256 compute units x 2048 threads), or fewer if the rows cannot
-// be that many.
+// Sweep of the first rows_used[seq] rows of every sequence.  One launch covers `block` sequences; its grid is
+// sized to the GPU, not to the input, or smaller if the rows cannot be that many.
 template <int DT, int BLOCK, int U>
 hipError_t launch_sweep_used_one(const aasd::SweepParams& p, const SweepPlan& pl, int64_t sequences, hipStream_t stream)
 {
-    const int64_t resident = 256 * (2048 / BLOCK);
+    // twice as many workgroups as the GPU holds at once (compute units x workgroups of this kernel per compute unit)
+    static int64_t resident = 0;   // (one GPU model per process; a benign race: every thread computes the same value)
+    if (resident == 0) {
+        int dev = 0, cus = 0, per_cu = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+            cus = 256;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, aasd::row_sweep_used_kernel<DT, BLOCK, U>, BLOCK, 0) != hipSuccess ||
+            per_cu < 1)
+            per_cu = 1;
+        resident = (int64_t)cus * per_cu * 2;   // twice over: the second half starts as workgroups of the first end, which evens out their finish times
+    }
     for (int64_t seq0 = 0; seq0 < sequences; seq0 += BLOCK) {
         const int nseq = (int)(sequences - seq0 < BLOCK ? sequences - seq0 : BLOCK);
         const int64_t most = (int64_t)nseq * p.rows_per_seq * pl.nseg;

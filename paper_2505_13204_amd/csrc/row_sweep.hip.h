@@ -576,7 +576,7 @@ __global__ __launch_bounds__(BLOCK) void row_sweep_used_kernel(SweepParams p, in
     if (tid == 0) offs[0] = 0;
     __syncthreads();
 
-    const int units = offs[nseq] * p.nseg;
+    const int units = __builtin_amdgcn_readfirstlane(offs[nseq]) * p.nseg;
     for (int unit = blockIdx.x; unit < units; unit += gridDim.x) {
         const int crow = unit / p.nseg;
         int lo = 0, hi = nseq;   // the sequence s with offs[s] <= crow < offs[s + 1]
@@ -584,7 +584,10 @@ __global__ __launch_bounds__(BLOCK) void row_sweep_used_kernel(SweepParams p, in
             const int mid = (lo + hi) >> 1;
             if (offs[mid] <= crow) lo = mid; else hi = mid;
         }
-        const int64_t row = (seq0 + lo) * p.rows_per_seq + (crow - offs[lo]);
+        // the unit is the same in every lane: keep it in scalar registers (values read from LDS arrive in vector ones)
+        const int r_in_seq = __builtin_amdgcn_readfirstlane(crow - offs[lo]);
+        const int seq_local = __builtin_amdgcn_readfirstlane(lo);
+        const int64_t row = (seq0 + seq_local) * p.rows_per_seq + r_in_seq;
         sweep_unit<DT, false, false, BLOCK, U>(p, row, unit - crow * p.nseg, sh, nullptr);
     }
 }
