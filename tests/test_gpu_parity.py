@@ -185,6 +185,12 @@ def test_every_compiled_launch_shape(shape, monkeypatch):
         bk.compare_align(got, ref, bk.Tally(), oracle.EXTRAS_SAMPLE)
     zd, drafts, dl, strict = _verify_case(rng, 2, 2, 3, 40000, "bf16")
     _verify_both(zd, drafts, dl, strict, 0.1, 0.1, 0, bk.Tally())
+    # top-k verification runs the alignment form of the sweep over verify rows
+    ref = oracle.verify_topk(synth.to_host_bits(zd), drafts, dl, topk=3)
+    t = lambda a, dt: torch.as_tensor(np.ascontiguousarray(a), device=DEV).to(dt)
+    got = bk.to_np(aasd.verify_topk(zd, t(drafts, torch.int32), t(dl, torch.int32), topk=3))
+    for name in ("accept_len", "best_cand", "next_token", "row_argmax"):
+        np.testing.assert_array_equal(got[name], ref[name], err_msg=name)
 
 
 # --------------------------------------------------------------------------- retrieval

@@ -309,3 +309,19 @@ def test_verify_tree_more_sequences_than_one_launch_covers(B, N, V):
     tally = bk.Tally()
     ref, _ = _verify_tree_both(zd, tree, None, 0.1, 0.1, 0, tally)
     assert ref["accept_len"].max() >= 1
+
+
+@pytest.mark.parametrize("shape", ["256,1", "256,2", "256,4", "512,2", "512,4", "1024,1", "1024,2", "256,2,5", "512,2,8", "1024,1,4"])
+def test_verify_tree_under_every_compiled_launch_shape(shape, monkeypatch):
+    """The used-rows sweep is compiled for the same (threads, loads in flight[, segments]) shapes as the plain
+    sweep; every one of them must give the oracle's answers, for both element types."""
+    monkeypatch.setenv("AASD_SWEEP_CONFIG", shape)
+    rng = np.random.default_rng(19)
+    B, C, k, N, V = 7, 4, 5, 24, 128256 // 4 + 5
+    drafts, dl, strict, dx = _random_candidates(rng, B, C, k, 2, alphabet=30)
+    tree = oracle.build_tree(drafts, dl, strict, dx, root_tok=np.zeros(B, np.int32), max_nodes=N)
+    tally = bk.Tally()
+    for dtype in ("bf16", "f32"):
+        zd = _tree_logits(rng, tree, V, dtype, p_lead=0.5)
+        _verify_tree_both(zd, tree, tree["node_strict"], 0.1, 0.1, 0, tally)
+    assert tally.tokens > 20
