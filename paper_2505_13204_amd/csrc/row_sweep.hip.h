@@ -380,23 +380,21 @@ __device__ __forceinline__ bool process_wave(const SweepParams& p, const SegShap
 #pragma unroll
     for (int o = 4; o < 64; o <<= 1) m = fmaxf(m, __shfl_xor(m, o));
     float thr2 = -INFINITY;
-    if (ALIGN) {
+    if (ALIGN && want_cand && znext < m) {   // the same in every lane
         // The 16 group maxima are 16 distinct elements, so the c-th largest of them (c <= 8) bounds the
-        // c-th largest logit from below.  Bitonic sort of the 16 values (descending in group index);
-        // the number of elements above this bound has a light tail, unlike a minimum over c classes.
+        // c-th largest logit from below; the number of elements above this bound has a light tail, unlike a
+        // minimum over c classes.  Every lane ranks its group's maximum among the 16 (ties by group index;
+        // the values arrive by constant-lane reads, no chain of dependent shuffles), and the group whose rank
+        // is c - 1 names the bound.
         const int g = lane >> 2;
-        float v = G;
+        int rank = 0;
 #pragma unroll
-        for (int k = 2; k <= 16; k <<= 1) {
-#pragma unroll
-            for (int j = k >> 1; j > 0; j >>= 1) {
-                const float o = __shfl_xor(v, j << 2);
-                const bool desc = (g & k) == 0;    // direction of this block (the last stage: all descending)
-                const bool lower = (g & j) == 0;   // this lane holds the lower-indexed element of the pair
-                v = (lower == desc) ? fmaxf(v, o) : fminf(v, o);
-            }
+        for (int q = 0; q < 16; ++q) {
+            const float x = __shfl(G, q << 2);
+            rank += (x > G || (x == G && q < g)) ? 1 : 0;
         }
-        thr2 = __shfl(v, (p.c - 1) << 2);
+        const unsigned long long owners = __ballot(rank == p.c - 1);
+        thr2 = __shfl(G, __ffsll((long long)owners) - 1);
     }
 
     // ---- lane sums brought to the common reference m ----
