@@ -1,8 +1,10 @@
 /*
  * aasd.h - C ABI of the MI355X (gfx950) hot path of Alignment-Augmented
  * Speculative Decoding: alignment sampling over prefill logits, n-gram draft
- * retrieval over the token buffer, and conditional verification of draft
- * candidates against the target model's logits.
+ * retrieval over the token buffer (stateless, or through a persistent draft
+ * pool), conditional verification of draft candidates against the target
+ * model's logits, and the draft-tree form of the same path (tree build with
+ * its attention mask, verification over the tree's nodes).
  *
  * Conventions shared by every entry point
  *   - Pointers named in "DEVICE" lists are device (HBM) pointers owned by the
@@ -62,9 +64,9 @@ const char *aasd_last_error(void);
 
 /*
  * Measurement hook, not part of the method: while two hipEvent_t handles (passed as void*) are
- * set for the calling thread, aasd_align_sample and aasd_verify record `start` on the stream
- * immediately before and `stop` immediately after their row-sweep kernel, so that a caller can
- * time that kernel alone.  Pass NULL, NULL to switch it off (the default).
+ * set for the calling thread, aasd_align_sample, aasd_verify, aasd_verify_tree and aasd_verify_topk
+ * record `start` on the stream immediately before and `stop` immediately after their row-sweep
+ * kernel, so that a caller can time that kernel alone.  Pass NULL, NULL to switch it off (the default).
  */
 void aasd_set_sweep_events(void *start, void *stop);
 /* The same around the kernel that makes the full-vocabulary draws of AASD_EXTRAS_GUMBEL. */
