@@ -43,6 +43,9 @@ def parse():
     ap.add_argument("--extras-mode", default="top", choices=["top", "sample", "gumbel"],
                     help="how alignment sampling chooses the extras: best-ranked (Fig. 2), seeded draws among the top-c, "
                          "or seeded draws from the whole row (a second, ALU-bound kernel over the misaligned rows)")
+    ap.add_argument("--streams", type=int, default=2, choices=[1, 2],
+                    help="2: alignment sampling (prefill rows) is enqueued on a second HIP stream of the same priority, so "
+                         "that it overlaps with retrieval and verification, which do not depend on it; 1: one stream")
     ap.add_argument("--retrieval", default="scan", choices=["scan", "pool"],
                     help="n-gram retrieval by the stateless scan of the token buffer, or through the persistent draft pool "
                          "(built in set-up; the latency loop then does an incremental update and a lookup per step)")
@@ -85,6 +88,17 @@ def read_traffic(path):
                 k_, v_ = line.split("=", 1)
                 measured[k_.strip()] = v_.strip()
     return measured
+
+
+def prewarm(torch, step_fn, seconds=0.25):
+    """Part of set-up: run the step for a quarter of a second so that clocks and caches of a fresh process are
+    in their steady state before the W warm-up steps and the K timed ones (the first ~50 ms of work after start-up
+    run 5-8 % slower on this GPU, which a handful of sub-millisecond warm-up steps does not cover)."""
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < seconds:
+        for _ in range(5):
+            step_fn()
+        torch.cuda.synchronize()
 
 
 def graph_latency_us(torch, steps_fn, check, n_steps):
@@ -233,13 +247,20 @@ def main():
     verify_rows = BB * w.R
     rows_per_step = prefill_rows + verify_rows
 
-    def one_pass():
-        aasd.align_sample(prefill, next_tok_d, m=w.m, c=w.c, mode=mode, seed=w.seed, out=align_out)
+    side = torch.cuda.Stream(device=dev)   # default priority, like the main stream
+
+    def one_pass(two_streams=False):
+        if two_streams:     # prefill alignment and decode verification are independent pieces of work
+            with torch.cuda.stream(side):
+                aasd.align_sample(prefill, next_tok_d, m=w.m, c=w.c, mode=mode, seed=w.seed, out=align_out)
+        else:
+            aasd.align_sample(prefill, next_tok_d, m=w.m, c=w.c, mode=mode, seed=w.seed, out=align_out)
         do_retrieve(out=r_out)
         do_verify(verify_logits, r_out["drafts"], r_out["draft_len"], r_out["strict"], workspace=ws, out=v_out)
 
+    prewarm(torch, lambda: one_pass(args.streams == 2))
     for _ in range(args.warmup):
-        one_pass()
+        one_pass(args.streams == 2)
     torch.cuda.synchronize()
 
     # ---------------------------------------------------------------- timed region: exactly K steps
@@ -247,11 +268,19 @@ def main():
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(K):
-        one_pass()
+        one_pass(args.streams == 2)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / K
     value = rows_per_step / (ms_per_step * 1e-3)
+    ms_per_step_one_stream = ms_per_step
+    if args.streams == 2:   # for comparison: the same K steps on one stream
+        torch.cuda.synchronize()
+        ts0 = time.perf_counter()
+        for i in range(K):
+            one_pass(False)
+        torch.cuda.synchronize()
+        ms_per_step_one_stream = (time.perf_counter() - ts0) * 1e3 / K
 
     # ---------------------------------------------------------------- the same K steps again, instrumented
     # HIP events on the stream the kernels run on: one pair around each API call, and (through the library's
@@ -322,8 +351,9 @@ def main():
                    "frac": round(verify_gbs / HBM_PEAK_GBS, 4), "call_ms": round(verify_ms, 4)},
         "retrieve_drafts": {"sequences": BB, "call_ms": round(retr_ms, 4), "through": args.retrieval,
                             **({"pool_build_ms": round(pool_build_ms, 3), "pool_MB": round(pool.nbytes / 1e6, 1)} if use_pool else {})},
+        "ms_per_step_one_stream": round(ms_per_step_one_stream, 4),
         "ms_per_step_instrumented": round(ms_per_step_instrumented, 4),
-        "note": "kernel times: HIP events recorded by the library around the sweep kernel alone, over a repeat of the K timed "
+        "note": "kernel times: HIP events recorded by the library around the sweep kernel alone, over a one-stream repeat of the K timed "
                 "steps with the events switched on (they cost idle time between kernels, so the timed region runs without "
                 "them); call times include the finish kernels",
     }
@@ -399,7 +429,8 @@ def main():
                    "n_gram": [w.n_min, w.n_max], "decode_steps": S, "prefill_rows": prefill_rows,
                    "verify_rows": verify_rows, "rows_per_step": rows_per_step,
                    "form": "all decode steps verified as one batch", "extras_mode": args.extras_mode,
-                   "verifier": "top-%d" % args.topk if topk else "adaptive threshold", "retrieval": args.retrieval},
+                   "verifier": "top-%d" % args.topk if topk else "adaptive threshold", "retrieval": args.retrieval,
+                   "streams": args.streams},
         "roofline": roofline, "cpu_baseline": cpu, "latency": latency,
         "tokens_per_decode_step": round(trace.mean_accept_len, 3), "setup_s": round(setup_s, 1),
     }
@@ -507,9 +538,15 @@ def bench_tree(args, w, dev):
     setup_s = time.time() - t_setup
     rows_per_step = prefill_rows + tree_rows
 
-    def one_pass(i=None, ev=None, kev=None):
+    side = torch.cuda.Stream(device=dev)   # default priority, like the main stream
+
+    def one_pass(i=None, ev=None, kev=None, two_streams=False):
         if ev: ev[0].record(); aasd.set_sweep_events(kev[0], kev[1])
-        aasd.align_sample(prefill, next_tok_d, m=w.m, c=w.c, mode=aasd.EXTRAS_TOP, seed=w.seed, out=align_out)
+        if two_streams:     # prefill alignment does not feed the decode steps of this batch: it may overlap with them
+            with torch.cuda.stream(side):
+                aasd.align_sample(prefill, next_tok_d, m=w.m, c=w.c, mode=aasd.EXTRAS_TOP, seed=w.seed, out=align_out)
+        else:
+            aasd.align_sample(prefill, next_tok_d, m=w.m, c=w.c, mode=aasd.EXTRAS_TOP, seed=w.seed, out=align_out)
         if ev: ev[1].record()
         aasd.retrieve_drafts(tokens_b, len_b, plen_b, w.n_min, w.n_max, w.k, w.C, extras=extras_b, n_extras=n_extras_b,
                              m=w.m, extras_stride=w.L, out=r_out)
@@ -521,17 +558,26 @@ def bench_tree(args, w, dev):
                          alpha=w.alpha, beta=w.beta, workspace=ws, want_rows=False, want_nodes=False, out=v_out)
         if ev: ev[4].record()
 
+    prewarm(torch, lambda: one_pass(two_streams=args.streams == 2))
     for _ in range(args.warmup):
-        one_pass()
+        one_pass(two_streams=args.streams == 2)
     torch.cuda.synchronize()
     K = args.steps
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(K):
-        one_pass()
+        one_pass(two_streams=args.streams == 2)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / K
+    ms_per_step_one_stream = ms_per_step
+    if args.streams == 2:
+        torch.cuda.synchronize()
+        ts0 = time.perf_counter()
+        for i in range(K):
+            one_pass()
+        torch.cuda.synchronize()
+        ms_per_step_one_stream = (time.perf_counter() - ts0) * 1e3 / K
     # the same K steps again with HIP events around every call and around the sweep kernels (see main())
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(K)]
     kev = [[hip_event() for _ in range(4)] for _ in range(K)]
@@ -564,6 +610,7 @@ def bench_tree(args, w, dev):
         "retrieve_drafts": {"sequences": BB, "call_ms": round(retr_ms, 4)},
         "build_tree": {"sequences": BB, "call_ms": round(build_ms, 4), "mean_nodes": round(float(n_nodes_h.mean()), 2),
                        "max_nodes": int(n_nodes_h.max())},
+        "ms_per_step_one_stream": round(ms_per_step_one_stream, 4),
         "ms_per_step_instrumented": round(ms_per_step_instrumented, 4),
         "note": "only the rows of existing tree nodes are read and counted; kernel times from HIP events around the sweep kernel "
                 "alone, over a repeat of the K timed steps with the events switched on",
@@ -635,7 +682,7 @@ def bench_tree(args, w, dev):
         "config": {"workload": w.name, "B": w.B, "prompt_len": w.L, "V": w.V, "logits_dtype": w.dtype,
                    "k": w.k, "C": w.C, "m": w.m, "n_gram": [w.n_min, w.n_max], "max_nodes": N, "decode_steps": S,
                    "prefill_rows": prefill_rows, "tree_rows": tree_rows, "rows_per_step": rows_per_step,
-                   "form": "all decode steps built and verified as one batch of trees"},
+                   "form": "all decode steps built and verified as one batch of trees", "streams": args.streams},
         "roofline": roofline, "cpu_baseline": cpu, "latency": latency,
         "tokens_per_decode_step": round(trace.mean_accept_len, 3), "setup_s": round(setup_s, 1),
     }
