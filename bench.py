@@ -309,19 +309,20 @@ def main():
     ms_per_step_instrumented = (time.perf_counter() - ti0) * 1e3 / K
     draws = None
     if mode == aasd.EXTRAS_GUMBEL:
-        # the draw kernel is bound by instruction issue: its inner loop has 197 vector instructions per four tokens
-        # (counted in the ISA), at least one lane cycle each, against 256 CUs x 64 lanes x 2.4 GHz = 39.3e12 lane
+        # the draw kernel is bound by vector-instruction issue: rocprofv3's SQ_INSTS_VALU counts 122,043,312 wave
+        # instructions for the 168,656,640 tokens of this workload's launch, i.e. 46.3 lane cycles per token (a wave
+        # instruction occupies its 64 lanes for one cycle each), against 256 CUs x 64 lanes x 2.4 GHz = 39.3e12 lane
         # cycles per second
         draw_ms = float(np.mean([hip_elapsed(kev[i][4], kev[i][5]) for i in range(K)]))
         n_mis = int(align_out["misaligned"].sum().item())
         tokens = n_mis * w.V
-        lane_cycles = 197.0 / 4.0
+        lane_cycles = 122043312.0 * 64.0 / 168656640.0
         peak = 256 * 64 * 2.4e9 / 1e12
         ach = tokens * lane_cycles / (draw_ms * 1e-3) / 1e12
         draws = {"kernel": "aasd::gumbel_extras_kernel", "rows_drawn": n_mis, "tokens": tokens, "kernel_ms": round(draw_ms, 4),
                  "Gtokens/s": round(tokens / (draw_ms * 1e-3) / 1e9, 1),
                  "roofline": {"bound": "alu", "achieved": round(ach, 2), "peak": round(peak, 2), "unit": "T lane-cycles/s",
-                              "frac": round(ach / peak, 4), "lane_cycles_per_token": lane_cycles}}
+                              "frac": round(ach / peak, 4), "lane_cycles_per_token": round(lane_cycles, 2)}}
     align_ms = float(np.mean([ev[i][0].elapsed_time(ev[i][1]) for i in range(K)]))
     retr_ms = float(np.mean([ev[i][1].elapsed_time(ev[i][2]) for i in range(K)]))
     verify_ms = float(np.mean([ev[i][2].elapsed_time(ev[i][3]) for i in range(K)]))
