@@ -6,6 +6,7 @@
 
 #include <cstdarg>
 #include <cstdio>
+#include <atomic>
 #include <cstdlib>
 #include <cstring>
 
@@ -116,7 +117,8 @@ template <int DT, int BLOCK, int U>
 hipError_t launch_sweep_used_one(const aasd::SweepParams& p, const SweepPlan& pl, int64_t sequences, hipStream_t stream)
 {
     // twice as many workgroups as the GPU holds at once (compute units x workgroups of this kernel per compute unit)
-    static int64_t resident = 0;   // (one GPU model per process; a benign race: every thread computes the same value)
+    static std::atomic<int64_t> cached{0};   // one GPU model per process: every thread would compute the same value
+    int64_t resident = cached.load(std::memory_order_relaxed);
     if (resident == 0) {
         int dev = 0, cus = 0, per_cu = 0;
         if (hipGetDevice(&dev) != hipSuccess ||
@@ -126,6 +128,7 @@ hipError_t launch_sweep_used_one(const aasd::SweepParams& p, const SweepPlan& pl
             per_cu < 1)
             per_cu = 1;
         resident = (int64_t)cus * per_cu * 2;   // twice over: the second half starts as workgroups of the first end, which evens out their finish times
+        cached.store(resident, std::memory_order_relaxed);
     }
     for (int64_t seq0 = 0; seq0 < sequences; seq0 += BLOCK) {
         const int nseq = (int)(sequences - seq0 < BLOCK ? sequences - seq0 : BLOCK);
