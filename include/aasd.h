@@ -20,6 +20,11 @@
  *     NaN or +inf logits give unspecified numbers (never a fault).
  *   - All reductions have a fixed order and no floating-point atomics are
  *     used: the same inputs give byte-identical outputs on every run.
+ *   - Environment (for tests and tuning only): AASD_SWEEP_CONFIG="threads,loads[,segments]"
+ *     overrides the launch shape the library would pick for the row sweep
+ *     (threads in {256, 512, 1024}, loads in flight per lane in {1, 2, 4},
+ *     segments per row 1..16); a shape that is not compiled gives AASD_ERR_UNSUPPORTED.
+ *     The workspace queries answer for the shape in force.
  */
 #ifndef AASD_H
 #define AASD_H
