@@ -432,10 +432,15 @@ __device__ __forceinline__ bool process_wave(const SweepParams& p, const SegShap
                 for (int j0 = 0; j0 < nown; j0 += EPV) {
                     float cmx[EPV];
                     unpack<DT>(*(const u32x4*)(cm_lane + (size_t)j0 * Elt<DT>::kBytes), cmx);
+                    unsigned hits = 0;   // straight-line test of the EPV maxima; the rare hits are handled after it
 #pragma unroll
                     for (int e = 0; e < EPV; ++e)
-                        if (j0 + e < nown && cmx[e] > znext && cmx[e] >= thr2)
-                            note(rs.first_idx + ((j0 + e) * BLOCK + tid) * EPV);
+                        hits |= (j0 + e < nown && cmx[e] > znext && cmx[e] >= thr2) ? 1u << e : 0u;
+                    while (hits) {
+                        const int e = __ffs((int)hits) - 1;
+                        hits &= hits - 1;
+                        note(rs.first_idx + ((j0 + e) * BLOCK + tid) * EPV);
+                    }
                 }
             } else {
                 // vocabulary too large for LDS: look at every chunk again
