@@ -630,3 +630,35 @@ def test_decode_steps_captured_in_a_hip_graph_match_the_eager_launches():
         for s in range(S):
             assert (rec[s] == eager[s]).all(), (i, s, rec[s].tolist(), eager[s].tolist())
     assert any(int(e[2]) > 0 for e in eager)
+
+
+def test_verify_topk_strided_rows_zero_probability_tokens_and_tiny_vocabularies():
+    rng = np.random.default_rng(52)
+    t = lambda a, dt: torch.as_tensor(np.ascontiguousarray(a), device=DEV).to(dt)
+    # rows embedded in a larger buffer: odd row stride (rows start at any 2-byte offset), gap between sequences
+    B, C, k, V = 4, 3, 4, 1501
+    R = 1 + C * k
+    zd, drafts, dl = _topk_case(rng, B, C, k, V, "bf16", ties=True)
+    big = torch.full((B, R + 2, V + 7), 99.0, dtype=torch.bfloat16, device=DEV)   # the padding would win every row if it were read
+    big[:, :R, :V] = zd
+    ref = oracle.verify_topk(synth.to_host_bits(zd), drafts, dl, topk=4)
+    got = bk.to_np(aasd.verify_topk(big[:, :R, :V], t(drafts, torch.int32), t(dl, torch.int32), topk=4))
+    for name in ("accept_len", "best_cand", "next_token", "row_argmax"):
+        np.testing.assert_array_equal(got[name], ref[name], err_msg=name)
+    # tokens of probability zero, and vocabularies smaller than k
+    for V in (1, 3, 7, 40):
+        B, C, k = 6, 2, 3
+        R = 1 + C * k
+        z = rng.standard_normal((B, R, V)).astype(np.float32)
+        z[rng.random((B, R, V)) < 0.4] = -np.inf
+        z[:, :, 0] = np.where(np.isinf(z).all(axis=2), 0.0, z[:, :, 0])      # at least one finite logit per row
+        zd = torch.from_numpy(z).to(DEV)
+        drafts = rng.integers(0, V, size=(B, C, k)).astype(np.int32)
+        dl = rng.integers(0, k + 1, size=(B, C)).astype(np.int32)
+        for topk in (1, 2, 8):
+            ref = oracle.verify_topk(z, drafts, dl, topk=topk)
+            got = bk.to_np(aasd.verify_topk(zd, t(drafts, torch.int32), t(dl, torch.int32), topk=topk))
+            for name in ("accept_len", "best_cand", "next_token", "row_argmax"):
+                np.testing.assert_array_equal(got[name], ref[name], err_msg=f"{name} V={V} topk={topk}")
+            want = ((ref["tok_rank"] >= 0) & (ref["tok_rank"] < topk)).astype(np.uint8)
+            np.testing.assert_array_equal(got["tok_pass"], want, err_msg=f"tok_pass V={V} topk={topk}")
