@@ -325,3 +325,23 @@ def test_verify_tree_under_every_compiled_launch_shape(shape, monkeypatch):
         zd = _tree_logits(rng, tree, V, dtype, p_lead=0.5)
         _verify_tree_both(zd, tree, tree["node_strict"], 0.1, 0.1, 0, tally)
     assert tally.tokens > 20
+
+
+@pytest.mark.parametrize("V", [1, 3, 9, 70])
+def test_verify_tree_tiny_vocabularies_and_zero_probability_tokens(V):
+    rng = np.random.default_rng(60 + V)
+    B, N = 8, 12
+    tok = rng.integers(-1, V + 2, size=(B, N)).astype(np.int32)      # some ids outside the vocabulary: they fail
+    par = np.full((B, N), -1, np.int32)
+    for i in range(1, N):
+        par[:, i] = rng.integers(0, i, size=B)
+    tree = dict(node_token=tok, node_parent=par, n_nodes=rng.integers(1, N + 1, size=B).astype(np.int32))
+    z = rng.standard_normal((B, N, V)).astype(np.float32) * 2
+    z[rng.random((B, N, V)) < 0.35] = -np.inf
+    z[:, :, 0] = np.where(np.isinf(z).all(axis=2), 0.5, z[:, :, 0])   # at least one finite logit per row
+    tally = bk.Tally()
+    for dtype in ("f32", "bf16"):
+        zd = torch.from_numpy(z).to(DEV)
+        zd = zd.to(torch.bfloat16) if dtype == "bf16" else zd
+        for alpha, beta, flags in [(0.1, 0.1, 0), (0.0, 0.0, 0), (0.0, 0.3, aasd.VERIFY_NO_CLAMP)]:
+            _verify_tree_both(zd, tree, None, alpha, beta, flags, tally)
