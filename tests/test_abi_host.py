@@ -204,3 +204,12 @@ def test_pool_rejects_invalid_arguments(lib):
         assert ret(**kw) == INVALID, kw
     assert ret(pool=None) == WORKSPACE and ret(nb=need - 1) == WORKSPACE
     assert ret(B=0) == 0
+
+
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the header compiles as C99 on its own (no C++ or HIP types in it)."""
+    import subprocess
+    src = tmp_path / "use.c"
+    src.write_text('#include "aasd.h"\nint main(void) { return (int)sizeof(aasd_status) + AASD_MAX_TREE_NODES > 0 ? 0 : 1; }\n')
+    subprocess.check_call(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-fsyntax-only",
+                           "-I", os.path.join(ROOT, "include"), str(src)])
