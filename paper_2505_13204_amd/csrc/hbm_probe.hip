@@ -37,6 +37,18 @@ __global__ __launch_bounds__(256) void probe_read_kernel(const u32x4* __restrict
     if (acc == 0x12345678u) sink[0] = acc;  // practically never: keeps the loads alive
 }
 
+// the same read with non-temporal loads (the form the row sweep uses for data it reads once)
+__global__ __launch_bounds__(256) void probe_read_nt_kernel(const u32x4* __restrict__ src, unsigned* __restrict__ sink, size_t n)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    unsigned acc = 0;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        const u32x4 v = __builtin_nontemporal_load(src + i);
+        acc ^= v.x ^ v.y ^ v.z ^ v.w;
+    }
+    if (acc == 0x12345678u) sink[0] = acc;
+}
+
 int main(int argc, char** argv)
 {
     const size_t mib = argc > 1 ? (size_t)atoll(argv[1]) : 2048;
@@ -73,6 +85,14 @@ int main(int argc, char** argv)
     CHECK(hipEventSynchronize(e1));
     CHECK(hipEventElapsedTime(&ms, e0, e1));
     printf("read: %zu B read per launch, %.1f us, %.1f GB/s\n", bytes, ms * 1e3 / reps, bytes / (ms * 1e-3 / reps) / 1e9);
+    hipLaunchKernelGGL(probe_read_nt_kernel, dim3(grid), dim3(256), 0, 0, a, sink, n);
+    CHECK(hipEventRecord(e0));
+    for (int r = 0; r < reps; ++r) hipLaunchKernelGGL(probe_read_nt_kernel, dim3(grid), dim3(256), 0, 0, a, sink, n);
+    CHECK(hipEventRecord(e1));
+    CHECK(hipEventSynchronize(e1));
+    CHECK(hipEventElapsedTime(&ms, e0, e1));
+    printf("read, non-temporal loads: %zu B read per launch, %.1f us, %.1f GB/s\n", bytes, ms * 1e3 / reps,
+           bytes / (ms * 1e-3 / reps) / 1e9);
     CHECK(hipDeviceSynchronize());
     return 0;
 }
