@@ -39,11 +39,11 @@ size_t elt_size(int32_t dt) { return dt == AASD_F32 ? 4 : 2; }
 
 // Launch plan of the row sweep: threads per workgroup, 16-byte loads in flight per lane and
 // buffer, and how many contiguous segments a row is cut into (one workgroup each).
-// Measured on MI355X at V = 128256 bf16: with many rows, 1024 threads x 2 loads is fastest
-// without the LDS chunk-maximum array (verification) and 256 x 2 with it (alignment sampling,
-// whose occupancy is LDS- and register-bound; 256 x 4 is as fast at best but unstable run to run).  With few rows one workgroup per row cannot fill the GPU (a
-// single workgroup streams at some 15-30 GB/s), so rows are cut into segments until there are a
-// few thousand workgroups.  AASD_SWEEP_CONFIG="block,unroll[,segments]" overrides the plan
+// Measured on MI355X at V = 128256 bf16 (non-temporal loads): 256 threads x 2 loads is the fastest shape, or
+// within 1 % of it, at every row count, for verification (6.9 TB/s at 36864 rows against 6.7 for 1024 x 2) and
+// for alignment sampling (whose occupancy is LDS- and register-bound).  With few rows one workgroup per row
+// cannot fill the GPU (a single workgroup streams at some 15-30 GB/s), so rows are cut into segments until
+// there are several thousand workgroups.  AASD_SWEEP_CONFIG="block,unroll[,segments]" overrides the plan
 // (developer knob for tuning runs and tests).
 struct SweepPlan { int block, unroll, nseg, seg_vecs, npart; };
 
@@ -53,10 +53,10 @@ SweepPlan plan_sweep(bool align, int64_t rows, int32_t V, int32_t dt)
 {
     const int per_vec = dt == AASD_BF16 ? 8 : 4;
     const int nvec_max = V / per_vec > 0 ? V / per_vec : 1;
-    SweepPlan pl{align ? 256 : 1024, 2, 1, 0, 0};
+    SweepPlan pl{256, 2, 1, 0, 0};
     if (rows > 0 && rows < kSplitBelowRows) {
-        pl.block = 256; pl.unroll = align ? 2 : 4;
-        const int64_t want = (kSplitBelowRows + rows - 1) / rows;
+        const int64_t target = align ? 6144 : 4096;   // workgroups wanted (measured: 2048 alignment rows are fastest in 3 segments)
+        const int64_t want = (target + rows - 1) / rows;
         const int by_len = nvec_max / (pl.block * 2) > 0 ? nvec_max / (pl.block * 2) : 1;  // >= 2 vectors per lane
         const int by_part = aasd::kMaxPartials / (pl.block / aasd::kWave);
         int n = (int)(want < by_len ? want : by_len);

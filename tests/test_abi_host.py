@@ -95,8 +95,8 @@ def test_verify_rejects_invalid_arguments(lib):
 
 def test_workspace_query(lib):
     """One 32-byte partial per wave of the sweep; alignment sampling adds a list of 48 chunk positions."""
-    big = lib.aasd_verify_workspace_bytes(64, 16, 8, 152064, 1)      # 8256 rows, one workgroup of 16 waves per row
-    assert big == 64 * 129 * 16 * 32
+    big = lib.aasd_verify_workspace_bytes(64, 16, 8, 152064, 1)      # 8256 rows, one workgroup of 4 waves per row
+    assert big == 64 * 129 * 4 * 32
     small = lib.aasd_verify_workspace_bytes(1, 1, 8, 128256, 1)      # 9 rows: rows are cut into segments
     assert small % (9 * 32) == 0 and 9 * 32 < small <= 9 * 64 * 32
     assert lib.aasd_verify_workspace_bytes(1, 0, 4, 100, 1) == 0
@@ -148,7 +148,7 @@ def test_verify_tree_rejects_invalid_arguments(lib):
     assert _verify_tree(lib, wsb=lib.aasd_verify_tree_workspace_bytes(2, 16, 100, 1) - 1) == WORKSPACE
     assert _verify_tree(lib, ws=FAKE + 4) == WORKSPACE
     assert _verify_tree(lib, B=0) == 0
-    assert lib.aasd_verify_tree_workspace_bytes(64, 64, 128256, 1) == 64 * 64 * 16 * 32   # 4096 rows, 16 waves per row
+    assert lib.aasd_verify_tree_workspace_bytes(64, 64, 128256, 1) == 64 * 64 * 4 * 32   # 4096 rows, 4 waves per row
     assert lib.aasd_verify_tree_workspace_bytes(1, 0, 100, 1) == 0
     assert lib.aasd_verify_tree_workspace_bytes(1, 257, 100, 1) == 0
 
