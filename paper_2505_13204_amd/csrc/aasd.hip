@@ -62,6 +62,19 @@ SweepPlan plan_sweep(bool align, int64_t rows, int32_t V, int32_t dt)
         int n = (int)(want < by_len ? want : by_len);
         pl.nseg = n < by_part ? n : by_part;
     }
+    if (align) {
+        // The alignment sweep keeps one chunk maximum per 16-byte vector in LDS.  Rows are cut further until at
+        // least four workgroups fit the 160 KB of a compute unit (V = 152064 bf16 needs 45 KB in one piece and runs
+        // 4 % faster in two); a piece that cannot fit at all runs without the array.
+        const size_t elt = dt == AASD_BF16 ? 2 : 4;
+        const int by_part = aasd::kMaxPartials / (pl.block / aasd::kWave);
+        while (pl.nseg < by_part) {
+            const size_t per_lane = (size_t)((nvec_max + pl.nseg - 1) / pl.nseg + pl.block - 1) / pl.block * elt;
+            const size_t stride = (per_lane + 15) / 16 * 16 + 16;
+            if (stride * pl.block <= 40 * 1024) break;
+            ++pl.nseg;
+        }
+    }
     if (const char* e = getenv("AASD_SWEEP_CONFIG")) {
         int b = 0, u = 0, n = 0;
         const int got = sscanf(e, "%d,%d,%d", &b, &u, &n);

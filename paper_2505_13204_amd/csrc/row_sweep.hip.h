@@ -69,6 +69,7 @@ struct SweepParams {
 // Running state of one lane.
 struct LaneAcc {
     float vmax;   // largest logit seen
+    float v2;     // second largest chunk maximum (alignment sweep only): tells whether one chunk can hold all the lane's candidates
     int code;     // index of the first element of the chunk that set vmax
     float r2;     // reference exponent (log2 units) of s and t
     float rlim;   // chunk maximum above which the reference must move
@@ -80,7 +81,7 @@ struct LaneAcc {
 
 __device__ __forceinline__ void lane_acc_init(LaneAcc& a)
 {
-    a.vmax = -INFINITY; a.code = 0x7fffffff;
+    a.vmax = -INFINITY; a.v2 = -INFINITY; a.code = 0x7fffffff;
     a.r2 = kNegHuge; a.rlim = -INFINITY;
 #pragma unroll
     for (int i = 0; i < kNumAcc; ++i) { a.s[i] = 0.f; a.t[i] = 0.f; }
@@ -90,12 +91,13 @@ __device__ __forceinline__ void lane_acc_init(LaneAcc& a)
 // Fold N consecutive elements (first index idx0) into the lane state.
 // CLAMP: exponents are floored at a finite value so that -inf logits contribute exactly zero.
 // COUNT: count elements above zcmp.  UNIFORM: all 64 lanes are active (ballot counting).
-template <int N, bool CLAMP, bool COUNT, bool UNIFORM>
+template <int N, bool CLAMP, bool COUNT, bool UNIFORM, bool SECOND>
 __device__ __forceinline__ float accumulate(LaneAcc& a, const float (&z)[N], int idx0, float zcmp)
 {
     float cmax = z[0];
 #pragma unroll
     for (int e = 1; e < N; ++e) cmax = fmaxf(cmax, z[e]);
+    if (SECOND) a.v2 = fmaxf(a.v2, fminf(cmax, a.vmax));   // the smaller of the new maximum and the old one
     a.code = cmax > a.vmax ? idx0 : a.code;
     a.vmax = fmaxf(a.vmax, cmax);
     if (cmax > a.rlim) {  // rare: first chunk of the lane, or a jump of more than kRefSlack nats
@@ -210,7 +212,7 @@ __device__ __forceinline__ void cm_store_batch(unsigned char* cm_lane, int j0, c
 
 // The single HBM pass of one lane over its share of the row: vectors tid, tid+BLOCK, ...
 // loaded U at a time with the next batch in flight while the current one is folded in.
-template <int DT, bool CLAMP, bool COUNT, int BLOCK, int U>
+template <int DT, bool CLAMP, bool COUNT, bool SECOND, int BLOCK, int U>
 __device__ __forceinline__ void sweep_lane(LaneAcc& a, const SegShape& rs, int tid, float zcmp,
                                            bool store_cm, unsigned char* cm_lane)
 {
@@ -219,7 +221,7 @@ __device__ __forceinline__ void sweep_lane(LaneAcc& a, const SegShape& rs, int t
 
     if (tid < rs.head_n) {
         const float z1[1] = {load_elt<DT>(rs.base, tid)};
-        accumulate<1, CLAMP, COUNT, false>(a, z1, tid, zcmp);
+        accumulate<1, CLAMP, COUNT, false, SECOND>(a, z1, tid, zcmp);
     }
 
     // Full batches of BLOCK*U vectors.  Two register buffers alternate: while one batch is folded
@@ -243,7 +245,7 @@ __device__ __forceinline__ void sweep_lane(LaneAcc& a, const SegShape& rs, int t
             float z[EPV];
             unpack<DT>(buf[u], z);
             const int vec = (it * U + u) * BLOCK + tid;
-            cmax[u] = accumulate<EPV, CLAMP, COUNT, true>(a, z, rs.first_idx + vec * EPV, zcmp);
+            cmax[u] = accumulate<EPV, CLAMP, COUNT, true, SECOND>(a, z, rs.first_idx + vec * EPV, zcmp);
         }
         if (store_cm) cm_store_batch<DT, U>(cm_lane, it * U, cmax);
     };
@@ -270,7 +272,7 @@ __device__ __forceinline__ void sweep_lane(LaneAcc& a, const SegShape& rs, int t
             if (vec < rs.nvec) {
                 float z[EPV];
                 unpack<DT>(rem[u], z);
-                const float cmax = accumulate<EPV, CLAMP, COUNT, false>(a, z, rs.first_idx + vec * EPV, zcmp);
+                const float cmax = accumulate<EPV, CLAMP, COUNT, false, SECOND>(a, z, rs.first_idx + vec * EPV, zcmp);
                 if (store_cm) cm_store<DT>(cm_lane, nsuper * U + u, cmax);
             }
         }
@@ -278,7 +280,7 @@ __device__ __forceinline__ void sweep_lane(LaneAcc& a, const SegShape& rs, int t
     if (tid < rs.tail_n) {
         const int idx = rs.tail0 + tid;
         const float z1[1] = {load_elt<DT>(rs.base, idx)};
-        accumulate<1, CLAMP, COUNT, false>(a, z1, idx, zcmp);
+        accumulate<1, CLAMP, COUNT, false, SECOND>(a, z1, idx, zcmp);
     }
 }
 
@@ -371,7 +373,7 @@ __device__ __forceinline__ bool process_wave(const SweepParams& p, const SegShap
     const float zcmp = has_next ? znext : INFINITY;
 
     LaneAcc a;
-    sweep_lane<DT, CLAMP, ALIGN && COUNT, BLOCK, U>(a, rs, tid, zcmp, want_cand && p.cm_enabled, cm_lane);
+    sweep_lane<DT, CLAMP, ALIGN && COUNT, ALIGN, BLOCK, U>(a, rs, tid, zcmp, want_cand && p.cm_enabled, cm_lane);
 
     // ---- wave maximum, and a lower bound on the c-th largest logit of the wave's share ----
     float G = a.vmax;  // becomes the maximum of this lane's 4-lane group
@@ -418,11 +420,16 @@ __device__ __forceinline__ bool process_wave(const SweepParams& p, const SegShap
     int nlist = 0;
     if (want_cand && znext < m) {
         if (lane == 0) sh.count[wid] = 0;
-        if (a.vmax > znext && a.vmax >= thr2) {  // only lanes that saw a qualifying element look again
-            auto note = [&](int first_elem) {
-                const unsigned pos = atomicAdd(&sh.count[wid], 1u);
-                if (pos < (unsigned)kListCap) sh.list[wid][pos] = first_elem;
-            };
+        auto note = [&](int first_elem) {
+            const unsigned pos = atomicAdd(&sh.count[wid], 1u);
+            if (pos < (unsigned)kListCap) sh.list[wid][pos] = first_elem;
+        };
+        const bool qualifies = a.vmax > znext && a.vmax >= thr2;
+        // Almost every qualifying lane has exactly one chunk at or above the bound, the one that set its maximum,
+        // and knows where it is; only a lane whose second largest chunk maximum qualifies too looks again.
+        const bool several = qualifies && a.v2 > znext && a.v2 >= thr2;
+        if (qualifies && !several) note(a.code);
+        if (several) {
             if (tid < rs.head_n) {
                 const float z = load_elt<DT>(rs.base, tid);
                 if (z > znext && z >= thr2) note(tid);
