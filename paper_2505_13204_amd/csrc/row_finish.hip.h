@@ -144,8 +144,25 @@ __device__ __forceinline__ void row_topc_from_lists(const AlignFinishParams& p, 
                                                     float (&kz)[AASD_MAX_CANDSET], int (&ki)[AASD_MAX_CANDSET], int& nK)
 {
     const int np = p.npart;
-    // inclusive prefix of the list lengths: entry e of the row belongs to the first partial whose prefix exceeds e
-    int incl = lane < np ? wp.nlist : 0;
+    // The waves' maxima are np different tokens, so the c-th largest of them is another lower bound on the row's
+    // c-th largest logit, and a much tighter one than any single wave's when the row was cut into many short
+    // pieces (64 waves of 2000 tokens each would otherwise let through more candidates than the buffer holds).
+    if (np >= p.c) {
+        float v = lane < np ? wp.m : -INFINITY, kth = -INFINITY;
+        for (int r = 0; r < p.c; ++r) {
+            float mx = v;
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+            kth = mx;
+            const unsigned long long owners = __ballot(v == mx);
+            if (lane == __ffsll((long long)owners) - 1) v = -INFINITY;   // one wave gives up its maximum per round
+        }
+        thr2 = fmaxf(thr2, kth);
+    }
+    // inclusive prefix of the list lengths: entry e of the row belongs to the first partial whose prefix exceeds e.
+    // A partial whose maximum is below the row's bound (or not above znext) cannot hold a candidate: its list is
+    // skipped, which matters when a row was cut into many segments (up to 64 lists).
+    int incl = (lane < np && wp.m >= thr2 && wp.m > znext) ? wp.nlist : 0;
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) {
         const int up = __shfl_up(incl, o);
