@@ -1,7 +1,7 @@
 // Fused single-pass row sweep: softmax normaliser, entropy, greedy pick and (for prefill
 // rows) rank of the next prompt token and the candidate tokens ranked above it.
 //
-// A row is read from HBM exactly once with 16-byte loads.  A workgroup owns one row, or one of
+// A row is read from HBM exactly once with 16-byte non-temporal loads.  A workgroup owns one row, or one of
 // several contiguous segments of a row when there are too few rows to fill the GPU.  Every
 // wave works on its own: it folds its share into a partial result (maximum, sum of
 // exponentials, entropy sum, position of the maximum, rank count, the chunks that may hold its
@@ -15,9 +15,11 @@
 //   - the running maximum and the position of the chunk that set it (the greedy pick is then
 //     found by re-reading that one chunk),
 //   - the reference exponent of the running sums, which is only moved when a chunk exceeds it
-//     by more than 44 nats (floating point does not care about a common scale),
-//   - one chunk maximum per chunk parked in LDS, from which the few chunks that can hold a
-//     top-c token are found after the sweep; only their positions are written out, and the
+//     by more than a few nats (floating point does not care about a common scale, but the
+//     entropy sum loses accuracy if its largest term is far from the reference),
+//   - the second largest chunk maximum of the lane, and one chunk maximum per chunk parked in LDS:
+//     after the sweep a lane with one qualifying chunk names it directly, a lane with several finds
+//     them in LDS; only the positions of those chunks are written out, and the
 //     finish kernel re-reads those chunks (Sec. 3.2 / Fig. 2 need the tokens ranked above the
 //     prompt token, not a full sort).
 #pragma once
