@@ -114,7 +114,8 @@ void aasd_set_draw_events(void *start, void *stop);
  *             (NULL = no row has a next token)
  * DEVICE out: argmax[rows] i32, misaligned[rows] u8, entropy[rows] f32, p_next[rows] f32,
  *             p_max[rows] f32 (all required); rank[rows] i32 (NULL = not wanted);
- *             extras[rows, m] i32 and n_extras[rows] u8 (required when m > 0);
+ *             extras[rows, m] i32 and n_extras[rows] u8 (required when m > 0; with m = 0 an n_extras
+ *             array, if given, is set to 0);
  *             near_count: one u32 that is INCREMENTED by the number of SAMPLE draws that fell
  *             within 1e-6 (relative to the total weight) of a boundary between two picks, in
  *             GUMBEL mode by the number of rows in which a pick's key is within 5e-5 of the next

@@ -298,6 +298,8 @@ __global__ __launch_bounds__(kFinishBlock) void align_finish_kernel(AlignFinishP
                 for (int j = 0; j < p.m_x; ++j) p.extras[row * p.m_x + j] = -1;
                 p.n_extras[row] = 0;
             }
+        } else if (p.n_extras) {
+            p.n_extras[row] = 0;   // m = 0: no extras; a count array that was passed anyway is still defined
         }
     }
 }

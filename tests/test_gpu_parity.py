@@ -82,6 +82,18 @@ def test_align_no_next_tokens_and_no_rank():
     assert (got["n_extras"] == 0).all() and (got["extras"] == -1).all()
 
 
+def test_align_without_extras_defines_the_count_array():
+    """m = 0: no extras are chosen; an n_extras array that the caller passes anyway comes back as zeros."""
+    rng = np.random.default_rng(44)
+    z = _random_rows(rng, 70, 3000, "bf16")
+    nt = torch.from_numpy(rng.integers(0, 3000, size=70).astype(np.int32)).to(DEV)
+    for mode in (aasd.EXTRAS_TOP, aasd.EXTRAS_SAMPLE, aasd.EXTRAS_GUMBEL):
+        out = {"n_extras": torch.full((70,), 0xAB, dtype=torch.uint8, device=DEV)}
+        got = aasd.align_sample(z, nt, m=0, c=1, mode=mode, out=out)
+        torch.cuda.synchronize()
+        assert (got["n_extras"] == 0).all()
+
+
 def test_align_degenerate_rows():
     V = 4096
     z = np.zeros((6, V), np.float32)
