@@ -674,3 +674,24 @@ def test_verify_topk_strided_rows_zero_probability_tokens_and_tiny_vocabularies(
                 np.testing.assert_array_equal(got[name], ref[name], err_msg=f"{name} V={V} topk={topk}")
             want = ((ref["tok_rank"] >= 0) & (ref["tok_rank"] < topk)).astype(np.uint8)
             np.testing.assert_array_equal(got["tok_pass"], want, err_msg=f"tok_pass V={V} topk={topk}")
+
+
+def test_more_work_than_one_launch_covers():
+    """A launch covers at most 2^22 workgroups: 5,000,000 prefill rows and 500,000 sequences of 9 verify rows go
+    out as two launches each (tiny vocabulary, so that the oracle can follow)."""
+    rng = np.random.default_rng(71)
+    rows, V = 5_000_000, 8
+    z = (rng.standard_normal((rows, V)) * 2).astype(np.float32)
+    zd = torch.from_numpy(z).to(DEV).to(torch.bfloat16)
+    nt = rng.integers(-1, V, size=rows).astype(np.int32)
+    tally = bk.Tally()
+    got = bk.hip_align(zd, nt, 1, 2, oracle.EXTRAS_TOP)
+    ref = bk.oracle_align(zd, nt, 1, 2, oracle.EXTRAS_TOP)
+    bk.compare_align(got, ref, tally, oracle.EXTRAS_TOP)
+    B, C, k = 500_000, 1, 8
+    R = 1 + C * k
+    zv = zd[:B * R].view(B, R, V)
+    drafts = rng.integers(0, V, size=(B, C, k)).astype(np.int32)
+    dl = rng.integers(0, k + 1, size=(B, C)).astype(np.int32)
+    _verify_both(zv, drafts, dl, None, 0.1, 0.1, 0, tally)
+    print("large counts", tally)
