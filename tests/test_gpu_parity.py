@@ -688,6 +688,9 @@ def test_more_work_than_one_launch_covers():
     got = bk.hip_align(zd, nt, 1, 2, oracle.EXTRAS_TOP)
     ref = bk.oracle_align(zd, nt, 1, 2, oracle.EXTRAS_TOP)
     bk.compare_align(got, ref, tally, oracle.EXTRAS_TOP)
+    got = bk.hip_align(zd, nt, 1, 1, oracle.EXTRAS_GUMBEL, seed=5, want_rank=False)     # the draw kernel is chunked too
+    ref = bk.oracle_align(zd, nt, 1, 1, oracle.EXTRAS_GUMBEL, seed=5)
+    bk.compare_align(got, ref, tally, oracle.EXTRAS_GUMBEL)
     B, C, k = 500_000, 1, 8
     R = 1 + C * k
     zv = zd[:B * R].view(B, R, V)
