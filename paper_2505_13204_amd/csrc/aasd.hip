@@ -47,7 +47,7 @@ size_t elt_size(int32_t dt) { return dt == AASD_F32 ? 4 : 2; }
 // (developer knob for tuning runs and tests).
 struct SweepPlan { int block, unroll, nseg, seg_vecs, npart; };
 
-constexpr int64_t kSplitBelowRows = 4096;
+constexpr int64_t kSplitBelowRows = 8192;
 
 SweepPlan plan_sweep(bool align, int64_t rows, int32_t V, int32_t dt)
 {
@@ -55,7 +55,7 @@ SweepPlan plan_sweep(bool align, int64_t rows, int32_t V, int32_t dt)
     const int nvec_max = V / per_vec > 0 ? V / per_vec : 1;
     SweepPlan pl{256, 2, 1, 0, 0};
     if (rows > 0 && rows < kSplitBelowRows) {
-        const int64_t target = align ? 6144 : 4096;   // workgroups wanted (measured: 2048 alignment rows are fastest in 3 segments)
+        const int64_t target = align ? 6144 : 8192;   // workgroups wanted (measured: 2048 alignment rows are fastest in 3 segments, 4608 verify rows in 2)
         const int64_t want = (target + rows - 1) / rows;
         const int by_len = nvec_max / (pl.block * 2) > 0 ? nvec_max / (pl.block * 2) : 1;  // >= 2 vectors per lane
         const int by_part = aasd::kMaxPartials / (pl.block / aasd::kWave);
