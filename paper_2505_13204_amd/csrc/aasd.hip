@@ -395,15 +395,23 @@ int aasd_retrieve_drafts(const int32_t* tokens, int64_t tok_stride, const int32_
     p.extras = extras; p.n_extras = n_extras; p.m_x = have_table ? m : 0; p.extras_stride = extras_stride;
     p.drafts = drafts; p.draft_len = draft_len; p.src_pos = src_pos; p.n_cand = n_cand; p.key_len = key_len;
     p.draft_extras = draft_extras; p.strict = strict;
-    // positions per lane per tile: enough for the whole buffer when it fits in 64 KB of LDS, odd
-    constexpr int kMaxRun = 11;  // (8 + 1024*11) * 4 + 1024*11 = 56,352 bytes
-    int run = (int)((tok_stride + aasd::kRetrieveBlock - 1) / aasd::kRetrieveBlock);
-    if (run > kMaxRun) run = kMaxRun;
+    // Up to 512 sequences: 1024 threads each (all resident at once, the shortest chain of work per thread) and the
+    // whole buffer in one LDS tile if it fits in 56 KB.  More sequences: 256 threads each, so that a compute unit holds several sequences at once and their load,
+    // barrier and hash phases overlap (8192 sequences of 4352 tokens: 61 us against 145 us); one tile if the buffer
+    // fits in 45 KB (a second tile costs more than the lower occupancy), else tiles of 22 KB.  Positions per lane
+    // per tile are odd.
+    const bool many = B > 512;   // more sequences than 1024-thread workgroups fit the GPU at once (2 per compute unit)
+    const int block = many ? aasd::kRetrieveBlockSmall : aasd::kRetrieveBlock;
+    int max_run = 11;
+    if (many) max_run = (tok_stride + block - 1) / block <= 35 ? 35 : 17;   // (8 + 256*17) * 5 = 21,800 bytes; (8 + 1024*11) * 4 + 1024*11 = 56,352 bytes
+    int run = (int)((tok_stride + block - 1) / block);
+    if (run > max_run) run = max_run;
     run |= 1;
     p.run = run;
-    p.tile = run * aasd::kRetrieveBlock;
+    p.tile = run * block;
     const size_t dyn = (size_t)(AASD_MAX_KEY + p.tile) * 4 + (size_t)p.tile;
-    hipLaunchKernelGGL(aasd::retrieve_kernel, dim3((unsigned)B), dim3(aasd::kRetrieveBlock), dyn, (hipStream_t)stream, p);
+    if (many) hipLaunchKernelGGL(aasd::retrieve_kernel<aasd::kRetrieveBlockSmall>, dim3((unsigned)B), dim3(block), dyn, (hipStream_t)stream, p);
+    else hipLaunchKernelGGL(aasd::retrieve_kernel<aasd::kRetrieveBlock>, dim3((unsigned)B), dim3(block), dyn, (hipStream_t)stream, p);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(AASD_ERR_LAUNCH, "retrieve_drafts launch failed: %s", hipGetErrorString(e));
     return AASD_OK;

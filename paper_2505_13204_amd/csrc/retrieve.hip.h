@@ -14,7 +14,9 @@
 
 namespace aasd {
 
-constexpr int kRetrieveBlock = 1024;
+constexpr int kRetrieveBlock = 1024;       // threads per sequence when there are few sequences (latency)
+constexpr int kRetrieveBlockSmall = 256;   // and when there are many (more sequences in flight per compute unit)
+constexpr int kRetrieveTileSlots = 64;  // tiles whose longest match is remembered (later ones are always looked at again)
 constexpr uint32_t kHashBase = 0x9E3779B1u;  // odd multiplier of the window hash (mod 2^32)
 
 struct RetrieveParams {
@@ -35,7 +37,7 @@ struct RetrieveParams {
     int32_t* draft_extras;
     uint8_t* strict;
     int32_t run;   // positions per lane per tile (odd: LDS accesses of a wave then hit distinct banks)
-    int32_t tile;  // positions per tile = kRetrieveBlock * run
+    int32_t tile;  // positions per tile = threads per workgroup * run
 };
 
 // Write the outputs of one sequence from the candidate positions pos[0 .. ncand) (latest first): the
@@ -75,15 +77,16 @@ __device__ __forceinline__ void write_candidates(const RetrieveParams& p, int b,
     }
 }
 
-__global__ __launch_bounds__(kRetrieveBlock) void retrieve_kernel(RetrieveParams p)
+template <int BLOCK>
+__global__ __launch_bounds__(BLOCK) void retrieve_kernel(RetrieveParams p)
 {
-    constexpr int BLOCK = kRetrieveBlock;
     constexpr int NW = BLOCK / kWave;
     extern __shared__ __align__(16) unsigned char smem[];
     int32_t* ltok = (int32_t*)smem;                           // ltok[i] = tok[tlo - AASD_MAX_KEY + i]
     uint8_t* ell = (uint8_t*)(ltok + AASD_MAX_KEY + p.tile);  // match length of every position of the tile
     __shared__ int32_t suffix[AASD_MAX_KEY];                  // suffix[i] = tok[len - 1 - i]
     __shared__ int s_best;
+    __shared__ int tile_best[kRetrieveTileSlots];             // longest match inside each of the first tiles
     __shared__ int wave_cnt[NW];
     __shared__ int32_t pos[AASD_MAX_CANDIDATES];
 
@@ -98,6 +101,7 @@ __global__ __launch_bounds__(kRetrieveBlock) void retrieve_kernel(RetrieveParams
 
     if (tid < AASD_MAX_KEY) suffix[tid] = (len - 1 - tid >= 0) ? tok[len - 1 - tid] : 0;
     if (tid == 0) s_best = 0;
+    for (int i = tid; i < kRetrieveTileSlots; i += BLOCK) tile_best[i] = 0;
     __syncthreads();
 
     int n_star = 0, count = 0;
@@ -147,11 +151,17 @@ __global__ __launch_bounds__(kRetrieveBlock) void retrieve_kernel(RetrieveParams
             return best;
         };
 
-        // pass A: longest key that occurs anywhere
+        // pass A: longest key that occurs anywhere, and in which tiles
         int best = 0;
         for (int t = 0; t < ntiles; ++t) {
             if (t > 0) __syncthreads();  // the previous tile is no longer read
-            best = max(best, stage_and_match(t));
+            int tb = stage_and_match(t);
+            best = max(best, tb);
+            if (t < kRetrieveTileSlots) {
+#pragma unroll
+                for (int o = 32; o > 0; o >>= 1) tb = max(tb, __shfl_xor(tb, o));
+                if (lane == 0 && tb > 0) atomicMax(&tile_best[t], tb);
+            }
         }
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) best = max(best, __shfl_xor(best, o));
@@ -159,34 +169,50 @@ __global__ __launch_bounds__(kRetrieveBlock) void retrieve_kernel(RetrieveParams
         __syncthreads();
         n_star = s_best;
 
-        // pass B: hits of that key length, latest first (the last tile is still resident)
+        // pass B: hits of that key length, latest first.  Tiles without such a hit are skipped; in the others a
+        // thread counts the hits of its run, one scan over the threads (in descending position order) gives every
+        // thread the number of later hits, and it writes its own, latest first, while there is room.
         if (n_star > 0) {
+            int resident = ntiles - 1;   // the tile whose match lengths are in LDS
             for (int t = ntiles - 1; t >= 0 && count < C; --t) {
-                if (t != ntiles - 1) {
+                if (t < kRetrieveTileSlots && tile_best[t] < n_star) continue;   // the same in every thread
+                if (t != resident) {
                     __syncthreads();
                     stage_and_match(t);
-                    __syncthreads();
+                    resident = t;
                 }
+                __syncthreads();
                 const int tlo = t * tile;
                 const int thi = min(tlo + tile, len);
-                for (int base = thi - 1; base >= tlo && count < C; base -= BLOCK) {
-                    const int pp = base - tid;
-                    const bool hit = pp >= tlo && ell[pp - tlo] >= n_star;
-                    const unsigned long long bal = __ballot(hit);
-                    const int before = __popcll(bal & ((1ull << lane) - 1ull));
-                    if (lane == 0) wave_cnt[wid] = __popcll(bal);
-                    __syncthreads();
-                    int offset = count, total = 0;
-#pragma unroll
-                    for (int w = 0; w < NW; ++w) {
-                        const int cw = wave_cnt[w];
-                        if (w < wid) offset += cw;
-                        total += cw;
-                    }
-                    if (hit && offset + before < C) pos[offset + before] = pp;
-                    count += total;
-                    __syncthreads();
+                const int pstart = tlo + tid * run;
+                int mine = 0;
+                for (int q = 0; q < run; ++q) {
+                    const int pp = pstart + q;
+                    if (pp < thi && ell[pp - tlo] >= n_star) ++mine;
                 }
+                // hits in threads with a higher index: suffix sum over the lanes, then over the waves
+                int incl = mine;
+#pragma unroll
+                for (int o = 1; o < 64; o <<= 1) {
+                    const int dn = __shfl_down(incl, o);
+                    if (lane + o < 64) incl += dn;
+                }
+                if (lane == 0) wave_cnt[wid] = incl;
+                __syncthreads();
+                int later = incl - mine, total = 0;
+#pragma unroll
+                for (int w = 0; w < NW; ++w) {
+                    const int cw = wave_cnt[w];
+                    if (w > wid) later += cw;
+                    total += cw;
+                }
+                int slot = count + later;
+                for (int q = run - 1; q >= 0 && mine > 0 && slot < C; --q) {
+                    const int pp = pstart + q;
+                    if (pp < thi && ell[pp - tlo] >= n_star) pos[slot++] = pp;
+                }
+                count += total;
+                __syncthreads();   // wave_cnt and ell are reused by the next tile
             }
         }
     }

@@ -220,9 +220,9 @@ def _retrieve_both(tokens, lens, plens, n_min, n_max, k, C, extras=None, n_extra
 
 @pytest.mark.parametrize("n_min,n_max,k,C", [(1, 1, 1, 1), (1, 6, 6, 4), (3, 3, 4, 2), (2, 4, 8, 16), (1, 8, 16, 32)])
 @pytest.mark.parametrize("cap", [1, 90, 1500, 12000, 30011])
-def test_retrieve_random_small_alphabet(n_min, n_max, k, C, cap):
-    rng = np.random.default_rng(cap + n_max)
-    B = 24
+@pytest.mark.parametrize("B", [24, 520])    # up to 512 sequences: 1024 threads each; more: 256 threads each, smaller tiles
+def test_retrieve_random_small_alphabet(n_min, n_max, k, C, cap, B):
+    rng = np.random.default_rng(cap + n_max + B)
     alphabet = 3 if cap < 2000 else 40
     toks = rng.integers(0, alphabet, size=(B, cap)).astype(np.int32)
     lens = rng.integers(0, cap + 1, size=B).astype(np.int32)
@@ -233,26 +233,26 @@ def test_retrieve_random_small_alphabet(n_min, n_max, k, C, cap):
         assert (ref["n_cand"] > 0).any()
 
 
-def test_retrieve_planted_spans_multi_tile_and_extras():
+@pytest.mark.parametrize("B", [3, 513])
+def test_retrieve_planted_spans_multi_tile_and_extras(B):
     """A 20000-token context (two LDS tiles) with spans repeated across the tile boundary, plus
     gathering of the alignment extras."""
     rng = np.random.default_rng(4)
     L, V, m = 20000, 50000, 2
-    B = 3
     toks = rng.integers(0, V, size=(B, L + 64)).astype(np.int32)
     for b in range(B):
         span = toks[b, 100:140].copy()
-        for dst in (5000, 11200, 11264 - 5, 19000):  # 11264 = tile size for this capacity
+        for dst in (5000, 2 * 4352 - 5, 11200, 11264 - 5, 19000):  # tiles: 11264 positions with few sequences, 4352 with many
             toks[b, dst:dst + 40] = span
         toks[b, L - 6:L] = span[10:16]  # the context ends inside the span
     lens = np.full(B, L, np.int32)
-    plens = np.array([L, 12000, 0], np.int32)
+    plens = np.resize(np.array([L, 12000, 0], np.int32), B)
     extras = rng.integers(0, V, size=(B * L, m)).astype(np.int32)
     n_extras = rng.integers(0, m + 1, size=B * L).astype(np.uint8)
     extras[np.arange(m)[None, :] >= n_extras[:, None]] = -1
     ref = _retrieve_both(toks, lens, plens, 2, 6, 8, 8, extras=extras, n_extras=n_extras, m=m, xs=L)
-    assert (ref["key_len"] == 6).all() and (ref["n_cand"] == 5).all()
-    assert ref["src_pos"][0].tolist()[:5] == [19016, 11264 - 5 + 16, 11200 + 16, 5016, 116]
+    assert (ref["key_len"] == 6).all() and (ref["n_cand"] == 6).all()
+    assert ref["src_pos"][0].tolist()[:6] == [19016, 11264 - 5 + 16, 11200 + 16, 2 * 4352 - 5 + 16, 5016, 116]
 
 
 def test_retrieve_hash_collision_is_not_a_hit():
