@@ -248,6 +248,14 @@ __global__ __launch_bounds__(kFinishBlock) void align_finish_kernel(AlignFinishP
     if (row >= p.rows) return;  // whole wave; the kernel has no barrier
     const int V = p.V, np = p.npart;
 
+    // The kernel is a chain of dependent loads; the logit of the prompt's next token depends on nothing computed
+    // here, so its two loads go first and overlap with those of the partials and of the argmax chunk.
+    const RowShape rs = row_shape<DT>(p.logits, row * p.row_stride, V);
+    int nt = p.next_tok ? p.next_tok[row] : -1;
+    if (nt >= V) nt = -1;
+    const bool has_next = nt >= 0;
+    const float znext = has_next ? load_elt<DT>(rs.base, nt) : 0.f;
+
     // ---- merge the partials: lane s holds partial s ----
     WavePartial wp;
     wp.m = -INFINITY; wp.S = 0.f; wp.T = 0.f; wp.code = 0x7fffffff; wp.cnt = 0; wp.nlist = 0; wp.thr2 = -INFINITY;
@@ -266,14 +274,8 @@ __global__ __launch_bounds__(kFinishBlock) void align_finish_kernel(AlignFinishP
     const int code = wave_min(live && wp.m == m ? wp.code : 0x7fffffff);
     const unsigned rank = wave_sum(wp.cnt);
 
-    const RowShape rs = row_shape<DT>(p.logits, row * p.row_stride, V);
     const int am = wave_first_max<DT>(rs, V, code, m, lane);
     const float H = entropy_from_sums(S, T2);
-
-    int nt = p.next_tok ? p.next_tok[row] : -1;
-    if (nt >= V) nt = -1;
-    const bool has_next = nt >= 0;
-    const float znext = has_next ? load_elt<DT>(rs.base, nt) : 0.f;
     const bool mis = has_next && znext < m;
 
     // ---- top-c of the row among the tokens of the listed chunks ----
