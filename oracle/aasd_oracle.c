@@ -537,7 +537,7 @@ int orc_build_tree(const int32_t *drafts, const int32_t *draft_len, const uint8_
 {
     if (!drafts || !draft_len || B < 0) return -1;
     if (k < 1 || k > 16 || C < 1 || C > 32 || m_x < 0 || m_x > 4) return -1;
-    if (max_nodes < 1 || max_nodes > 256) return -1;
+    if (max_nodes < 1 || max_nodes > 512) return -1;   /* 16 candidates x 8 tokens x (1 + 2 extras) + root = 385 (Sec. 3.2, Sec. 4.1) */
     const int32_t N = max_nodes, W = (N + 31) / 32;
     int32_t *tok = (int32_t *)malloc(sizeof(int32_t) * (size_t)N);
     int32_t *par = (int32_t *)malloc(sizeof(int32_t) * (size_t)N);
@@ -620,7 +620,7 @@ int orc_verify_tree(const void *logits, int dtype, int32_t B, int32_t N, int32_t
 {
     if (!logits || !node_token || !node_parent || !n_nodes || B < 0 || V <= 0) return -1;
     if (dtype != ORC_F32 && dtype != ORC_BF16) return -1;
-    if (N < 1 || N > 256 || row_stride < V || seq_stride < (int64_t)N * row_stride) return -1;
+    if (N < 1 || N > 512 || row_stride < V || seq_stride < (int64_t)N * row_stride) return -1;
 
     double *z = (double *)malloc(sizeof(double) * 2 * (size_t)V);
     double *m = (double *)malloc(sizeof(double) * (size_t)N);

@@ -120,7 +120,7 @@ int orc_verify_topk(const void *logits, int dtype, int32_t B, int32_t C, int32_t
  *   order (candidate, slot), slot 0 = the retrieved token, slots 1..m_x = its extras; a (parent,
  *   token) pair that already exists is reused, otherwise it becomes the next node.  Extras are
  *   siblings of the retrieved token and have no continuation of their own.  Nodes beyond
- *   max_nodes are dropped (and with them whatever would hang below).  A node is strict iff every
+ *   max_nodes (at most 512) are dropped (and with them whatever would hang below).  A node is strict iff every
  *   occurrence that maps to it is a strict retrieved token.
  * Outputs (any may be NULL): node_token/node_parent/node_depth [B,max_nodes] (-1 / -1 / 0 for
  *   unused slots; root: token root_tok[b] or -1, parent -1), node_strict [B,max_nodes],

@@ -65,19 +65,27 @@ def _trie_reference(drafts, draft_len, strict, dx, max_nodes):
     return nodes, is_strict, cand_node
 
 
-@pytest.mark.parametrize("C,k,m,N", [(1, 4, 0, 8), (3, 4, 2, 64), (8, 8, 2, 40), (16, 8, 2, 256), (32, 16, 4, 256), (4, 6, 3, 5)])
-def test_tree_build_against_dictionary_trie(C, k, m, N):
-    rng = np.random.default_rng(C * 100 + k)
+@pytest.mark.parametrize("C,k,m,N,alphabet", [(1, 4, 0, 8, 3), (3, 4, 2, 64, 3), (8, 8, 2, 40, 3), (16, 8, 2, 256, 3),
+                                              (32, 16, 4, 256, 3), (4, 6, 3, 5, 3),
+                                              # the paper's parameters (Sec. 4.1: up to two extras per position) need up to
+                                              # 1 + 16*8*3 = 385 nodes; a wider alphabet shares fewer prefixes and fills them
+                                              (16, 8, 2, 385, 12), (16, 8, 2, 512, 40), (32, 16, 4, 512, 6), (16, 8, 2, 300, 40)])
+def test_tree_build_against_dictionary_trie(C, k, m, N, alphabet):
+    rng = np.random.default_rng(C * 100 + k + alphabet)
     B = 12
-    drafts = rng.integers(0, 3, size=(B, C, k)).astype(np.int32)   # tiny alphabet: many shared prefixes
+    drafts = rng.integers(0, alphabet, size=(B, C, k)).astype(np.int32)   # small alphabet: shared prefixes
     drafts[rng.random((B, C, k)) < 0.05] = -1                      # a missing token ends the candidate's path
     dl = rng.integers(0, k + 1, size=(B, C)).astype(np.int32)
     strict = (rng.random((B, C, k)) < 0.4).astype(np.uint8)
     dx = None
     if m:
-        dx = rng.integers(0, 4, size=(B, C, k, m)).astype(np.int32)
-        dx[rng.random((B, C, k, m)) < 0.5] = -1
+        dx = rng.integers(0, alphabet + 1, size=(B, C, k, m)).astype(np.int32)
+        dx[rng.random((B, C, k, m)) < (0.5 if alphabet == 3 else 0.1)] = -1
+    if alphabet > 3:
+        dl[:] = np.maximum(dl, k - 1)                                     # long candidates: large trees
     t = oracle.build_tree(drafts, dl, strict, dx, root_tok=np.arange(B), max_nodes=N)
+    if N >= 385:
+        assert t["n_nodes"].max() > 256                                   # the case needs the larger budget
     W = (N + 31) // 32
     for b in range(B):
         nodes, st, cand_node = _trie_reference(drafts[b], dl[b], strict[b], None if dx is None else dx[b], N)
@@ -101,6 +109,54 @@ def test_tree_build_against_dictionary_trie(C, k, m, N):
         for i in range(1, n):
             p = nodes[i][1]
             assert 0 <= p < i and nodes[i][2] == nodes[p][2] + 1
+
+
+def test_tree_at_the_papers_largest_parameters_has_385_nodes():
+    """16 candidates of 8 tokens, every position misaligned with two extras (the shape of Fig. 2's caption at every
+    position; Sec. 4.1 allows at most two), all tokens distinct: nothing merges, so the tree is known in closed form.
+    Layer j holds 48 nodes in (candidate, slot) order; the retrieved token of (j, c) is the parent of layer j+1's
+    three nodes of candidate c; every extra is a leaf."""
+    C, k, m = 16, 8, 2
+    per = 1 + m
+    drafts = (1000 + np.arange(C * k)).reshape(1, C, k).astype(np.int32)
+    dx = (5000 + np.arange(C * k * m)).reshape(1, C, k, m).astype(np.int32)
+    dl = np.full((1, C), k, np.int32)
+    strict = np.zeros((1, C, k), np.uint8)
+    strict[0, :, 4:] = 1
+    node = lambda j, c, s: 1 + (j - 1) * C * per + c * per + s      # j = 1..k
+    t = oracle.build_tree(drafts, dl, strict, dx, root_tok=[7], max_nodes=512)
+    assert t["n_nodes"][0] == 1 + C * k * per == 385
+    for j in range(1, k + 1):
+        for c in range(C):
+            for s in range(per):
+                i = node(j, c, s)
+                want_tok = drafts[0, c, j - 1] if s == 0 else dx[0, c, j - 1, s - 1]
+                want_par = 0 if j == 1 else node(j - 1, c, 0)
+                assert (t["node_token"][0, i], t["node_parent"][0, i], t["node_depth"][0, i]) == (want_tok, want_par, j)
+                assert t["node_strict"][0, i] == (1 if s == 0 and j > 4 else 0)
+                row = t["mask"][0, i]
+                bits = {a for a in range(512) if (row[a // 32] >> (a % 32)) & 1}
+                assert bits == {0, i} | {node(jj, c, 0) for jj in range(1, j)}
+            assert t["cand_node"][0, c, j - 1] == node(j, c, 0)
+    assert (t["node_token"][0, 385:] == -1).all() and (t["mask"][0, 385:] == 0).all()
+    # the same input under a budget of 256: creation order is kept, the rest is dropped with what hangs below it
+    t2 = oracle.build_tree(drafts, dl, strict, dx, root_tok=[7], max_nodes=256)
+    assert t2["n_nodes"][0] == 256
+    np.testing.assert_array_equal(t2["node_token"][0], t["node_token"][0, :256])
+    np.testing.assert_array_equal(t2["node_parent"][0], t["node_parent"][0, :256])
+    dropped = t["cand_node"][0] >= 256
+    assert (t2["cand_node"][0][dropped] == -1).all() and (t2["cand_node"][0][~dropped] == t["cand_node"][0][~dropped]).all()
+    # verification over all 385 rows: the stream follows candidate 9 to its end
+    V = 7000
+    z = np.full((1, 512, V), -20.0, np.float32)
+    for i in range(385):
+        z[0, i, 3] = 0.0                                             # a token no node carries wins every row ...
+    path = [0] + [node(j, 9, 0) for j in range(1, k + 1)]
+    for a, nxt in zip(path[:-1], path[1:]):
+        z[0, a, t["node_token"][0, nxt]] = 5.0                       # ... except along the path of candidate 9
+    out = oracle.verify_tree(z, t["node_token"], t["node_parent"], t["node_strict"], t["n_nodes"], alpha=F32A, beta=F32A)
+    assert out["accept_len"][0] == k and out["best_node"][0] == node(k, 9, 0) and out["next_token"][0] == 3
+    assert out["accept_path"][0, :k].tolist() == path[1:]
 
 
 def _random_rows(rng, B, R, V):
