@@ -139,7 +139,8 @@ def main():
     import torch
 
     import paper_2505_13204_amd as aasd
-    from paper_2505_13204_amd import _lib, harness, synth
+    from paper_2505_13204_amd import _lib
+    from tests import harness, synth
 
     _lib.load()  # no CPU fallback: fail loudly if the HIP library is missing
     assert torch.cuda.is_available(), "bench.py needs a GPU"
@@ -449,7 +450,7 @@ def bench_tree(args, w, dev):
     import torch
 
     import paper_2505_13204_amd as aasd
-    from paper_2505_13204_amd import harness, synth
+    from tests import harness, synth
 
     elt = 2 if w.dtype == "bf16" else 4
     dt_code = aasd.BF16 if w.dtype == "bf16" else aasd.F32

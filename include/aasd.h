@@ -12,19 +12,21 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Calls only enqueue work; outputs are valid once the caller has
  *     synchronised the stream.  There is no host synchronisation inside.
- *   - Return value: AASD_OK (0) or a negative aasd_status.  On an error nothing
- *     is enqueued.  aasd_last_error() returns a thread-local message for the
- *     last failing call on the calling thread.  No exception crosses the ABI.
+ *   - Return value: AASD_OK (0) or a negative aasd_status.  Every argument is
+ *     checked before the first launch: with AASD_ERR_INVALID_ARG,
+ *     AASD_ERR_UNSUPPORTED or AASD_ERR_WORKSPACE nothing has been enqueued.
+ *     AASD_ERR_LAUNCH means that the HIP runtime refused a launch; kernels that
+ *     the same call launched before it may already be enqueued, and the outputs
+ *     are then undefined.  aasd_last_error() returns a thread-local message for
+ *     the last failing call on the calling thread.  No exception crosses the ABI.
  *   - A call with zero rows / zero sequences succeeds and enqueues nothing.
  *   - Logits must be finite or -inf, with at least one finite value per row;
  *     NaN or +inf logits give unspecified numbers (never a fault).
  *   - All reductions have a fixed order and no floating-point atomics are
  *     used: the same inputs give byte-identical outputs on every run.
- *   - Environment (for tests and tuning only): AASD_SWEEP_CONFIG="threads,loads[,segments]"
- *     overrides the launch shape the library would pick for the row sweep
- *     (threads in {256, 512, 1024}, loads in flight per lane in {1, 2, 4},
- *     segments per row 1..16); a shape that is not compiled gives AASD_ERR_UNSUPPORTED.
- *     The workspace queries answer for the shape in force.
+ *   - The library reads no environment variable and keeps no state between
+ *     calls besides the last error message.  (Measurement and test hooks, off
+ *     by default, are declared apart in aasd_hooks.h.)
  */
 #ifndef AASD_H
 #define AASD_H
@@ -55,6 +57,7 @@ typedef enum {
 
 /* aasd_verify flags */
 #define AASD_VERIFY_NO_CLAMP 1u /* threshold alpha*H+beta without the min with Delta (Eq. 3 when alpha = 0) */
+#define AASD_VERIFY_ZEROED_WORKSPACE 2u /* the caller vouches for the workspace's counters: one launch instead of two (see aasd_verify) */
 
 /* limits */
 #define AASD_MAX_EXTRAS 4      /* m */
@@ -62,20 +65,10 @@ typedef enum {
 #define AASD_MAX_KEY 8         /* n_max */
 #define AASD_MAX_DRAFT 16      /* k */
 #define AASD_MAX_CANDIDATES 32 /* C */
-#define AASD_MAX_TREE_NODES 256 /* nodes of a draft tree, root included */
+#define AASD_MAX_TREE_NODES 512 /* nodes of a draft tree, root included (16 candidates x 8 tokens x (1 + 2 extras) + 1 = 385) */
 
 const char *aasd_version(void);
 const char *aasd_last_error(void);
-
-/*
- * Measurement hook, not part of the method: while two hipEvent_t handles (passed as void*) are
- * set for the calling thread, aasd_align_sample, aasd_verify, aasd_verify_tree and aasd_verify_topk
- * record `start` on the stream immediately before and `stop` immediately after their row-sweep
- * kernel, so that a caller can time that kernel alone.  Pass NULL, NULL to switch it off (the default).
- */
-void aasd_set_sweep_events(void *start, void *stop);
-/* The same around the kernel that makes the full-vocabulary draws of AASD_EXTRAS_GUMBEL. */
-void aasd_set_draw_events(void *start, void *stop);
 
 /*
  * Alignment sampling over the prefill logits (Sec. 2.3 for aligned/misaligned
@@ -196,8 +189,20 @@ size_t aasd_verify_workspace_bytes(int32_t B, int32_t C, int32_t k, int32_t V, i
  *             tok_p[B,C,k], tok_delta[B,C,k] f32 (0 beyond draft_len; NULL = not wanted);
  *             near_count[B] u32 = number of evaluated tokens (up to and including each
  *             candidate's first failure) with |p - delta| < 1e-6 (NULL = not wanted)
- * workspace : DEVICE scratch of at least aasd_verify_workspace_bytes(B, C, k, V, dt) bytes, 16-byte
- *             aligned; it needs no initialisation and holds nothing of value afterwards
+ * workspace : DEVICE scratch of at least aasd_verify_workspace_bytes(B, C, k, V, dt) bytes, 128-byte
+ *             aligned; it needs no initialisation and holds nothing of value afterwards.
+ *             The call enqueues two kernels (row sweep, then decisions).  With
+ *             AASD_VERIFY_ZEROED_WORKSPACE it may enqueue ONE instead (it does when the rows are few
+ *             enough for all workgroups of the launch to be on the GPU at once, the case of a decode
+ *             step), in which the last workgroup to finish a
+ *             sequence's rows also takes that sequence's decisions; this form counts finished
+ *             workgroups in counters at the start of the workspace, which must be zero when the
+ *             kernel starts and are zero again when it ends.  By setting the flag the caller vouches
+ *             for that: the workspace was zero-filled once, and has since been used only by calls of
+ *             aasd_verify with this flag and the same B, C, k, V, dt that ran to completion (calls
+ *             that share a workspace must not overlap in either form).  The two forms add the same
+ *             terms in a different order: their decisions agree (except within rounding of a
+ *             threshold), row_argmax exactly, probabilities and entropies to fp32 rounding.
  * Parameters: 1 <= k <= 16, 1 <= C <= 32, V >= 1, row_stride >= V, seq_stride >= R*row_stride.
  */
 int aasd_verify(const void *logits, int32_t dt, int32_t B, int32_t C, int32_t k, int32_t V,
@@ -286,7 +291,7 @@ int aasd_verify_topk(const void *logits, int32_t dt, int32_t B, int32_t C, int32
  *             mask[B, max_nodes, W] u32 with W = (max_nodes+31)/32: bit a of row i is set iff node a
  *             is node i or an ancestor of it (NULL = not wanted);
  *             cand_node[B,C,k] i32: the node of every candidate token, -1 if none (NULL = not wanted)
- * Parameters: 1 <= k <= 16, 1 <= C <= 32, 0 <= m <= 4, 1 <= max_nodes <= 256, B >= 0.
+ * Parameters: 1 <= k <= 16, 1 <= C <= 32, 0 <= m <= 4, 1 <= max_nodes <= 512, B >= 0.
  */
 int aasd_build_tree(const int32_t *drafts, const int32_t *draft_len, const uint8_t *strict,
                     const int32_t *draft_extras, int32_t m, const int32_t *root_tok, int32_t B,
@@ -313,7 +318,7 @@ int aasd_build_tree(const int32_t *drafts, const int32_t *draft_len, const uint8
  *             accepted) with |p - delta| < 1e-6 (each NULL = not wanted)
  * workspace : DEVICE scratch of at least aasd_verify_tree_workspace_bytes(B, N, V, dt) bytes, 16-byte
  *             aligned; needs no initialisation.
- * Parameters: 1 <= N <= 256, V >= 1, row_stride >= V, seq_stride >= N*row_stride, B >= 0.
+ * Parameters: 1 <= N <= 512, V >= 1, row_stride >= V, seq_stride >= N*row_stride, B >= 0.
  */
 size_t aasd_verify_tree_workspace_bytes(int32_t B, int32_t N, int32_t V, int32_t dt);
 int aasd_verify_tree(const void *logits, int32_t dt, int32_t B, int32_t N, int32_t V,

@@ -1,0 +1,38 @@
+/*
+ * aasd_hooks.h - measurement and test hooks of libaasd.  NOT part of the method and not needed by a
+ * caller of aasd.h: a benchmark uses them to time one kernel of a call, the tests use them to force
+ * every compiled launch shape.  Each hook acts on the calling thread only and is off by default.
+ */
+#ifndef AASD_HOOKS_H
+#define AASD_HOOKS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/*
+ * While two hipEvent_t handles (passed as void*) are set, aasd_align_sample, aasd_verify,
+ * aasd_verify_tree and aasd_verify_topk record `start` on the stream immediately before and `stop`
+ * immediately after their row-sweep kernel (for the one-launch form of aasd_verify: its only kernel),
+ * so that a caller can time that kernel alone.  NULL, NULL switches it off.
+ */
+void aasd_hook_sweep_events(void *start, void *stop);
+/* The same around the kernel that makes the full-vocabulary draws of AASD_EXTRAS_GUMBEL. */
+void aasd_hook_draw_events(void *start, void *stop);
+
+/*
+ * Overrides the launch shape that the library would pick for the row sweep: threads per workgroup,
+ * 16-byte loads in flight per lane, segments a row is cut into (0 = leave that to the library).
+ * Compiled shapes: 256 x {1, 2, 4}, 512 x {2, 4}, 1024 x {1, 2}; segments 1..16.  (0, 0, n) overrides
+ * the segments only, (0, 0, 0) switches the override off.  Returns AASD_OK, or an error for a shape
+ * that is not compiled (the override is then unchanged).  The workspace queries answer for the shape
+ * in force, so set it before asking.
+ */
+int aasd_hook_sweep_plan(int32_t threads, int32_t loads, int32_t segments);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AASD_HOOKS_H */

@@ -16,9 +16,10 @@ from . import _lib
 F32, BF16 = 0, 1
 EXTRAS_TOP, EXTRAS_SAMPLE, EXTRAS_GUMBEL = 0, 1, 2
 VERIFY_NO_CLAMP = 1
+VERIFY_ZEROED_WORKSPACE = 2
 
 MAX_EXTRAS, MAX_CANDSET, MAX_KEY, MAX_DRAFT, MAX_CANDIDATES = 4, 8, 8, 16, 32
-MAX_TREE_NODES = 256
+MAX_TREE_NODES = 512
 HASH_BASE = 0x9E3779B1  # multiplier of the retrieval kernel's window hash (mod 2^32)
 
 
@@ -39,12 +40,17 @@ def _check(rc: int):
 
 def set_sweep_events(start, stop):
     """Measurement hook: raw hipEvent_t handles (ints) recorded around the row-sweep kernel; None, None = off."""
-    _lib.load().aasd_set_sweep_events(start, stop)
+    _lib.load().aasd_hook_sweep_events(start, stop)
 
 
 def set_draw_events(start, stop):
     """The same hook around the kernel that makes the full-vocabulary draws of EXTRAS_GUMBEL."""
-    _lib.load().aasd_set_draw_events(start, stop)
+    _lib.load().aasd_hook_draw_events(start, stop)
+
+
+def set_sweep_plan(threads: int = 0, loads: int = 0, segments: int = 0):
+    """Test hook: force the launch shape of the row sweep for this thread; (0, 0, 0) = the library picks."""
+    _check(_lib.load().aasd_hook_sweep_plan(threads, loads, segments))
 
 
 def _dtype_code(t: torch.Tensor) -> int:
@@ -235,11 +241,13 @@ def verify_workspace_bytes(B: int, C: int, k: int, V: int, dt: int) -> int:
 def verify(logits: torch.Tensor, drafts: torch.Tensor, draft_len: torch.Tensor, strict: Optional[torch.Tensor] = None,
            alpha: float = 0.1, beta: float = 0.1, flags: int = 0, V: Optional[int] = None,
            want_rows: bool = True, want_tokens: bool = True, want_near: bool = True,
-           workspace: Optional[torch.Tensor] = None, out: Optional[dict] = None):
+           workspace: Optional[torch.Tensor] = None, out: Optional[dict] = None, zeroed_workspace: bool = False):
     """aasd_verify over logits[B, R, row_stride], R = 1 + C*k, drafts [B,C,k], draft_len [B,C].
 
     Returns a dict of device tensors: accept_len, best_cand, next_token [B]; row_entropy, row_pmax,
-    row_argmax [B,R]; tok_p, tok_delta [B,C,k]; near_count [B] (the optional ones may be None)."""
+    row_argmax [B,R]; tok_p, tok_delta [B,C,k]; near_count [B] (the optional ones may be None).
+    zeroed_workspace=True passes AASD_VERIFY_ZEROED_WORKSPACE (one launch): the workspace given must have been
+    zero-filled once and used since only by such calls with the same B."""
     _dev_check(logits, drafts, draft_len, strict, workspace)
     assert logits.dim() == 3 and logits.stride(2) == 1
     B, R = logits.shape[0], logits.shape[1]
@@ -271,7 +279,11 @@ def verify(logits: torch.Tensor, drafts: torch.Tensor, draft_len: torch.Tensor, 
     if workspace is None:
         workspace = o.get("workspace")
     if workspace is None or workspace.numel() * workspace.element_size() < ws_bytes:
-        workspace = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
+        if zeroed_workspace:
+            raise ValueError("zeroed_workspace=True needs the caller's own zero-filled workspace of sufficient size")
+        workspace = torch.empty(max(ws_bytes, 32), dtype=torch.uint8, device=dev)
+    if zeroed_workspace:
+        flags |= VERIFY_ZEROED_WORKSPACE
     rc = _lib.load().aasd_verify(
         logits.data_ptr(), _dtype_code(logits), B, C, k, V, row_stride, seq_stride,
         drafts.data_ptr(), draft_len.data_ptr(), _ptr(strict), float(alpha), float(beta), flags,

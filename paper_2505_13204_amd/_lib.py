@@ -30,10 +30,12 @@ def load():
     lib.aasd_version.argtypes = []
     lib.aasd_last_error.restype = c_char_p
     lib.aasd_last_error.argtypes = []
-    lib.aasd_set_sweep_events.restype = None
-    lib.aasd_set_sweep_events.argtypes = [c_void_p, c_void_p]
-    lib.aasd_set_draw_events.restype = None
-    lib.aasd_set_draw_events.argtypes = [c_void_p, c_void_p]
+    lib.aasd_hook_sweep_events.restype = None
+    lib.aasd_hook_sweep_events.argtypes = [c_void_p, c_void_p]
+    lib.aasd_hook_draw_events.restype = None
+    lib.aasd_hook_draw_events.argtypes = [c_void_p, c_void_p]
+    lib.aasd_hook_sweep_plan.restype = c_int32
+    lib.aasd_hook_sweep_plan.argtypes = [c_int32, c_int32, c_int32]
     lib.aasd_align_sample.restype = c_int32
     lib.aasd_align_sample.argtypes = [
         c_void_p, c_int32, c_int64, c_int32, c_int64, c_void_p, c_int32, c_int32, c_int32, c_uint64, c_uint64,

@@ -9,7 +9,6 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libaasd.so")
-PROBE = os.path.join(_HERE, "hbm_probe")
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
@@ -36,11 +35,6 @@ def build(verbose: bool = True) -> str:
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)
-    # plain copy/read kernels of known size (HBM ceiling, counter scaling reference)
-    probe = [hipcc, "-O3", "-std=c++17", "--offload-arch=gfx950", "-o", PROBE, os.path.join(CSRC, "hbm_probe.hip")]
-    if verbose:
-        print(" ".join(probe), flush=True)
-    subprocess.check_call(probe)
     return LIB
 
 

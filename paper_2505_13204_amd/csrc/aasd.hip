@@ -1,6 +1,7 @@
 // C ABI of the AASD hot path: argument validation and kernel launches (see include/aasd.h).
 // Validation touches no HIP API, so every error path can be exercised without a GPU.
 #include "aasd.h"
+#include "aasd_hooks.h"
 
 #include <hip/hip_runtime.h>
 
@@ -22,8 +23,10 @@
 namespace {
 
 thread_local char g_err[512] = "";
-thread_local hipEvent_t g_sweep_start = nullptr, g_sweep_stop = nullptr;  // measurement hook
+// measurement and test hooks (aasd_hooks.h): all off unless a caller switches them on for its own thread
+thread_local hipEvent_t g_sweep_start = nullptr, g_sweep_stop = nullptr;
 thread_local hipEvent_t g_draw_start = nullptr, g_draw_stop = nullptr;
+thread_local int g_plan_block = 0, g_plan_unroll = 0, g_plan_nseg = 0;   // 0 = the library picks
 
 int fail(int code, const char* fmt, ...)
 {
@@ -43,8 +46,8 @@ size_t elt_size(int32_t dt) { return dt == AASD_F32 ? 4 : 2; }
 // within 1 % of it, at every row count, for verification (6.9 TB/s at 36864 rows against 6.7 for 1024 x 2) and
 // for alignment sampling (whose occupancy is LDS- and register-bound).  With few rows one workgroup per row
 // cannot fill the GPU (a single workgroup streams at some 15-30 GB/s), so rows are cut into segments until
-// there are several thousand workgroups.  AASD_SWEEP_CONFIG="block,unroll[,segments]" overrides the plan
-// (developer knob for tuning runs and tests).
+// there are several thousand workgroups.  aasd_hook_sweep_plan overrides the plan for the calling thread
+// (tests force every compiled shape with it; it accepts compiled shapes only).
 struct SweepPlan { int block, unroll, nseg, seg_vecs, npart; };
 
 constexpr int64_t kSplitBelowRows = 8192;
@@ -75,18 +78,45 @@ SweepPlan plan_sweep(bool align, int64_t rows, int32_t V, int32_t dt)
             ++pl.nseg;
         }
     }
-    if (const char* e = getenv("AASD_SWEEP_CONFIG")) {
-        int b = 0, u = 0, n = 0;
-        const int got = sscanf(e, "%d,%d,%d", &b, &u, &n);
-        if (got >= 2) { pl.block = b; pl.unroll = u; }
-        if (got >= 3 && n >= 1) pl.nseg = n;
-    }
+    if (g_plan_block > 0) { pl.block = g_plan_block; pl.unroll = g_plan_unroll; }
+    if (g_plan_nseg > 0) pl.nseg = g_plan_nseg;
     const int waves = pl.block / aasd::kWave > 0 ? pl.block / aasd::kWave : 1;
     if (pl.nseg * waves > aasd::kMaxPartials) pl.nseg = aasd::kMaxPartials / waves > 0 ? aasd::kMaxPartials / waves : 1;
     const int per_seg = (nvec_max + pl.nseg - 1) / pl.nseg;
     pl.seg_vecs = (per_seg + pl.block - 1) / pl.block * pl.block;
     pl.npart = pl.nseg * waves;
     return pl;
+}
+
+// Plan of the one-launch form of verification.  Its workgroups do not end with the sweep: each sends its partial
+// to memory, waits, and is counted in (about a microsecond without loads in flight).  That costs nothing while
+// all workgroups of the launch are on the GPU at once (it is paid once, at the end), so a short launch is cut into
+// at most as many workgroups as the GPU holds: 256 compute units x 7 workgroups of 256 threads.
+constexpr int64_t kFusedResident = 256 * 7;
+
+SweepPlan plan_fused(int64_t rows, int32_t V, int32_t dt)
+{
+    SweepPlan pl = plan_sweep(false, rows, V, dt);
+    if (g_plan_nseg == 0 && rows > 0 && pl.nseg > 1) {
+        const int64_t fit = kFusedResident * 256 / pl.block / rows;
+        const int nseg = (int)(fit < 1 ? 1 : (fit < pl.nseg ? fit : pl.nseg));
+        if (nseg != pl.nseg) {
+            const int per_vec = dt == AASD_BF16 ? 8 : 4;
+            const int nvec_max = V / per_vec > 0 ? V / per_vec : 1;
+            const int waves = pl.block / aasd::kWave;
+            pl.nseg = nseg;
+            pl.seg_vecs = ((nvec_max + nseg - 1) / nseg + pl.block - 1) / pl.block * pl.block;
+            pl.npart = nseg * waves;
+        }
+    }
+    return pl;
+}
+
+// the (threads, loads in flight) shapes the sweep kernels are compiled for
+bool compiled_shape(int block, int unroll)
+{
+    return (block == 256 && (unroll == 1 || unroll == 2 || unroll == 4)) || (block == 512 && (unroll == 2 || unroll == 4)) ||
+           (block == 1024 && (unroll == 1 || unroll == 2));
 }
 
 constexpr size_t kMaxChunkMaxLds = 60 * 1024;      // dynamic LDS the sweep may use for chunk maxima
@@ -118,9 +148,41 @@ int launch_sweep(const aasd::SweepParams& p, const SweepPlan& pl, int64_t rows, 
     else if (pl.block == 512 && pl.unroll == 2) e = launch_sweep_one<DT, ALIGN, COUNT, 512, 2>(p, units, dyn_lds, stream);
     else if (pl.block == 1024 && pl.unroll == 2) e = launch_sweep_one<DT, ALIGN, COUNT, 1024, 2>(p, units, dyn_lds, stream);
     else if (pl.block == 1024 && pl.unroll == 1) e = launch_sweep_one<DT, ALIGN, COUNT, 1024, 1>(p, units, dyn_lds, stream);
-    else return fail(AASD_ERR_UNSUPPORTED, "AASD_SWEEP_CONFIG=%d,%d is not a compiled launch shape", pl.block, pl.unroll);
+    else return fail(AASD_ERR_UNSUPPORTED, "sweep plan %d,%d is not a compiled launch shape", pl.block, pl.unroll);   // unreachable: plans are checked when set
     if (g_sweep_stop) (void)hipEventRecord(g_sweep_stop, stream);
     if (e != hipSuccess) return fail(AASD_ERR_LAUNCH, "row sweep launch failed: %s", hipGetErrorString(e));
+    return AASD_OK;
+}
+
+// Sweep and verification tail in one launch per chunk of units (verify_fused_kernel).
+template <int DT, int BLOCK, int U>
+hipError_t launch_fused_one(const aasd::VerifyFusedParams& p, int64_t units, hipStream_t stream)
+{
+    for (int64_t unit0 = 0; unit0 < units; unit0 += kMaxUnitsPerLaunch) {
+        const int64_t n = units - unit0 < kMaxUnitsPerLaunch ? units - unit0 : kMaxUnitsPerLaunch;
+        hipLaunchKernelGGL((aasd::verify_fused_kernel<DT, BLOCK, U>), dim3((unsigned)n), dim3(BLOCK), 0, stream, p, unit0);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+template <int DT>
+int launch_fused(const aasd::VerifyFusedParams& p, const SweepPlan& pl, int64_t rows, hipStream_t stream)
+{
+    const int64_t units = rows * pl.nseg;
+    hipError_t e;
+    if (g_sweep_start) (void)hipEventRecord(g_sweep_start, stream);
+    if (pl.block == 256 && pl.unroll == 4) e = launch_fused_one<DT, 256, 4>(p, units, stream);
+    else if (pl.block == 256 && pl.unroll == 2) e = launch_fused_one<DT, 256, 2>(p, units, stream);
+    else if (pl.block == 256 && pl.unroll == 1) e = launch_fused_one<DT, 256, 1>(p, units, stream);
+    else if (pl.block == 512 && pl.unroll == 4) e = launch_fused_one<DT, 512, 4>(p, units, stream);
+    else if (pl.block == 512 && pl.unroll == 2) e = launch_fused_one<DT, 512, 2>(p, units, stream);
+    else if (pl.block == 1024 && pl.unroll == 2) e = launch_fused_one<DT, 1024, 2>(p, units, stream);
+    else if (pl.block == 1024 && pl.unroll == 1) e = launch_fused_one<DT, 1024, 1>(p, units, stream);
+    else return fail(AASD_ERR_UNSUPPORTED, "sweep plan %d,%d is not a compiled launch shape", pl.block, pl.unroll);   // unreachable
+    if (g_sweep_stop) (void)hipEventRecord(g_sweep_stop, stream);
+    if (e != hipSuccess) return fail(AASD_ERR_LAUNCH, "verify launch failed: %s", hipGetErrorString(e));
     return AASD_OK;
 }
 
@@ -166,7 +228,7 @@ int launch_sweep_used(const aasd::SweepParams& p, const SweepPlan& pl, int64_t s
     else if (pl.block == 512 && pl.unroll == 2) e = launch_sweep_used_one<DT, 512, 2>(p, pl, sequences, stream);
     else if (pl.block == 1024 && pl.unroll == 2) e = launch_sweep_used_one<DT, 1024, 2>(p, pl, sequences, stream);
     else if (pl.block == 1024 && pl.unroll == 1) e = launch_sweep_used_one<DT, 1024, 1>(p, pl, sequences, stream);
-    else return fail(AASD_ERR_UNSUPPORTED, "AASD_SWEEP_CONFIG=%d,%d is not a compiled launch shape", pl.block, pl.unroll);
+    else return fail(AASD_ERR_UNSUPPORTED, "sweep plan %d,%d is not a compiled launch shape", pl.block, pl.unroll);   // unreachable
     if (g_sweep_stop) (void)hipEventRecord(g_sweep_stop, stream);
     if (e != hipSuccess) return fail(AASD_ERR_LAUNCH, "row sweep launch failed: %s", hipGetErrorString(e));
     return AASD_OK;
@@ -220,6 +282,96 @@ bool pool_layout(int32_t B, int32_t capacity, int32_t n_min, int32_t n_max, aasd
     return true;
 }
 
+// Workspace of aasd_verify: the arrival counters of the one-launch form (a 128-byte line each: one per sequence,
+// plus one per group when a sequence's workgroups count in groups first), then the per-wave partial results of
+// the sweep.
+int verify_groups(int64_t rows, int64_t per_seq)
+{
+    // groups pay one more dependent atomic at the end of the launch; they are worth it only where a sequence's
+    // workgroups all finish together (a short launch) and are many
+    if (rows >= kSplitBelowRows || per_seq <= 24) return 1;
+    int g = 1;
+    while ((int64_t)g * g < per_seq) ++g;   // about sqrt(per_seq) groups of about sqrt(per_seq) workgroups
+    return g;
+}
+
+size_t verify_counter_bytes(int32_t B, int ngroups)
+{
+    return (size_t)B * (size_t)(ngroups > 1 ? 1 + ngroups : 1) * aasd::kCounterWords * sizeof(unsigned);
+}
+
+int verify_check(const void* logits, int32_t dt, int32_t B, int32_t C, int32_t k, int32_t V, int64_t row_stride,
+                 int64_t seq_stride, const int32_t* drafts, const int32_t* draft_len, uint32_t flags,
+                 const int32_t* accept_len, const int32_t* best_cand, const int32_t* next_token)
+{
+    if (!valid_dtype(dt)) return fail(AASD_ERR_INVALID_ARG, "verify: unknown dtype %d", dt);
+    if (B < 0) return fail(AASD_ERR_INVALID_ARG, "verify: B = %d < 0", B);
+    if (k < 1 || k > AASD_MAX_DRAFT) return fail(AASD_ERR_INVALID_ARG, "verify: k = %d outside [1,%d]", k, AASD_MAX_DRAFT);
+    if (C < 1 || C > AASD_MAX_CANDIDATES) return fail(AASD_ERR_INVALID_ARG, "verify: C = %d outside [1,%d]", C, AASD_MAX_CANDIDATES);
+    if (V <= 0) return fail(AASD_ERR_INVALID_ARG, "verify: V = %d <= 0", V);
+    const int64_t R = 1 + (int64_t)C * k;
+    if (row_stride < V) return fail(AASD_ERR_INVALID_ARG, "verify: row_stride %lld < V %d", (long long)row_stride, V);
+    if (seq_stride < R * row_stride)
+        return fail(AASD_ERR_INVALID_ARG, "verify: seq_stride %lld < R*row_stride %lld", (long long)seq_stride, (long long)(R * row_stride));
+    if (flags & ~(AASD_VERIFY_NO_CLAMP | AASD_VERIFY_ZEROED_WORKSPACE)) return fail(AASD_ERR_INVALID_ARG, "verify: unknown flag bits 0x%x", flags);
+    if (B == 0) return AASD_OK;
+    if (!logits || !drafts || !draft_len || !accept_len || !best_cand || !next_token)
+        return fail(AASD_ERR_INVALID_ARG, "verify: null required pointer");
+    if (((uintptr_t)logits % elt_size(dt)) != 0)
+        return fail(AASD_ERR_UNSUPPORTED, "verify: logits pointer is not aligned to its element size");
+    return AASD_OK;
+}
+
+// The launches of conditional verification; every argument has been checked.  one_launch: sweep and tail in
+// one kernel (the counters are zero); otherwise the sweep and then the tail kernel (the counters are not used).
+int verify_launch(const void* logits, int32_t dt, int32_t B, int32_t C, int32_t k, int32_t V, int64_t row_stride,
+                  int64_t seq_stride, const int32_t* drafts, const int32_t* draft_len, const uint8_t* strict, float alpha,
+                  float beta, uint32_t flags, int32_t* accept_len, int32_t* best_cand, int32_t* next_token,
+                  float* row_entropy, float* row_pmax, int32_t* row_argmax, float* tok_p, float* tok_delta,
+                  uint32_t* near_count, unsigned* counters, void* partials, bool one_launch, hipStream_t s)
+{
+    const int64_t R = 1 + (int64_t)C * k;
+    const int64_t rows = (int64_t)B * R;
+    SweepPlan pl = plan_sweep(false, rows, V, dt);
+    if (one_launch) {
+        // Measured: one launch is the faster form while all its workgroups are on the GPU at once (9 rows: 8.1 us
+        // against 9.8; 288 rows: 22 against 25); a launch of several rounds of workgroups is faster in two kernels,
+        // whose streaming workgroups end as soon as their partials are on their way (8256 rows: 413 us against 397).
+        const SweepPlan pf = plan_fused(rows, V, dt);
+        if (rows * pf.nseg * (pf.block / 256) <= kFusedResident) pl = pf;
+        else one_launch = false;
+    }
+    aasd::SweepParams sp{};
+    sp.logits = logits; sp.V = V; sp.row_stride = row_stride; sp.seq_stride = seq_stride; sp.rows_per_seq = (int32_t)R;
+    sp.c = 1; sp.nseg = pl.nseg; sp.seg_vecs = pl.seg_vecs; sp.partials = (aasd::WavePartial*)partials;
+
+    aasd::VerifyTailParams tp{};
+    tp.logits = logits; tp.B = B; tp.C = C; tp.k = k; tp.V = V; tp.row_stride = row_stride; tp.seq_stride = seq_stride;
+    tp.drafts = drafts; tp.draft_len = draft_len; tp.strict = strict; tp.alpha = alpha; tp.beta = beta;
+    tp.flags = flags & AASD_VERIFY_NO_CLAMP;
+    tp.accept_len = accept_len; tp.best_cand = best_cand; tp.next_token = next_token;
+    tp.tok_p = tok_p; tp.tok_delta = tok_delta; tp.near_count = near_count;
+    tp.row_entropy = row_entropy; tp.row_pmax = row_pmax; tp.row_argmax = row_argmax;
+    tp.partials = (const aasd::WavePartial*)partials; tp.npart = pl.npart;
+
+    if (one_launch) {
+        aasd::VerifyFusedParams fp{};
+        fp.s = sp; fp.t = tp; fp.counters = counters; fp.ngroups = verify_groups(rows, R * pl.nseg);
+        fp.t.npart = pl.nseg;   // this form leaves one partial per workgroup, not per wave
+        return dt == AASD_BF16 ? launch_fused<AASD_BF16>(fp, pl, rows, s) : launch_fused<AASD_F32>(fp, pl, rows, s);
+    }
+    const int rc = dt == AASD_BF16 ? launch_sweep<AASD_BF16, false, false>(sp, pl, rows, 0, s)
+                                   : launch_sweep<AASD_F32, false, false>(sp, pl, rows, 0, s);
+    if (rc != AASD_OK) return rc;
+    if (dt == AASD_BF16)
+        hipLaunchKernelGGL(aasd::verify_tail_kernel<AASD_BF16>, dim3((unsigned)B), dim3(aasd::kTailBlock), 0, s, tp);
+    else
+        hipLaunchKernelGGL(aasd::verify_tail_kernel<AASD_F32>, dim3((unsigned)B), dim3(aasd::kTailBlock), 0, s, tp);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(AASD_ERR_LAUNCH, "verify tail launch failed: %s", hipGetErrorString(e));
+    return AASD_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -228,16 +380,35 @@ const char* aasd_version(void) { return "aasd-mi355x 0.1 (gfx950)"; }
 
 const char* aasd_last_error(void) { return g_err; }
 
-void aasd_set_sweep_events(void* start, void* stop)
+void aasd_hook_sweep_events(void* start, void* stop)
 {
     g_sweep_start = (hipEvent_t)start;
     g_sweep_stop = (hipEvent_t)stop;
 }
 
-void aasd_set_draw_events(void* start, void* stop)
+void aasd_hook_draw_events(void* start, void* stop)
 {
     g_draw_start = (hipEvent_t)start;
     g_draw_stop = (hipEvent_t)stop;
+}
+
+int aasd_hook_sweep_plan(int32_t threads, int32_t loads, int32_t segments)
+{
+    if (threads == 0 && loads == 0 && segments == 0) {
+        g_plan_block = g_plan_unroll = g_plan_nseg = 0;
+        return AASD_OK;
+    }
+    if (threads == 0 && loads == 0) {   // segments only
+        if (segments < 1 || segments > 16) return fail(AASD_ERR_INVALID_ARG, "sweep plan: segments = %d outside [1,16]", segments);
+        g_plan_block = g_plan_unroll = 0;
+        g_plan_nseg = segments;
+        return AASD_OK;
+    }
+    if (!compiled_shape(threads, loads))
+        return fail(AASD_ERR_UNSUPPORTED, "sweep plan: %d threads x %d loads is not a compiled launch shape", threads, loads);
+    if (segments < 0 || segments > 16) return fail(AASD_ERR_INVALID_ARG, "sweep plan: segments = %d outside [0,16]", segments);
+    g_plan_block = threads; g_plan_unroll = loads; g_plan_nseg = segments;
+    return AASD_OK;
 }
 
 size_t aasd_align_sample_workspace_bytes(int64_t rows, int32_t V, int32_t dt)
@@ -421,8 +592,9 @@ size_t aasd_verify_workspace_bytes(int32_t B, int32_t C, int32_t k, int32_t V, i
 {
     if (B < 0 || C < 1 || C > AASD_MAX_CANDIDATES || k < 1 || k > AASD_MAX_DRAFT || V <= 0 || !valid_dtype(dt)) return 0;
     const int64_t rows = (int64_t)B * (1 + C * k);
-    const SweepPlan pl = plan_sweep(false, rows, V, dt);
-    return (size_t)rows * pl.npart * sizeof(aasd::WavePartial);
+    const SweepPlan pl = plan_sweep(false, rows, V, dt);   // the two-launch form needs the most partials (one per wave)
+    const SweepPlan pf = plan_fused(rows, V, dt);
+    return verify_counter_bytes(B, verify_groups(rows, (int64_t)(1 + C * k) * pf.nseg)) + (size_t)rows * pl.npart * sizeof(aasd::WavePartial);
 }
 
 int aasd_verify(const void* logits, int32_t dt, int32_t B, int32_t C, int32_t k, int32_t V,
@@ -433,50 +605,18 @@ int aasd_verify(const void* logits, int32_t dt, int32_t B, int32_t C, int32_t k,
                 float* tok_delta, uint32_t* near_count, void* workspace, size_t workspace_bytes,
                 void* stream)
 {
-    if (!valid_dtype(dt)) return fail(AASD_ERR_INVALID_ARG, "verify: unknown dtype %d", dt);
-    if (B < 0) return fail(AASD_ERR_INVALID_ARG, "verify: B = %d < 0", B);
-    if (k < 1 || k > AASD_MAX_DRAFT) return fail(AASD_ERR_INVALID_ARG, "verify: k = %d outside [1,%d]", k, AASD_MAX_DRAFT);
-    if (C < 1 || C > AASD_MAX_CANDIDATES) return fail(AASD_ERR_INVALID_ARG, "verify: C = %d outside [1,%d]", C, AASD_MAX_CANDIDATES);
-    if (V <= 0) return fail(AASD_ERR_INVALID_ARG, "verify: V = %d <= 0", V);
-    const int64_t R = 1 + (int64_t)C * k;
-    if (row_stride < V) return fail(AASD_ERR_INVALID_ARG, "verify: row_stride %lld < V %d", (long long)row_stride, V);
-    if (seq_stride < R * row_stride)
-        return fail(AASD_ERR_INVALID_ARG, "verify: seq_stride %lld < R*row_stride %lld", (long long)seq_stride, (long long)(R * row_stride));
-    if (flags & ~AASD_VERIFY_NO_CLAMP) return fail(AASD_ERR_INVALID_ARG, "verify: unknown flag bits 0x%x", flags);
-    if (B == 0) return AASD_OK;
-    if (!logits || !drafts || !draft_len || !accept_len || !best_cand || !next_token)
-        return fail(AASD_ERR_INVALID_ARG, "verify: null required pointer");
-    if (((uintptr_t)logits % elt_size(dt)) != 0)
-        return fail(AASD_ERR_UNSUPPORTED, "verify: logits pointer is not aligned to its element size");
+    const int rc = verify_check(logits, dt, B, C, k, V, row_stride, seq_stride, drafts, draft_len, flags, accept_len,
+                                best_cand, next_token);
+    if (rc != AASD_OK || B == 0) return rc;
     const size_t need = aasd_verify_workspace_bytes(B, C, k, V, dt);
     if (!workspace || workspace_bytes < need)
         return fail(AASD_ERR_WORKSPACE, "verify: workspace of %zu bytes needed, %zu given", need, workspace ? workspace_bytes : (size_t)0);
-    if (((uintptr_t)workspace % 16) != 0) return fail(AASD_ERR_WORKSPACE, "verify: workspace is not 16-byte aligned");
-
-    hipStream_t s = (hipStream_t)stream;
-    const int64_t rows = (int64_t)B * R;
-    const SweepPlan pl = plan_sweep(false, rows, V, dt);
-    aasd::SweepParams sp{};
-    sp.logits = logits; sp.V = V; sp.row_stride = row_stride; sp.seq_stride = seq_stride; sp.rows_per_seq = (int32_t)R;
-    sp.c = 1; sp.nseg = pl.nseg; sp.seg_vecs = pl.seg_vecs; sp.partials = (aasd::WavePartial*)workspace;
-    int rc = dt == AASD_BF16 ? launch_sweep<AASD_BF16, false, false>(sp, pl, rows, 0, s)
-                             : launch_sweep<AASD_F32, false, false>(sp, pl, rows, 0, s);
-    if (rc != AASD_OK) return rc;
-
-    aasd::VerifyTailParams tp{};
-    tp.logits = logits; tp.B = B; tp.C = C; tp.k = k; tp.V = V; tp.row_stride = row_stride; tp.seq_stride = seq_stride;
-    tp.drafts = drafts; tp.draft_len = draft_len; tp.strict = strict; tp.alpha = alpha; tp.beta = beta; tp.flags = flags;
-    tp.accept_len = accept_len; tp.best_cand = best_cand; tp.next_token = next_token;
-    tp.tok_p = tok_p; tp.tok_delta = tok_delta; tp.near_count = near_count;
-    tp.row_entropy = row_entropy; tp.row_pmax = row_pmax; tp.row_argmax = row_argmax;
-    tp.partials = (const aasd::WavePartial*)workspace; tp.npart = pl.npart;
-    if (dt == AASD_BF16)
-        hipLaunchKernelGGL(aasd::verify_tail_kernel<AASD_BF16>, dim3((unsigned)B), dim3(aasd::kTailBlock), 0, s, tp);
-    else
-        hipLaunchKernelGGL(aasd::verify_tail_kernel<AASD_F32>, dim3((unsigned)B), dim3(aasd::kTailBlock), 0, s, tp);
-    const hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return fail(AASD_ERR_LAUNCH, "verify tail launch failed: %s", hipGetErrorString(e));
-    return AASD_OK;
+    if (((uintptr_t)workspace % 128) != 0) return fail(AASD_ERR_WORKSPACE, "verify: workspace is not 128-byte aligned");
+    const size_t partial_bytes = (size_t)B * (1 + C * k) * plan_sweep(false, (int64_t)B * (1 + C * k), V, dt).npart * sizeof(aasd::WavePartial);
+    return verify_launch(logits, dt, B, C, k, V, row_stride, seq_stride, drafts, draft_len, strict, alpha, beta, flags,
+                         accept_len, best_cand, next_token, row_entropy, row_pmax, row_argmax, tok_p, tok_delta,
+                         near_count, (unsigned*)workspace, (char*)workspace + (need - partial_bytes),
+                         (flags & AASD_VERIFY_ZEROED_WORKSPACE) != 0, (hipStream_t)stream);
 }
 
 size_t aasd_pool_bytes(int32_t B, int32_t capacity, int32_t n_min, int32_t n_max)

@@ -90,6 +90,13 @@ __device__ __forceinline__ void wave_best(float& z, int& i)
     }
 }
 
+// Plain fill of n 32-bit words (used where a memset node must not enter a captured graph).
+__global__ __launch_bounds__(256) void fill_u32_kernel(unsigned* dst, unsigned value, int n)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n) dst[i] = value;
+}
+
 // Philox4x32 with 10 rounds (Salmon et al., SC'11): counter-based, integer only.
 __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
                                               uint32_t k0, uint32_t k1, uint32_t (&out)[4])

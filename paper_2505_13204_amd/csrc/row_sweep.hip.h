@@ -39,12 +39,35 @@ struct WavePartial {
     float m;       // largest logit of the wave's share (-inf: the share was empty)
     float S;       // sum of e^(z - m) over the share
     float T;       // sum of log2(e^(z - m)) * e^(z - m)  (log2 units, <= 0)
-    int code;      // index of the first element of the chunk that holds the first maximum
+    int code;      // index of the first element of the chunk that holds the first maximum (EXACT sweeps: of that maximum itself)
     unsigned cnt;  // elements with z > z_next
     int nlist;     // chunks listed for this wave (they hold every token of its share that can be in the row's top-c)
     float thr2;    // a lower bound on the c-th largest logit of the wave's share
     int pad;
 };
+
+// A partial that another workgroup of the SAME launch will read (one-launch verification) goes to memory and
+// comes from memory word by word with device-scope atomic accesses: these pass through the caches that are
+// private to a compute unit or to one of the GPU's dies, where a plain store could linger and a plain load
+// could hit a stale line.  (A device-scope fence would do as well, but it writes back and invalidates the
+// whole die-level cache each time, which costs microseconds per workgroup.)
+__device__ __forceinline__ void store_partial_coherent(WavePartial* out, const WavePartial& wp)
+{
+    static_assert(sizeof(WavePartial) == 32, "WavePartial is four 64-bit words");
+    const uint64_t* src = reinterpret_cast<const uint64_t*>(&wp);
+    uint64_t* dst = reinterpret_cast<uint64_t*>(out);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) __hip_atomic_store(dst + i, src[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ WavePartial load_partial_coherent(const WavePartial* in)
+{
+    WavePartial wp;
+    uint64_t* dst = reinterpret_cast<uint64_t*>(&wp);
+    const uint64_t* src = reinterpret_cast<const uint64_t*>(in);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) dst[i] = __hip_atomic_load(src + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return wp;
+}
 
 constexpr int kMaxPartials = 64;   // partials per row (segments x waves): one lane each in the finish kernel
 constexpr int kListCap = 48;       // chunk positions a wave may list
@@ -93,14 +116,25 @@ __device__ __forceinline__ void lane_acc_init(LaneAcc& a)
 // Fold N consecutive elements (first index idx0) into the lane state.
 // CLAMP: exponents are floored at a finite value so that -inf logits contribute exactly zero.
 // COUNT: count elements above zcmp.  UNIFORM: all 64 lanes are active (ballot counting).
-template <int N, bool CLAMP, bool COUNT, bool UNIFORM, bool SECOND>
+// EXACT: a.code is the index of the first element that attains the lane's maximum, not just of its chunk
+// (a few more instructions per chunk: used where the greedy pick must come out of the partials alone).
+template <int N, bool CLAMP, bool COUNT, bool UNIFORM, bool SECOND, bool EXACT = false>
 __device__ __forceinline__ float accumulate(LaneAcc& a, const float (&z)[N], int idx0, float zcmp)
 {
     float cmax = z[0];
 #pragma unroll
     for (int e = 1; e < N; ++e) cmax = fmaxf(cmax, z[e]);
     if (SECOND) a.v2 = fmaxf(a.v2, fminf(cmax, a.vmax));   // the smaller of the new maximum and the old one
-    a.code = cmax > a.vmax ? idx0 : a.code;
+    if (EXACT) {
+        if (cmax > a.vmax) {
+            int off = 0;
+#pragma unroll
+            for (int e = N - 1; e >= 0; --e) off = z[e] == cmax ? e : off;
+            a.code = idx0 + off;
+        }
+    } else {
+        a.code = cmax > a.vmax ? idx0 : a.code;
+    }
     a.vmax = fmaxf(a.vmax, cmax);
     if (cmax > a.rlim) {  // rare: first chunk of the lane, or a jump of more than kRefSlack nats
         float nr2 = cmax * kLog2e;
@@ -214,7 +248,7 @@ __device__ __forceinline__ void cm_store_batch(unsigned char* cm_lane, int j0, c
 
 // The single HBM pass of one lane over its share of the row: vectors tid, tid+BLOCK, ...
 // loaded U at a time with the next batch in flight while the current one is folded in.
-template <int DT, bool CLAMP, bool COUNT, bool SECOND, int BLOCK, int U>
+template <int DT, bool CLAMP, bool COUNT, bool SECOND, int BLOCK, int U, bool EXACT = false>
 __device__ __forceinline__ void sweep_lane(LaneAcc& a, const SegShape& rs, int tid, float zcmp,
                                            bool store_cm, unsigned char* cm_lane)
 {
@@ -223,7 +257,7 @@ __device__ __forceinline__ void sweep_lane(LaneAcc& a, const SegShape& rs, int t
 
     if (tid < rs.head_n) {
         const float z1[1] = {load_elt<DT>(rs.base, tid)};
-        accumulate<1, CLAMP, COUNT, false, SECOND>(a, z1, tid, zcmp);
+        accumulate<1, CLAMP, COUNT, false, SECOND, EXACT>(a, z1, tid, zcmp);
     }
 
     // Full batches of BLOCK*U vectors.  Two register buffers alternate: while one batch is folded
@@ -247,7 +281,7 @@ __device__ __forceinline__ void sweep_lane(LaneAcc& a, const SegShape& rs, int t
             float z[EPV];
             unpack<DT>(buf[u], z);
             const int vec = (it * U + u) * BLOCK + tid;
-            cmax[u] = accumulate<EPV, CLAMP, COUNT, true, SECOND>(a, z, rs.first_idx + vec * EPV, zcmp);
+            cmax[u] = accumulate<EPV, CLAMP, COUNT, true, SECOND, EXACT>(a, z, rs.first_idx + vec * EPV, zcmp);
         }
         if (store_cm) cm_store_batch<DT, U>(cm_lane, it * U, cmax);
     };
@@ -274,7 +308,7 @@ __device__ __forceinline__ void sweep_lane(LaneAcc& a, const SegShape& rs, int t
             if (vec < rs.nvec) {
                 float z[EPV];
                 unpack<DT>(rem[u], z);
-                const float cmax = accumulate<EPV, CLAMP, COUNT, false, SECOND>(a, z, rs.first_idx + vec * EPV, zcmp);
+                const float cmax = accumulate<EPV, CLAMP, COUNT, false, SECOND, EXACT>(a, z, rs.first_idx + vec * EPV, zcmp);
                 if (store_cm) cm_store<DT>(cm_lane, nsuper * U + u, cmax);
             }
         }
@@ -282,7 +316,7 @@ __device__ __forceinline__ void sweep_lane(LaneAcc& a, const SegShape& rs, int t
     if (tid < rs.tail_n) {
         const int idx = rs.tail0 + tid;
         const float z1[1] = {load_elt<DT>(rs.base, idx)};
-        accumulate<1, CLAMP, COUNT, false, SECOND>(a, z1, idx, zcmp);
+        accumulate<1, CLAMP, COUNT, false, SECOND, EXACT>(a, z1, idx, zcmp);
     }
 }
 
@@ -364,7 +398,7 @@ struct SweepShared {
 
 // One attempt of a wave at its share.  Returns false (in every lane) if the sums came out
 // non-finite, which happens when the share holds -inf logits; the caller repeats with CLAMP.
-template <int DT, bool ALIGN, bool COUNT, bool CLAMP, int BLOCK, int U>
+template <int DT, bool ALIGN, bool COUNT, bool CLAMP, int BLOCK, int U, bool COHERENT, bool EXACT>
 __device__ __forceinline__ bool process_wave(const SweepParams& p, const SegShape& rs, bool has_next, float znext,
                                              SweepShared<BLOCK / kWave>& sh, unsigned char* cm_lane, const RowShape& row_s,
                                              WavePartial* out, int32_t* out_list)
@@ -375,7 +409,7 @@ __device__ __forceinline__ bool process_wave(const SweepParams& p, const SegShap
     const float zcmp = has_next ? znext : INFINITY;
 
     LaneAcc a;
-    sweep_lane<DT, CLAMP, ALIGN && COUNT, ALIGN, BLOCK, U>(a, rs, tid, zcmp, want_cand && p.cm_enabled, cm_lane);
+    sweep_lane<DT, CLAMP, ALIGN && COUNT, ALIGN, BLOCK, U, EXACT>(a, rs, tid, zcmp, want_cand && p.cm_enabled, cm_lane);
 
     // ---- wave maximum, and a lower bound on the c-th largest logit of the wave's share ----
     float G = a.vmax;  // becomes the maximum of this lane's 4-lane group
@@ -494,15 +528,20 @@ __device__ __forceinline__ bool process_wave(const SweepParams& p, const SegShap
     if (lane == 0) {
         WavePartial wp;
         wp.m = m; wp.S = S; wp.T = T; wp.code = code; wp.cnt = cnt; wp.nlist = nlist; wp.thr2 = thr2; wp.pad = 0;
-        *out = wp;
+        if (COHERENT) store_partial_coherent(out, wp);
+        else *out = wp;
     }
     return true;
 }
 
 // One unit of work: segment `seg` of row `row`; every wave writes one WavePartial.
-template <int DT, bool ALIGN, bool COUNT, int BLOCK, int U>
+// COHERENT: the partial is written for a reader in another workgroup of the same launch.
+// EXACT: the partial's `code` is the index of the share's first maximum itself (verification only).
+// local_out: if given (an array of one WavePartial per wave, in LDS), the waves leave their partials there and
+// nothing goes to the workspace: the caller merges them.
+template <int DT, bool ALIGN, bool COUNT, int BLOCK, int U, bool COHERENT = false, bool EXACT = false>
 __device__ __forceinline__ void sweep_unit(const SweepParams& p, int64_t row, int seg, SweepShared<BLOCK / kWave>& sh,
-                                           unsigned char* cm)
+                                           unsigned char* cm, WavePartial* local_out = nullptr)
 {
     constexpr int NW = BLOCK / kWave;
     const int64_t off = (row / p.rows_per_seq) * p.seq_stride + (row % p.rows_per_seq) * p.row_stride;
@@ -511,7 +550,7 @@ __device__ __forceinline__ void sweep_unit(const SweepParams& p, int64_t row, in
     const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
 
     const int64_t slot = (row * p.nseg + seg) * NW + wid;
-    WavePartial* out = p.partials + slot;
+    WavePartial* out = local_out ? local_out + wid : p.partials + slot;
     int32_t* out_list = ALIGN ? p.lists + slot * kListCap : nullptr;
 
     // a wave whose lanes own no element at all leaves the neutral partial
@@ -520,7 +559,8 @@ __device__ __forceinline__ void sweep_unit(const SweepParams& p, int64_t row, in
         if (lane == 0) {
             WavePartial wp;
             wp.m = -INFINITY; wp.S = 0.f; wp.T = 0.f; wp.code = 0x7fffffff; wp.cnt = 0; wp.nlist = 0; wp.thr2 = -INFINITY; wp.pad = 0;
-            *out = wp;
+            if (COHERENT) store_partial_coherent(out, wp);
+            else *out = wp;
         }
         return;
     }
@@ -535,8 +575,9 @@ __device__ __forceinline__ void sweep_unit(const SweepParams& p, int64_t row, in
     }
     const bool has_next = ALIGN && (nt >= 0 || p.cand_all);
     unsigned char* cm_lane = cm + (size_t)tid * (size_t)p.cm_stride;
-    if (!process_wave<DT, ALIGN, COUNT, false, BLOCK, U>(p, rs, has_next, znext, sh, cm_lane, row_s, out, out_list))
-        process_wave<DT, ALIGN, COUNT, true, BLOCK, U>(p, rs, has_next, znext, sh, cm_lane, row_s, out, out_list);
+    static_assert(!(EXACT && ALIGN), "the alignment sweep lists chunks by their first element");
+    if (!process_wave<DT, ALIGN, COUNT, false, BLOCK, U, COHERENT, EXACT>(p, rs, has_next, znext, sh, cm_lane, row_s, out, out_list))
+        process_wave<DT, ALIGN, COUNT, true, BLOCK, U, COHERENT, EXACT>(p, rs, has_next, znext, sh, cm_lane, row_s, out, out_list);
 }
 
 // Streaming kernel: grid = rows x segments.

@@ -2,10 +2,14 @@
 //
 // One workgroup per sequence.  First the wave partials that the sweep left in the workspace
 // are merged per row (maximum, sum of exponentials, entropy, greedy pick), a group of lanes per
-// row, into LDS.  Then, with 16 lanes per candidate (k <= 16 draft tokens), four
-// candidates per wave and up to 32 candidates per workgroup, each lane decides its token; a wave
+// row, into LDS.  Then, with 16 lanes per candidate (k <= 16 draft tokens) and four
+// candidates per wave, each lane decides its token; a wave
 // ballot turns the decisions of a candidate into a bit field whose trailing ones are the
 // accepted prefix (the cascade rule of Sec. 2.1); one thread then takes the longest candidate.
+//
+// The same work exists in two launch forms: as a kernel of its own after the sweep
+// (verify_tail_kernel), and inside the sweep kernel (verify_fused_kernel), where the workgroup
+// that is the last to finish a row segment of a sequence does that sequence's tail.
 #pragma once
 
 #include "row_finish.hip.h"
@@ -38,24 +42,80 @@ struct VerifyTailParams {
 
 constexpr int kMaxVerifyRows = 1 + AASD_MAX_CANDIDATES * AASD_MAX_DRAFT;  // 513
 
-template <int DT>
-__global__ __launch_bounds__(kTailBlock) void verify_tail_kernel(VerifyTailParams p)
-{
-    __shared__ int lead[AASD_MAX_CANDIDATES];
-    __shared__ unsigned near_c[AASD_MAX_CANDIDATES];
-    __shared__ float4 stats[kMaxVerifyRows];  // per row {max logit, S, H, bits of argmax}
+struct TailShared {
+    int lead[AASD_MAX_CANDIDATES];
+    unsigned near_c[AASD_MAX_CANDIDATES];
+    float4 stats[kMaxVerifyRows];  // per row {max logit, S, H, bits of argmax}
+};
 
-    const int b = blockIdx.x;
+// What a thread needs of the drafts before it can decide its tokens: none of it depends on the row statistics.
+template <int NT>
+struct TailInputs {
+    static constexpr int kCandPerPass = NT / 16;   // 16 lanes per candidate
+    static constexpr int kPasses = (AASD_MAX_CANDIDATES + kCandPerPass - 1) / kCandPerPass;
+    int dl[kPasses], tok[kPasses];
+    float zt[kPasses];     // logit of the draft token in the row that verifies it
+    bool strict[kPasses];
+};
+
+// Loads the draft lengths, tokens and flags of sequence b.
+template <int NT>
+__device__ __forceinline__ void tail_load_drafts(const VerifyTailParams& p, int b, TailInputs<NT>& in)
+{
+    const int tid = threadIdx.x, j = tid & 15;  // j: 0-based position in the draft
+    const int C = p.C, k = p.k;
+#pragma unroll
+    for (int ps = 0; ps < TailInputs<NT>::kPasses; ++ps) {
+        const int cand = ps * TailInputs<NT>::kCandPerPass + (tid >> 4);
+        int dl = 0;
+        if (cand < C) {
+            dl = p.draft_len[(size_t)b * C + cand];
+            dl = dl < 0 ? 0 : (dl > k ? k : dl);
+        }
+        in.dl[ps] = dl;
+        in.tok[ps] = -1; in.zt[ps] = 0.f; in.strict[ps] = false;
+        if (cand < C && j < k) {   // every slot of the candidate, whatever its length: the loads need not wait for draft_len
+            const size_t idx = ((size_t)b * C + cand) * k + j;
+            in.tok[ps] = p.drafts[idx];
+            in.strict[ps] = p.strict != nullptr && p.strict[idx] != 0;
+        }
+    }
+}
+
+// Loads the logit of every draft token in the row that verifies it (needs the tokens).
+template <int DT, int NT>
+__device__ __forceinline__ void tail_load_logits(const VerifyTailParams& p, int b, TailInputs<NT>& in)
+{
+    const int tid = threadIdx.x, j = tid & 15;
+#pragma unroll
+    for (int ps = 0; ps < TailInputs<NT>::kPasses; ++ps) {
+        const int cand = ps * TailInputs<NT>::kCandPerPass + (tid >> 4);
+        const int t = in.tok[ps];
+        if (cand < p.C && j < p.k && t >= 0 && t < p.V) {
+            const int rho = (j == 0) ? 0 : 1 + cand * p.k + (j - 1);  // the row that follows the previous token
+            in.zt[ps] = load_elt<DT>(p.logits, (int64_t)b * p.seq_stride + (int64_t)rho * p.row_stride + t);
+        }
+    }
+}
+
+// The tail of sequence b, run by all NT threads of a workgroup (NT a multiple of 64).
+// COHERENT: the partials were written by other workgroups of this same launch (see store_partial_coherent).
+// EXACT: the partials name the first maximum of their share itself, so the greedy pick needs no second look at the row.
+template <int DT, int NT, bool COHERENT, bool EXACT>
+__device__ __forceinline__ void verify_tail_block(const VerifyTailParams& p, int b, const TailInputs<NT>& in, TailShared& sh)
+{
+    constexpr int kCandPerPass = TailInputs<NT>::kCandPerPass;
+    constexpr int kPasses = TailInputs<NT>::kPasses;
     const int tid = threadIdx.x, lane = tid & 63;
-    const int cand = tid >> 4, j = tid & 15;  // j: 0-based position in the draft
+    const int j = tid & 15;
     const int C = p.C, k = p.k, R = 1 + C * k;
 
     // ---- statistics of the sequence's rows from the sweep's partials ----
-    // G lanes per row (G = npart rounded up to a power of two), 64/G rows per wave at a time
+    // G lanes per row (G = npart rounded up to a power of two), NT/G rows at a time
     {
         int G = 1;
         while (G < p.npart) G <<= 1;
-        const int rows_per_pass = kTailBlock / G;
+        const int rows_per_pass = NT / G;
         const int sub = tid / G, s = tid - sub * G;  // row slot of this lane, partial index within the row
         for (int r0 = 0; r0 < R; r0 += rows_per_pass) {
             const int r = r0 + sub;
@@ -63,7 +123,10 @@ __global__ __launch_bounds__(kTailBlock) void verify_tail_kernel(VerifyTailParam
             const int64_t row = (int64_t)b * R + (have_row ? r : 0);
             WavePartial wp;
             wp.m = -INFINITY; wp.S = 0.f; wp.T = 0.f; wp.code = 0x7fffffff;
-            if (have_row && s < p.npart) wp = p.partials[row * p.npart + s];
+            if (have_row && s < p.npart) {
+                if (COHERENT) wp = load_partial_coherent(p.partials + row * p.npart + s);
+                else wp = p.partials[row * p.npart + s];
+            }
             float m = wp.m;
             for (int o = 1; o < G; o <<= 1) m = fmaxf(m, __shfl_xor(m, o));
             const bool live = wp.S > 0.f;
@@ -78,16 +141,18 @@ __global__ __launch_bounds__(kTailBlock) void verify_tail_kernel(VerifyTailParam
                 code = min(code, __shfl_xor(code, o));
             }
             if (have_row && s == 0) {
-                const RowShape rs = row_shape<DT>(p.logits, (int64_t)b * p.seq_stride + (int64_t)r * p.row_stride, p.V);
                 int am = 0;
                 if ((unsigned)code < (unsigned)p.V) {
                     am = code;
-                    const int len = (code >= rs.head && code < rs.tail0) ? Elt<DT>::kPerVec : 1;
-                    for (int e = 0; e < len; ++e)
-                        if (load_elt<DT>(rs.base, code + e) == m) { am = code + e; break; }
+                    if (!EXACT) {
+                        const RowShape rs = row_shape<DT>(p.logits, (int64_t)b * p.seq_stride + (int64_t)r * p.row_stride, p.V);
+                        const int len = (code >= rs.head && code < rs.tail0) ? Elt<DT>::kPerVec : 1;
+                        for (int e = 0; e < len; ++e)
+                            if (load_elt<DT>(rs.base, code + e) == m) { am = code + e; break; }
+                    }
                 }
                 const float H = entropy_from_sums(S, T2);
-                stats[r] = make_float4(m, S, H, __int_as_float(am));
+                sh.stats[r] = make_float4(m, S, H, __int_as_float(am));
                 if (p.row_entropy) p.row_entropy[row] = H;
                 if (p.row_pmax) p.row_pmax[row] = 1.0f / S;
                 if (p.row_argmax) p.row_argmax[row] = am;
@@ -96,71 +161,180 @@ __global__ __launch_bounds__(kTailBlock) void verify_tail_kernel(VerifyTailParam
     }
     __syncthreads();
 
-    int dl = 0;
-    if (cand < C) {
-        dl = p.draft_len[(size_t)b * C + cand];
-        dl = dl < 0 ? 0 : (dl > k ? k : dl);
-    }
-    const bool slot = cand < C && j < k;
-    const bool in = slot && j < dl;
-    const size_t idx = ((size_t)b * C + (cand < C ? cand : 0)) * k + (j < k ? j : 0);
+#pragma unroll
+    for (int ps = 0; ps < kPasses; ++ps) {
+        const int cand = ps * kCandPerPass + (tid >> 4);
+        if (ps * kCandPerPass >= C) break;   // the same in every thread
+        const int dl = in.dl[ps];
+        const bool slot = cand < C && j < k;
+        const bool inside = slot && j < dl;
+        const size_t idx = ((size_t)b * C + (cand < C ? cand : 0)) * k + (j < k ? j : 0);
 
-    bool pass = false, near = false;
-    float pf = 0.f, df = 0.f;
-    if (in) {
-        const int rho = (j == 0) ? 0 : 1 + cand * k + (j - 1);  // the row that follows the previous token
-        const int t = p.drafts[idx];
-        const float4 st = stats[rho];
-        const double m = (double)st.x, S = (double)st.y, H = (double)st.z;
-        const bool valid = t >= 0 && t < p.V;
-        float zt = 0.f;
-        if (valid) zt = load_elt<DT>(p.logits, (int64_t)b * p.seq_stride + (int64_t)rho * p.row_stride + t);
-        const double pr = valid ? exp((double)zt - m) / S : 0.0;
-        const double Delta = 1.0 / S;                                // Eq. 6
-        const double thr = (double)p.alpha * H + (double)p.beta;     // Eq. 5
-        double delta;
-        if (p.flags & AASD_VERIFY_NO_CLAMP) {
-            delta = thr;
-            pass = valid && pr >= delta;
-        } else {
-            const bool is_strict = p.strict != nullptr && p.strict[idx] != 0;
-            delta = is_strict ? Delta : fmin(thr, Delta);
-            pass = valid && (pr >= delta || zt == st.x);             // Eq. 4; ties with the maximum pass
+        bool pass = false, near = false;
+        float pf = 0.f, df = 0.f;
+        if (inside) {
+            const int rho = (j == 0) ? 0 : 1 + cand * k + (j - 1);
+            const int t = in.tok[ps];
+            const float4 st = sh.stats[rho];
+            const double m = (double)st.x, S = (double)st.y, H = (double)st.z;
+            const bool valid = t >= 0 && t < p.V;
+            const float zt = in.zt[ps];
+            const double pr = valid ? exp((double)zt - m) / S : 0.0;
+            const double Delta = 1.0 / S;                                // Eq. 6
+            const double thr = (double)p.alpha * H + (double)p.beta;     // Eq. 5
+            double delta;
+            if (p.flags & AASD_VERIFY_NO_CLAMP) {
+                delta = thr;
+                pass = valid && pr >= delta;
+            } else {
+                delta = in.strict[ps] ? Delta : fmin(thr, Delta);
+                pass = valid && (pr >= delta || zt == st.x);             // Eq. 4; ties with the maximum pass
+            }
+            near = fabs(pr - delta) < 1e-6;
+            pf = (float)pr;
+            df = (float)delta;
         }
-        near = fabs(pr - delta) < 1e-6;
-        pf = (float)pr;
-        df = (float)delta;
-    }
-    if (slot) {
-        if (p.tok_p) p.tok_p[idx] = pf;
-        if (p.tok_delta) p.tok_delta[idx] = df;
-    }
+        if (slot) {
+            if (p.tok_p) p.tok_p[idx] = pf;
+            if (p.tok_delta) p.tok_delta[idx] = df;
+        }
 
-    // accept-prefix: trailing ones of the candidate's 16-bit field
-    const unsigned shift = (unsigned)(lane >> 4) * 16u;
-    const unsigned field = (unsigned)((__ballot(pass) >> shift) & 0xffffull);
-    const unsigned nfield = (unsigned)((__ballot(near && in) >> shift) & 0xffffull);
-    const int a = __ffs(~field) - 1;  // bit 16 of ~field is always set, so a <= 16; a <= dl because bit dl is clear
-    if (j == 0 && cand < C) {
-        lead[cand] = a;
-        // evaluated tokens: the accepted ones and the first failure
-        const unsigned ev = (a + 1 >= 32) ? 0xffffffffu : ((1u << (a + 1)) - 1u);
-        near_c[cand] = (unsigned)__popc(nfield & ev);
+        // accept-prefix: trailing ones of the candidate's 16-bit field
+        const unsigned shift = (unsigned)(lane >> 4) * 16u;
+        const unsigned field = (unsigned)((__ballot(pass) >> shift) & 0xffffull);
+        const unsigned nfield = (unsigned)((__ballot(near && inside) >> shift) & 0xffffull);
+        const int a = __ffs(~field) - 1;  // bit 16 of ~field is always set, so a <= 16; a <= dl because bit dl is clear
+        if (j == 0 && cand < C) {
+            sh.lead[cand] = a;
+            // evaluated tokens: the accepted ones and the first failure
+            const unsigned ev = (a + 1 >= 32) ? 0xffffffffu : ((1u << (a + 1)) - 1u);
+            sh.near_c[cand] = (unsigned)__popc(nfield & ev);
+        }
     }
     __syncthreads();
     if (tid == 0) {
         int best_a = 0, best_c = 0;
         unsigned near_total = 0;
         for (int c = 0; c < C; ++c) {
-            if (lead[c] > best_a) { best_a = lead[c]; best_c = c; }  // lowest index on ties
-            near_total += near_c[c];
+            if (sh.lead[c] > best_a) { best_a = sh.lead[c]; best_c = c; }  // lowest index on ties
+            near_total += sh.near_c[c];
         }
         const int rho = best_a == 0 ? 0 : 1 + best_c * k + (best_a - 1);
         p.accept_len[b] = best_a;
         p.best_cand[b] = best_c;
-        p.next_token[b] = __float_as_int(stats[rho].w);
+        p.next_token[b] = __float_as_int(sh.stats[rho].w);
         if (p.near_count) p.near_count[b] = near_total;
     }
+}
+
+template <int DT>
+__global__ __launch_bounds__(kTailBlock) void verify_tail_kernel(VerifyTailParams p)
+{
+    __shared__ TailShared sh;
+    TailInputs<kTailBlock> in;
+    tail_load_drafts<kTailBlock>(p, blockIdx.x, in);
+    tail_load_logits<DT, kTailBlock>(p, blockIdx.x, in);
+    verify_tail_block<DT, kTailBlock, false, false>(p, blockIdx.x, in, sh);
+}
+
+// Sweep and tail in one launch.  Grid = rows x segments as for row_sweep_kernel.
+//
+// Every sequence has a counter, zero before the launch.  A workgroup whose waves have written their
+// partials (with stores that go to memory, and waited until memory has them) adds one to its sequence's
+// counter; the workgroup that brings it to rows_per_seq * nseg knows that every partial of the sequence
+// is in memory, puts the counter back to zero and does the sequence's tail.  No workgroup waits for
+// another, so the launch cannot stall however its workgroups are scheduled.
+// Additions to ONE address are served one after the other (some tens of nanoseconds each), and the
+// workgroups of a short launch all finish at about the same time; so when a sequence has many workgroups
+// they first count in `ngroups` group counters (workgroup u of the sequence in group u mod ngroups), and
+// only the last of each group adds to the sequence's counter.  Every counter has a 128-byte line of its
+// own: counters that share a line are served one after the other like a single one.
+constexpr int kCounterWords = 32;   // 128 bytes
+
+struct VerifyFusedParams {
+    SweepParams s;
+    VerifyTailParams t;
+    unsigned* counters;   // [B][1 + (ngroups > 1 ? ngroups : 0)][kCounterWords]
+    int32_t ngroups;      // 1: the sequence's counter alone
+};
+
+__device__ __forceinline__ bool arrive_is_last(unsigned* counter, unsigned expected)
+{
+    const unsigned before = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (before != expected - 1u) return false;
+    __hip_atomic_store(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // nobody else touches it again in this launch
+    return true;
+}
+
+template <int DT, int BLOCK, int U>
+__global__ __launch_bounds__(BLOCK) void verify_fused_kernel(VerifyFusedParams p, int64_t unit0)
+{
+    constexpr int NW = BLOCK / kWave;
+    __shared__ SweepShared<1> sh_store;
+    SweepShared<NW>& sh = *reinterpret_cast<SweepShared<NW>*>(&sh_store);  // never touched: no alignment sampling here
+    __shared__ TailShared tail_sh;
+    __shared__ WavePartial wave_part[NW];
+    __shared__ int s_last;
+
+    const int64_t unit = unit0 + blockIdx.x;
+    const int64_t row = unit / p.s.nseg;
+    const int seg = (int)(unit - row * p.s.nseg);
+    const int b = (int)(row / p.s.rows_per_seq);
+    const int tid = threadIdx.x;
+
+    sweep_unit<DT, false, false, BLOCK, U, false, true>(p.s, row, seg, sh, nullptr, wave_part);
+    // the drafts of the sequence: only the workgroup that turns out to be the sequence's last needs them, but asked
+    // for here they arrive while the partial travels to memory and the workgroup is counted in
+    TailInputs<BLOCK> in;
+    tail_load_drafts<BLOCK>(p.t, b, in);
+    __syncthreads();
+
+    // the first wave merges the workgroup's wave partials into ONE partial per (row, segment), sends it to
+    // memory, waits until memory has it, and counts the workgroup in
+    if (tid < kWave) {
+        WavePartial wp;
+        wp.m = -INFINITY; wp.S = 0.f; wp.T = 0.f; wp.code = 0x7fffffff;
+        if (tid < NW) wp = wave_part[tid];
+        float m = wp.m;
+#pragma unroll
+        for (int o = 1; o < NW; o <<= 1) m = fmaxf(m, __shfl_xor(m, o));
+        const bool live = wp.S > 0.f;
+        float dl2 = 0.f, f = 0.f;
+        if (live) partial_scale(wp.m, m, dl2, f);
+        float S = live ? wp.S * f : 0.f;
+        float T2 = live ? (wp.T + dl2 * wp.S) * f : 0.f;
+        int code = live && wp.m == m ? wp.code : 0x7fffffff;
+#pragma unroll
+        for (int o = 1; o < NW; o <<= 1) {
+            S += __shfl_xor(S, o);
+            T2 += __shfl_xor(T2, o);
+            code = min(code, __shfl_xor(code, o));
+        }
+        if (tid == 0) {
+            WavePartial out;
+            out.m = m; out.S = S; out.T = T2; out.code = code; out.cnt = 0; out.nlist = 0; out.thr2 = -INFINITY; out.pad = 0;
+            store_partial_coherent(p.s.partials + (row * p.s.nseg + seg), out);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+
+            const int lines = p.ngroups > 1 ? 1 + p.ngroups : 1;
+            unsigned* base = p.counters + (size_t)b * lines * kCounterWords;
+            const unsigned per_seq = (unsigned)p.s.rows_per_seq * (unsigned)p.s.nseg;
+            bool last;
+            if (p.ngroups > 1) {
+                const unsigned u = (unsigned)(row - (int64_t)b * p.s.rows_per_seq) * (unsigned)p.s.nseg + (unsigned)seg;
+                const unsigned g = u % (unsigned)p.ngroups;
+                const unsigned in_group = (per_seq - g + (unsigned)p.ngroups - 1u) / (unsigned)p.ngroups;
+                last = arrive_is_last(base + (size_t)(1 + g) * kCounterWords, in_group) && arrive_is_last(base, (unsigned)p.ngroups);
+            } else {
+                last = arrive_is_last(base, per_seq);
+            }
+            s_last = last ? 1 : 0;
+        }
+    }
+    __syncthreads();
+    if (!s_last) return;   // the same in every thread of the workgroup
+    tail_load_logits<DT, BLOCK>(p.t, b, in);                         // in flight together with the partials
+    verify_tail_block<DT, BLOCK, true, true>(p.t, b, in, tail_sh);   // p.t.npart = nseg: one partial per workgroup
 }
 
 }  // namespace aasd

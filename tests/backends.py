@@ -11,7 +11,7 @@ import torch
 
 import oracle
 import paper_2505_13204_amd as aasd
-from paper_2505_13204_amd import harness, synth
+from tests import harness, synth
 
 NEAR = 1e-6        # decisions whose oracle margin is below this are counted, not compared
 NEAR_GUMBEL = 5e-5 # the same for Gumbel-top-k draws: gap between neighbouring keys z + G (fp32 keys err by < 1e-5)
@@ -193,8 +193,10 @@ class OracleBackend(harness.Backend):
 
 
 class HipBackend(harness.Backend):
-    def __init__(self, device="cuda:0"):
+    def __init__(self, device="cuda:0", one_launch=False):
         self.device = torch.device(device)
+        self.one_launch = one_launch      # aasd_verify in its one-launch form, over a zero-filled workspace kept per shape
+        self._ws = {}
 
     def _dev(self, a, dtype):
         return torch.as_tensor(np.ascontiguousarray(a), device=self.device).to(dtype)
@@ -214,8 +216,16 @@ class HipBackend(harness.Backend):
         return synth.verify_logits(w, step, gs, copieds, length, drafts, draft_len, self.device, peaked=peaked)
 
     def verify(self, logits, drafts, draft_len, strict, w):
+        kw = {}
+        if self.one_launch:
+            B, C, k = drafts.shape
+            key = (B, C, k, logits.shape[2], logits.dtype)
+            if key not in self._ws:
+                nbytes = aasd.verify_workspace_bytes(B, C, k, logits.shape[2], aasd.BF16 if logits.dtype == torch.bfloat16 else aasd.F32)
+                self._ws[key] = torch.zeros(nbytes, dtype=torch.uint8, device=self.device)
+            kw = dict(workspace=self._ws[key], zeroed_workspace=True)
         out = aasd.verify(logits, self._dev(drafts, torch.int32), self._dev(draft_len, torch.int32),
-                          self._dev(strict, torch.uint8), alpha=w.alpha, beta=w.beta)
+                          self._dev(strict, torch.uint8), alpha=w.alpha, beta=w.beta, **kw)
         torch.cuda.synchronize()
         return to_np(out)
 
@@ -244,8 +254,8 @@ class HipBackend(harness.Backend):
 class ParityBackend(harness.Backend):
     """Runs both, asserts parity on every call, returns the oracle's results."""
 
-    def __init__(self, device="cuda:0"):
-        self.hip = HipBackend(device)
+    def __init__(self, device="cuda:0", one_launch=False):
+        self.hip = HipBackend(device, one_launch=one_launch)
         self.orc = OracleBackend()
         self.tally = Tally()
 
@@ -282,3 +292,47 @@ class ParityBackend(harness.Backend):
         got = self.hip.verify_tree(dev, tree, w)
         compare_verify_tree(got, ref, self.tally)
         return ref
+
+
+# --------------------------------------------------------------------------- the oracle over many rows
+# The oracle is single-threaded C without global state, and ctypes releases the interpreter lock during a
+# call: disjoint ranges of rows (or of sequences) can be handed to a few host threads.  Every range is still
+# computed by the same plain code; the threads share nothing but read-only inputs.
+def host_threads() -> int:
+    import os
+    return max(1, min(16, os.cpu_count() or 1))
+
+
+def _ranges(n, parts):
+    parts = max(1, min(parts, n))
+    edges = np.linspace(0, n, parts + 1).astype(np.int64)
+    return [(int(a), int(b)) for a, b in zip(edges[:-1], edges[1:]) if b > a]
+
+
+def oracle_align_rows(bits, next_tok, m, c, mode, seed=0, row_id_base=0, V=None):
+    """oracle.align_sample over all rows of `bits`, row ranges spread over the host's threads."""
+    from concurrent.futures import ThreadPoolExecutor
+    rows = bits.shape[0]
+    nt = None if next_tok is None else np.asarray(next_tok, dtype=np.int32)
+    rs = _ranges(rows, host_threads() * 4)
+    def run(ab):
+        a, b = ab
+        return oracle.align_sample(bits[a:b], None if nt is None else nt[a:b], m_x=m, c=c, mode=mode, seed=seed,
+                                   row_id_base=row_id_base + a, V=V)
+    with ThreadPoolExecutor(host_threads()) as ex:
+        parts = list(ex.map(run, rs))
+    return {k: np.concatenate([p[k] for p in parts]) for k in parts[0]}
+
+
+def oracle_verify_seqs(bits, drafts, draft_len, strict, alpha, beta, flags=0):
+    """oracle.verify over all sequences of `bits` [B, R, V], sequence ranges spread over the host's threads."""
+    from concurrent.futures import ThreadPoolExecutor
+    B = bits.shape[0]
+    rs = _ranges(B, host_threads() * 2)
+    def run(ab):
+        a, b = ab
+        return oracle.verify(bits[a:b], drafts[a:b], draft_len[a:b], None if strict is None else strict[a:b],
+                             alpha=alpha, beta=beta, flags=flags)
+    with ThreadPoolExecutor(host_threads()) as ex:
+        parts = list(ex.map(run, rs))
+    return {k: np.concatenate([p[k] for p in parts]) for k in parts[0]}

@@ -15,3 +15,15 @@ def pytest_configure(config):
 @pytest.fixture(scope="session")
 def golden_dir():
     return os.path.join(ROOT, "tests", "golden")
+
+
+@pytest.fixture
+def forced_plan():
+    """Force the row sweep's launch shape ("threads,loads[,segments]") for the test, then hand it back to the library."""
+    import paper_2505_13204_amd as aasd
+
+    def force(shape: str):
+        v = [int(x) for x in shape.split(",")]
+        aasd.set_sweep_plan(v[0], v[1], v[2] if len(v) > 2 else 0)
+    yield force
+    aasd.set_sweep_plan(0, 0, 0)

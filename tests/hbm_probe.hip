@@ -3,7 +3,9 @@
 // (2) a reference dispatch of known byte count for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE
 // counters (run it under `rocprofv3 --pmc FETCH_SIZE` and compare with the bytes printed here).
 //
-// usage: hbm_probe [MiB per buffer = 2048] [repeats = 10]
+// Measurement tool, not part of the library: build with
+//   hipcc -O3 -std=c++17 --offload-arch=gfx950 -o tests/hbm_probe tests/hbm_probe.hip
+// usage: tests/hbm_probe [MiB per buffer = 2048] [repeats = 10]
 #include <hip/hip_runtime.h>
 
 #include <cstdio>

@@ -21,9 +21,14 @@ def lib():
 
 
 def test_exports_every_declared_symbol(lib):
-    header = open(os.path.join(ROOT, "include", "aasd.h")).read()
-    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    names = set(re.findall(r"\b(aasd_[a-z_]+)\s*\(", header))
+    names = set()
+    inc = os.path.join(ROOT, "include")
+    headers = sorted(f for f in os.listdir(inc) if f.endswith(".h"))
+    assert "aasd.h" in headers and "aasd_hooks.h" in headers
+    for h in headers:
+        text = re.sub(r"/\*.*?\*/", "", open(os.path.join(inc, h)).read(), flags=re.S)
+        names |= set(re.findall(r"\b(aasd_[a-z_]+)\s*\(", text))
+    assert {"aasd_hook_sweep_events", "aasd_hook_draw_events", "aasd_hook_sweep_plan"} <= names
     assert {"aasd_version", "aasd_last_error", "aasd_align_sample", "aasd_align_sample_workspace_bytes",
             "aasd_retrieve_drafts", "aasd_verify_workspace_bytes", "aasd_verify"} <= names
     for n in names:
@@ -83,22 +88,43 @@ def _verify(lib, **kw):
 
 def test_verify_rejects_invalid_arguments(lib):
     for kw in [dict(dt=-1), dict(B=-1), dict(C=0), dict(C=33), dict(k=0), dict(k=17), dict(V=0), dict(rs=99), dict(ss=899),
-               dict(flags=2), dict(logits=None), dict(drafts=None), dict(dl=None), dict(al=None), dict(nt=None)]:
+               dict(flags=4), dict(flags=8 | 1), dict(logits=None), dict(drafts=None), dict(dl=None), dict(al=None), dict(nt=None)]:
         assert _verify(lib, **kw) == INVALID, kw
     assert _verify(lib, logits=FAKE + 1) == UNSUPPORTED
     assert _verify(lib, ws=None) == WORKSPACE
     assert _verify(lib, wsb=lib.aasd_verify_workspace_bytes(2, 2, 4, 100, 1) - 1) == WORKSPACE
-    assert _verify(lib, ws=FAKE + 4) == WORKSPACE
+    assert _verify(lib, ws=FAKE + 4) == WORKSPACE and _verify(lib, ws=FAKE + 64) == WORKSPACE   # 128-byte alignment
     assert b"workspace" in lib.aasd_last_error()
-    assert _verify(lib, B=0) == 0
+    assert _verify(lib, flags=2, ws=None) == WORKSPACE   # the one-launch form needs the caller's workspace all the more
+    assert _verify(lib, B=0) == 0 and _verify(lib, B=0, flags=3) == 0
+
+
+def test_sweep_plan_hook_accepts_compiled_shapes_only(lib):
+    """The override is validated when it is set, so no call can fail on it after its first launch."""
+    base = lib.aasd_verify_workspace_bytes(1, 1, 8, 128256, 1)
+    try:
+        for t, l, ok in [(256, 1, True), (256, 2, True), (256, 4, True), (512, 2, True), (512, 4, True), (1024, 1, True),
+                         (1024, 2, True), (512, 1, False), (1024, 4, False), (128, 2, False), (0, 2, False), (256, 0, False),
+                         (300, 2, False)]:
+            assert (lib.aasd_hook_sweep_plan(t, l, 0) == 0) == ok, (t, l)
+        assert lib.aasd_hook_sweep_plan(256, 2, 17) == INVALID and lib.aasd_hook_sweep_plan(256, 2, -1) == INVALID
+        assert lib.aasd_hook_sweep_plan(0, 0, 17) == INVALID
+        assert lib.aasd_hook_sweep_plan(1024, 1, 4) == 0
+        assert lib.aasd_verify_workspace_bytes(1, 1, 8, 128256, 1) == 7 * 128 + 9 * 4 * 16 * 32   # 4 segments x 16 waves; 36 workgroups count in 6 groups
+        assert lib.aasd_hook_sweep_plan(0, 0, 2) == 0                                        # segments only
+        assert lib.aasd_verify_workspace_bytes(1, 1, 8, 128256, 1) == 128 + 9 * 2 * 4 * 32
+    finally:
+        assert lib.aasd_hook_sweep_plan(0, 0, 0) == 0
+    assert lib.aasd_verify_workspace_bytes(1, 1, 8, 128256, 1) == base
 
 
 def test_workspace_query(lib):
-    """One 32-byte partial per wave of the sweep; alignment sampling adds a list of 48 chunk positions."""
+    """Arrival counters (a 128-byte line per sequence, plus one per group of workgroups in short launches), then one
+    32-byte partial per wave of the sweep; alignment sampling adds a list of 48 chunk positions."""
     big = lib.aasd_verify_workspace_bytes(64, 16, 8, 152064, 1)      # 8256 rows, one workgroup of 4 waves per row
-    assert big == 64 * 129 * 4 * 32
-    small = lib.aasd_verify_workspace_bytes(1, 1, 8, 128256, 1)      # 9 rows: rows are cut into segments
-    assert small % (9 * 32) == 0 and 9 * 32 < small <= 9 * 64 * 32
+    assert big == 64 * 128 + 64 * 129 * 4 * 32
+    small = lib.aasd_verify_workspace_bytes(1, 1, 8, 128256, 1)        # 9 rows: rows are cut into 16 segments, 144 workgroups in 12 groups
+    assert small == 13 * 128 + 9 * 16 * 4 * 32
     assert lib.aasd_verify_workspace_bytes(1, 0, 4, 100, 1) == 0
     assert lib.aasd_verify_workspace_bytes(1, 4, 17, 100, 1) == 0
     assert lib.aasd_verify_workspace_bytes(1, 4, 8, 0, 1) == 0
@@ -121,7 +147,7 @@ def _build_tree(lib, **kw):
 
 def test_build_tree_rejects_invalid_arguments(lib):
     for kw in [dict(B=-1), dict(k=0), dict(k=17), dict(C=0), dict(C=33), dict(m=-1), dict(m=5), dict(dx=FAKE, m=0),
-               dict(N=0), dict(N=257), dict(drafts=None), dict(dl=None), dict(tok=None), dict(par=None), dict(dep=None),
+               dict(N=0), dict(N=513), dict(drafts=None), dict(dl=None), dict(tok=None), dict(par=None), dict(dep=None),
                dict(st=None), dict(nn=None)]:
         assert _build_tree(lib, **kw) == INVALID, kw
         assert b"build_tree" in lib.aasd_last_error()
@@ -139,7 +165,7 @@ def _verify_tree(lib, **kw):
 
 
 def test_verify_tree_rejects_invalid_arguments(lib):
-    for kw in [dict(dt=2), dict(B=-1), dict(N=0), dict(N=257), dict(V=0), dict(rs=99), dict(ss=1599), dict(flags=4),
+    for kw in [dict(dt=2), dict(B=-1), dict(N=0), dict(N=513), dict(V=0), dict(rs=99), dict(ss=1599), dict(flags=4),
                dict(logits=None), dict(tok=None), dict(par=None), dict(nn=None), dict(al=None), dict(bn=None),
                dict(nt=None)]:
         assert _verify_tree(lib, **kw) == INVALID, kw
@@ -150,7 +176,7 @@ def test_verify_tree_rejects_invalid_arguments(lib):
     assert _verify_tree(lib, B=0) == 0
     assert lib.aasd_verify_tree_workspace_bytes(128, 64, 128256, 1) == 128 * 64 * 4 * 32   # 8192 rows, 4 waves per row
     assert lib.aasd_verify_tree_workspace_bytes(1, 0, 100, 1) == 0
-    assert lib.aasd_verify_tree_workspace_bytes(1, 257, 100, 1) == 0
+    assert lib.aasd_verify_tree_workspace_bytes(1, 513, 100, 1) == 0
 
 
 def _verify_topk(lib, **kw):
@@ -210,6 +236,6 @@ def test_header_is_plain_c(tmp_path):
     """The boundary is a C ABI: the header compiles as C99 on its own (no C++ or HIP types in it)."""
     import subprocess
     src = tmp_path / "use.c"
-    src.write_text('#include "aasd.h"\nint main(void) { return (int)sizeof(aasd_status) + AASD_MAX_TREE_NODES > 0 ? 0 : 1; }\n')
+    src.write_text('#include "aasd.h"\n#include "aasd_hooks.h"\nint main(void) { return (int)sizeof(aasd_status) + AASD_MAX_TREE_NODES > 0 ? 0 : 1; }\n')
     subprocess.check_call(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-fsyntax-only",
                            "-I", os.path.join(ROOT, "include"), str(src)])

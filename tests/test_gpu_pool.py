@@ -6,7 +6,7 @@ import torch
 
 import oracle
 import paper_2505_13204_amd as aasd
-from paper_2505_13204_amd import harness, synth
+from tests import harness, synth
 from tests import backends as bk
 
 pytestmark = pytest.mark.gpu

@@ -8,7 +8,7 @@ import torch
 
 import oracle
 import paper_2505_13204_amd as aasd
-from paper_2505_13204_amd import synth
+from tests import synth
 from tests import backends as bk
 from tests import test_gpu_parity as P
 from tests import test_gpu_tree as T

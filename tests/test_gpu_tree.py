@@ -7,7 +7,7 @@ import torch
 
 import oracle
 import paper_2505_13204_amd as aasd
-from paper_2505_13204_amd import harness, synth
+from tests import harness, synth
 from tests import backends as bk
 
 pytestmark = pytest.mark.gpu
@@ -42,7 +42,8 @@ def _build_both(drafts, dl, strict, dx, root, N):
 
 
 @pytest.mark.parametrize("C,k,m,N", [(1, 1, 0, 1), (1, 4, 0, 8), (3, 4, 2, 64), (8, 8, 2, 40), (16, 8, 2, 256),
-                                     (32, 16, 4, 256), (4, 6, 3, 5), (32, 16, 4, 33), (16, 8, 0, 129)])
+                                     (32, 16, 4, 256), (4, 6, 3, 5), (32, 16, 4, 33), (16, 8, 0, 129),
+                                     (16, 8, 2, 385), (16, 8, 2, 512), (32, 16, 4, 512), (16, 8, 2, 300)])
 def test_build_tree_random_small_alphabet(C, k, m, N):
     rng = np.random.default_rng(C * 100 + k)
     for B, alphabet in [(12, 3), (5, 50), (1, 2)]:
@@ -68,6 +69,37 @@ def test_build_tree_full_and_empty():
     out = aasd.build_tree(torch.empty((0, C, k), dtype=torch.int32, device=DEV),
                           torch.empty((0, C), dtype=torch.int32, device=DEV), max_nodes=64)
     assert out["n_nodes"].numel() == 0
+
+
+def test_tree_at_the_papers_largest_parameters():
+    """16 candidates of 8 tokens with two extras at every position and nothing shared: 385 nodes (Sec. 3.2 Eq. 2
+    with Sec. 4.1's cap of two extras).  Built and verified on the GPU against the oracle, also under a budget
+    (256) that cuts the tree, and with prefixes shared between candidates so that the count varies."""
+    rng = np.random.default_rng(385)
+    B, C, k, m, V = 3, 16, 8, 2, 9000
+    perm = np.stack([rng.permutation(V) for _ in range(B)]).astype(np.int32)           # all tokens of a sequence distinct
+    drafts = perm[:, :C * k].reshape(B, C, k).copy()
+    dx = perm[:, C * k:C * k * (1 + m)].reshape(B, C, k, m).copy()
+    drafts[1, 8:, :3] = drafts[1, :8, :3]               # sequence 1: candidates share three-token prefixes in pairs
+    drafts[2, 1:] = drafts[2, 0]                        # sequence 2: all candidates identical, one chain with extras
+    dx[2, 1:] = dx[2, 0]
+    dl = np.full((B, C), k, np.int32)
+    strict = (rng.random((B, C, k)) < 0.3).astype(np.uint8)
+    root = np.array([1, 2, 3], np.int32)
+    dx_in_vocab = dx
+    for N in (512, 385, 256):
+        ref = _build_both(drafts, dl, strict, dx_in_vocab, root, N)
+        if N >= 385:
+            assert ref["n_nodes"][0] == 385 and 256 < ref["n_nodes"][1] < 385 and ref["n_nodes"][2] == 1 + k * 3
+        else:
+            assert ref["n_nodes"][0] == 256
+    tree = oracle.build_tree(drafts, dl, strict, dx_in_vocab, root_tok=root, max_nodes=512)
+    tally = bk.Tally()
+    for dtype in ("bf16", "f32"):
+        zd = _tree_logits(rng, tree, V, dtype, p_lead=0.8)
+        ref, _ = _verify_tree_both(zd, tree, tree["node_strict"], 0.1, 0.1, 0, tally)
+    assert ref["accept_len"].max() >= 3 and tally.tokens > 100
+    print("385-node trees", tally)
 
 
 def test_build_tree_from_retrieval_outputs():
@@ -312,10 +344,10 @@ def test_verify_tree_more_sequences_than_one_launch_covers(B, N, V):
 
 
 @pytest.mark.parametrize("shape", ["256,1", "256,2", "256,4", "512,2", "512,4", "1024,1", "1024,2", "256,2,5", "512,2,8", "1024,1,4"])
-def test_verify_tree_under_every_compiled_launch_shape(shape, monkeypatch):
+def test_verify_tree_under_every_compiled_launch_shape(shape, forced_plan):
     """The used-rows sweep is compiled for the same (threads, loads in flight[, segments]) shapes as the plain
     sweep; every one of them must give the oracle's answers, for both element types."""
-    monkeypatch.setenv("AASD_SWEEP_CONFIG", shape)
+    forced_plan(shape)
     rng = np.random.default_rng(19)
     B, C, k, N, V = 7, 4, 5, 24, 128256 // 4 + 5
     drafts, dl, strict, dx = _random_candidates(rng, B, C, k, 2, alphabet=30)

@@ -4,7 +4,7 @@ import torch
 
 import oracle
 
-from paper_2505_13204_amd import harness, synth
+from tests import harness, synth
 from tests import backends as bk
 
 
