@@ -214,6 +214,30 @@ int aasd_verify(const void *logits, int32_t dt, int32_t B, int32_t C, int32_t k,
                 void *stream);
 
 /*
+ * aasd_verify for callers that cannot allocate device memory or pass a workspace along: code running
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  It is aasd_verify
+ * (same arguments, same kernels, same outputs) with the workspace replaced by scratch memory that is
+ * built into the library: 4.25 MiB per GPU, held from the first call on a GPU until the process ends.
+ * The call itself allocates nothing and frees nothing.
+ *   - Limit: the partial results of the call must fit aasd_verify_static_max_bytes() = 4 MiB, i.e.
+ *     aasd_verify_workspace_bytes(B, C, k, V, dt) minus its counters; this covers every decode step up to
+ *     32768 rows (B * (1 + C*k)).  Larger calls return AASD_ERR_UNSUPPORTED and enqueue nothing: use
+ *     aasd_verify with a workspace for them.
+ *   - Decode-step shapes run as one launch (the form AASD_VERIFY_ZEROED_WORKSPACE selects in aasd_verify;
+ *     the flag itself is not accepted here): the library keeps its own counters at zero.
+ *   - Every call on one GPU uses that GPU's one scratch array: calls that overlap in time on the same GPU
+ *     (two streams, two threads) race and give undefined outputs; calls ordered on one stream are safe.
+ *   - The device must be the calling thread's current device when the call is made.
+ */
+size_t aasd_verify_static_max_bytes(void);
+int aasd_verify_static(const void *logits, int32_t dt, int32_t B, int32_t C, int32_t k, int32_t V,
+                       int64_t row_stride, int64_t seq_stride, const int32_t *drafts,
+                       const int32_t *draft_len, const uint8_t *strict, float alpha, float beta,
+                       uint32_t flags, int32_t *accept_len, int32_t *best_cand, int32_t *next_token,
+                       float *row_entropy, float *row_pmax, int32_t *row_argmax, float *tok_p,
+                       float *tok_delta, uint32_t *near_count, void *stream);
+
+/*
  * Persistent draft pool (Sec. 3.1; Algorithm 1: the dictionary from n-grams to the positions after their
  * occurrences, initialised over the prompt and then extended by the windows that end in the new tokens).
  * aasd_pool_retrieve returns exactly what aasd_retrieve_drafts returns for the same arguments, but

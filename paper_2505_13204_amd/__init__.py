@@ -295,6 +295,30 @@ def verify(logits: torch.Tensor, drafts: torch.Tensor, draft_len: torch.Tensor, 
     return o
 
 
+def verify_static(logits: torch.Tensor, drafts: torch.Tensor, draft_len: torch.Tensor, strict: Optional[torch.Tensor],
+                  out: dict, alpha: float = 0.1, beta: float = 0.1, flags: int = 0, V: Optional[int] = None):
+    """aasd_verify_static: aasd_verify on the library's built-in scratch memory.  Nothing is allocated, here
+    or in the library: `out` must carry accept_len, best_cand, next_token [B] (int32) and may carry row_entropy,
+    row_pmax, row_argmax [B,R], tok_p, tok_delta [B,C,k], near_count [B]; it is returned."""
+    B, R = logits.shape[0], logits.shape[1]
+    _, C, k = drafts.shape
+    row_stride = logits.stride(1)
+    seq_stride = logits.stride(0) if B > 1 else R * row_stride
+    V = logits.shape[2] if V is None else V
+    rc = _lib.load().aasd_verify_static(
+        logits.data_ptr(), _dtype_code(logits), B, C, k, V, row_stride, seq_stride,
+        drafts.data_ptr(), draft_len.data_ptr(), _ptr(strict), float(alpha), float(beta), flags,
+        out["accept_len"].data_ptr(), out["best_cand"].data_ptr(), out["next_token"].data_ptr(),
+        _ptr(out.get("row_entropy")), _ptr(out.get("row_pmax")), _ptr(out.get("row_argmax")), _ptr(out.get("tok_p")),
+        _ptr(out.get("tok_delta")), _ptr(out.get("near_count")), _stream(logits.device))
+    _check(rc)
+    return out
+
+
+def verify_static_max_bytes() -> int:
+    return int(_lib.load().aasd_verify_static_max_bytes())
+
+
 def verify_topk_workspace_bytes(B: int, C: int, k: int, V: int, dt: int) -> int:
     return int(_lib.load().aasd_verify_topk_workspace_bytes(B, C, k, V, dt))
 

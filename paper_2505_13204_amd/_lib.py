@@ -56,6 +56,10 @@ def load():
         c_void_p, c_void_p, c_void_p, c_float, c_float, c_uint32,
         c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
         c_void_p, c_size_t, c_void_p]
+    lib.aasd_verify_static_max_bytes.restype = c_size_t
+    lib.aasd_verify_static_max_bytes.argtypes = []
+    lib.aasd_verify_static.restype = c_int32
+    lib.aasd_verify_static.argtypes = list(lib.aasd_verify.argtypes[:23]) + [c_void_p]
     lib.aasd_pool_bytes.restype = c_size_t
     lib.aasd_pool_bytes.argtypes = [c_int32, c_int32, c_int32, c_int32]
     lib.aasd_pool_update.restype = c_int32

@@ -20,6 +20,12 @@
 #include "verify_tail.hip.h"
 #include "verify_topk.hip.h"
 
+// Scratch memory of aasd_verify_static, one copy per GPU, zero when the library is loaded: 256 KiB of arrival
+// counters (2048 lines of 128 bytes), then 4 MiB of partial results.  Host code reaches it only through the
+// address that hipGetSymbolAddress returns for the current device: here the array's name is a handle, not a
+// device address.
+static __device__ __align__(256) unsigned char scratch[(256u << 10) + (4u << 20)];
+
 namespace {
 
 thread_local char g_err[512] = "";
@@ -299,6 +305,14 @@ size_t verify_counter_bytes(int32_t B, int ngroups)
 {
     return (size_t)B * (size_t)(ngroups > 1 ? 1 + ngroups : 1) * aasd::kCounterWords * sizeof(unsigned);
 }
+
+// Layout of `scratch` and what the host keeps about it per GPU.
+constexpr size_t kScratchCounterBytes = (size_t)256 << 10;
+constexpr size_t kScratchPartialBytes = (size_t)4 << 20;
+static_assert(sizeof(scratch) == kScratchCounterBytes + kScratchPartialBytes, "scratch layout");
+constexpr int kMaxDevices = 64;
+std::atomic<char*> g_scratch_ptr[kMaxDevices];    // device address of `scratch` on each GPU, once looked up
+std::atomic<bool> g_scratch_dirty[kMaxDevices];   // a launch on it failed midway: its counters may not be zero
 
 int verify_check(const void* logits, int32_t dt, int32_t B, int32_t C, int32_t k, int32_t V, int64_t row_stride,
                  int64_t seq_stride, const int32_t* drafts, const int32_t* draft_len, uint32_t flags,
@@ -617,6 +631,61 @@ int aasd_verify(const void* logits, int32_t dt, int32_t B, int32_t C, int32_t k,
                          accept_len, best_cand, next_token, row_entropy, row_pmax, row_argmax, tok_p, tok_delta,
                          near_count, (unsigned*)workspace, (char*)workspace + (need - partial_bytes),
                          (flags & AASD_VERIFY_ZEROED_WORKSPACE) != 0, (hipStream_t)stream);
+}
+
+size_t aasd_verify_static_max_bytes(void) { return kScratchPartialBytes; }
+
+int aasd_verify_static(const void* logits, int32_t dt, int32_t B, int32_t C, int32_t k, int32_t V,
+                       int64_t row_stride, int64_t seq_stride, const int32_t* drafts,
+                       const int32_t* draft_len, const uint8_t* strict, float alpha, float beta,
+                       uint32_t flags, int32_t* accept_len, int32_t* best_cand, int32_t* next_token,
+                       float* row_entropy, float* row_pmax, int32_t* row_argmax, float* tok_p,
+                       float* tok_delta, uint32_t* near_count, void* stream)
+{
+    if (flags & AASD_VERIFY_ZEROED_WORKSPACE) return fail(AASD_ERR_INVALID_ARG, "verify_static: AASD_VERIFY_ZEROED_WORKSPACE is about a caller's workspace");
+    const int rc = verify_check(logits, dt, B, C, k, V, row_stride, seq_stride, drafts, draft_len, flags, accept_len,
+                                best_cand, next_token);
+    if (rc != AASD_OK || B == 0) return rc;
+    const int64_t R = 1 + (int64_t)C * k, rows = (int64_t)B * R;
+    const size_t need = (size_t)rows * plan_sweep(false, rows, V, dt).npart * sizeof(aasd::WavePartial);
+    if (need > kScratchPartialBytes)
+        return fail(AASD_ERR_UNSUPPORTED, "verify_static: %zu bytes of partial results needed for %lld rows, the built-in scratch holds %zu "
+                    "(use aasd_verify with a workspace)", need, (long long)rows, kScratchPartialBytes);
+    // one launch only if its counters fit the built-in ones (they do for every shape that is served in one launch by
+    // aasd_verify, which are decode steps of at most 1792 workgroups; checked all the same)
+    const SweepPlan pf = plan_fused(rows, V, dt);
+    const bool one_launch = verify_counter_bytes(B, verify_groups(rows, R * pf.nseg)) <= kScratchCounterBytes;
+
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices)
+        return fail(AASD_ERR_UNSUPPORTED, "verify_static: no current device, or its index is beyond %d", kMaxDevices - 1);
+    char* base = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!base) {   // first call on this GPU: where its copy of the array lives
+        void* sym = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !sym) return fail(AASD_ERR_LAUNCH, "verify_static: hipGetSymbolAddress failed: %s", hipGetErrorString(e));
+        base = (char*)sym;
+        g_scratch_ptr[dev].store(base, std::memory_order_release);
+    }
+    hipStream_t s = (hipStream_t)stream;
+    unsigned* counters = (unsigned*)base;
+    if (one_launch && g_scratch_dirty[dev].exchange(false)) {
+        // The counters are zero when the library is loaded and every completed call leaves them so; only a call
+        // that failed between its launches can have left some behind.  (A fill kernel, not a memset: the caller may
+        // be capturing a graph.)
+        const int words = (int)(kScratchCounterBytes / sizeof(unsigned));
+        hipLaunchKernelGGL(aasd::fill_u32_kernel, dim3((words + 255) / 256), dim3(256), 0, s, counters, 0u, words);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) {
+            g_scratch_dirty[dev].store(true);
+            return fail(AASD_ERR_LAUNCH, "verify_static: clearing the counters failed: %s", hipGetErrorString(e));
+        }
+    }
+    const int rc2 = verify_launch(logits, dt, B, C, k, V, row_stride, seq_stride, drafts, draft_len, strict, alpha, beta, flags,
+                                  accept_len, best_cand, next_token, row_entropy, row_pmax, row_argmax, tok_p, tok_delta,
+                                  near_count, counters, base + kScratchCounterBytes, one_launch, s);
+    if (rc2 != AASD_OK) g_scratch_dirty[dev].store(true);
+    return rc2;
 }
 
 size_t aasd_pool_bytes(int32_t B, int32_t capacity, int32_t n_min, int32_t n_max)

@@ -99,6 +99,24 @@ def test_verify_rejects_invalid_arguments(lib):
     assert _verify(lib, B=0) == 0 and _verify(lib, B=0, flags=3) == 0
 
 
+def test_verify_static_checks_its_arguments_and_its_limit(lib):
+    def call(**kw):
+        a = dict(logits=FAKE, dt=1, B=2, C=2, k=4, V=100, rs=100, ss=900, drafts=FAKE, dl=FAKE, strict=None, alpha=0.1,
+                 beta=0.1, flags=0, al=FAKE, bc=FAKE, nt=FAKE, stream=None)
+        a.update(kw)
+        return lib.aasd_verify_static(a["logits"], a["dt"], a["B"], a["C"], a["k"], a["V"], a["rs"], a["ss"], a["drafts"],
+                                      a["dl"], a["strict"], a["alpha"], a["beta"], a["flags"], a["al"], a["bc"], a["nt"],
+                                      None, None, None, None, None, None, a["stream"])
+    for kw in [dict(dt=-1), dict(B=-1), dict(C=0), dict(k=17), dict(V=0), dict(rs=99), dict(ss=899), dict(flags=2),
+               dict(flags=4), dict(logits=None), dict(al=None)]:
+        assert call(**kw) == INVALID, kw
+    assert call(logits=FAKE + 1) == UNSUPPORTED
+    assert lib.aasd_verify_static_max_bytes() == 4 << 20
+    # 300 sequences of 129 rows with 4 partials of 32 bytes each: beyond the built-in 4 MiB
+    assert call(B=300, C=16, k=8, ss=12900) == UNSUPPORTED and b"built-in scratch" in lib.aasd_last_error()
+    assert call(B=0) == 0
+
+
 def test_sweep_plan_hook_accepts_compiled_shapes_only(lib):
     """The override is validated when it is set, so no call can fail on it after its first launch."""
     base = lib.aasd_verify_workspace_bytes(1, 1, 8, 128256, 1)
