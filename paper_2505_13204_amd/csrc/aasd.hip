@@ -97,14 +97,21 @@ SweepPlan plan_sweep(bool align, int64_t rows, int32_t V, int32_t dt)
 // Plan of the one-launch form of verification.  Its workgroups do not end with the sweep: each sends its partial
 // to memory, waits, and is counted in (about a microsecond without loads in flight).  That costs nothing while
 // all workgroups of the launch are on the GPU at once (it is paid once, at the end), so a short launch is cut into
-// at most as many workgroups as the GPU holds: 256 compute units x 7 workgroups of 256 threads.
-constexpr int64_t kFusedResident = 256 * 7;
+// at most as many workgroups as the GPU holds at once: 256 compute units x the waves per SIMD that the kernel's
+// registers allow (7 with 4 loads in flight per lane, 5 with 8, 4 with 16) x 4 SIMDs / waves per workgroup.
+// More loads in flight did not make short launches faster (measured: 4, 8 and 16 within 2 %), so 4 it is.
+int64_t fused_resident(int block, int unroll)
+{
+    const int waves_per_simd = unroll >= 4 ? 4 : (unroll == 2 ? 5 : 7);
+    return (int64_t)256 * (waves_per_simd * 4 / (block / aasd::kWave));
+}
 
 SweepPlan plan_fused(int64_t rows, int32_t V, int32_t dt)
 {
     SweepPlan pl = plan_sweep(false, rows, V, dt);
+    if (g_plan_block == 0) pl.unroll = 1;   // the kernel keeps 4 x this many loads per lane in flight
     if (g_plan_nseg == 0 && rows > 0 && pl.nseg > 1) {
-        const int64_t fit = kFusedResident * 256 / pl.block / rows;
+        const int64_t fit = fused_resident(pl.block, pl.unroll) / rows;
         const int nseg = (int)(fit < 1 ? 1 : (fit < pl.nseg ? fit : pl.nseg));
         if (nseg != pl.nseg) {
             const int per_vec = dt == AASD_BF16 ? 8 : 4;
@@ -352,7 +359,7 @@ int verify_launch(const void* logits, int32_t dt, int32_t B, int32_t C, int32_t 
         // against 9.8; 288 rows: 22 against 25); a launch of several rounds of workgroups is faster in two kernels,
         // whose streaming workgroups end as soon as their partials are on their way (8256 rows: 413 us against 397).
         const SweepPlan pf = plan_fused(rows, V, dt);
-        if (rows * pf.nseg * (pf.block / 256) <= kFusedResident) pl = pf;
+        if (rows * pf.nseg <= fused_resident(pf.block, pf.unroll)) pl = pf;
         else one_launch = false;
     }
     aasd::SweepParams sp{};

@@ -75,6 +75,49 @@ __device__ __forceinline__ int wave_min(int v)
     return v;
 }
 
+// The same reductions through the cross-lane data path of the vector ALU instead of LDS permutes: four steps
+// inside each row of 16 lanes (swap neighbours, swap pairs, mirror the half row, mirror the row), after which
+// every lane holds its row's result, then the four rows' results through scalar registers.  A tenth of the
+// latency of the butterflies above; used where a wave's epilogue is not hidden behind other waves.  The
+// combination order is fixed (and differs from the butterflies': sums may differ from theirs in the last bit).
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+template <int CTRL>
+__device__ __forceinline__ int dpp_move(int v)
+{
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, true);
+}
+constexpr int kDppSwap1 = 0xB1, kDppSwap2 = 0x4E, kDppHalfMirror = 0x141, kDppMirror = 0x140;
+__device__ __forceinline__ float lane_value(float v, int lane) { return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane)); }
+__device__ __forceinline__ float wave_sum_dpp(float v)
+{
+    v += dpp_move<kDppSwap1>(v);
+    v += dpp_move<kDppSwap2>(v);
+    v += dpp_move<kDppHalfMirror>(v);
+    v += dpp_move<kDppMirror>(v);
+    return (lane_value(v, 0) + lane_value(v, 16)) + (lane_value(v, 32) + lane_value(v, 48));
+}
+__device__ __forceinline__ float wave_max_dpp(float v)
+{
+    v = fmaxf(v, dpp_move<kDppSwap1>(v));
+    v = fmaxf(v, dpp_move<kDppSwap2>(v));
+    v = fmaxf(v, dpp_move<kDppHalfMirror>(v));
+    v = fmaxf(v, dpp_move<kDppMirror>(v));
+    return fmaxf(fmaxf(lane_value(v, 0), lane_value(v, 16)), fmaxf(lane_value(v, 32), lane_value(v, 48)));
+}
+__device__ __forceinline__ int wave_min_dpp(int v)
+{
+    v = min(v, dpp_move<kDppSwap1>(v));
+    v = min(v, dpp_move<kDppSwap2>(v));
+    v = min(v, dpp_move<kDppHalfMirror>(v));
+    v = min(v, dpp_move<kDppMirror>(v));
+    return min(min(__builtin_amdgcn_readlane(v, 0), __builtin_amdgcn_readlane(v, 16)),
+               min(__builtin_amdgcn_readlane(v, 32), __builtin_amdgcn_readlane(v, 48)));
+}
+
 // Total order used for "best token": larger logit first, then smaller id.
 __device__ __forceinline__ bool better(float za, int ia, float zb, int ib)
 {

@@ -282,7 +282,7 @@ __global__ __launch_bounds__(BLOCK) void verify_fused_kernel(VerifyFusedParams p
     const int b = (int)(row / p.s.rows_per_seq);
     const int tid = threadIdx.x;
 
-    sweep_unit<DT, false, false, BLOCK, U, false, true>(p.s, row, seg, sh, nullptr, wave_part);
+    sweep_unit<DT, false, false, BLOCK, U, false, true, 4 * U>(p.s, row, seg, sh, nullptr, wave_part);   // 4, 8 or 16 loads per lane in flight
     // the drafts of the sequence: only the workgroup that turns out to be the sequence's last needs them, but asked
     // for here they arrive while the partial travels to memory and the workgroup is counted in
     TailInputs<BLOCK> in;
