@@ -279,24 +279,26 @@ def test_row_id_base_partitioning():
 
 
 # --------------------------------------------------------------------------- retrieval
-def _pool_lookup(tok, n_min, n_max, C):
-    """Algorithm 1 taken literally: a dictionary from every window of 1..n_max tokens to the
-    positions just after its occurrences, then longest-key-first lookup with the context suffix."""
+def _suffix_match_lookup(tok, n_min, n_max, C):
+    """What the draft pool of Sec. 3.1 must answer, stated without a pool: for every position p that still has a
+    token after it, how many tokens before p agree with the end of the context (the length of the common
+    suffix of tok[:p] and tok, counted backwards one token at a time)?  The key that the lookup settles on is the
+    longest such agreement, capped at n_max and of at least n_min tokens; the hits are the positions that reach it,
+    latest first."""
     L = len(tok)
-    pool = {}
-    for klen in range(1, n_max + 1):
-        for i in range(0, L - klen + 1):
-            pool.setdefault(tuple(tok[i:i + klen]), []).append(i + klen)
-    for klen in range(n_max, n_min - 1, -1):
-        if klen >= L:
-            continue
-        hits = [p for p in pool.get(tuple(tok[L - klen:]), []) if p <= L - 1]  # needs a continuation token
-        if hits:
-            return klen, sorted(hits, reverse=True)[:C]
-    return 0, []
+    agree = {}
+    for p in range(1, L):                      # p <= L - 1: one continuation token at least
+        n = 0
+        while n < min(p, n_max, L - 1) and tok[p - 1 - n] == tok[L - 1 - n]:
+            n += 1
+        agree[p] = n
+    best = max(agree.values(), default=0)
+    if best < n_min:
+        return 0, []
+    return best, sorted((p for p, n in agree.items() if n >= best), reverse=True)[:C]
 
 
-def test_retrieval_equals_dictionary_pool_of_algorithm_1():
+def test_retrieval_equals_direct_suffix_matching():
     rng = np.random.default_rng(0)
     B, cap = 60, 90
     toks = rng.integers(0, 4, size=(B, cap)).astype(np.int32)  # tiny alphabet: many repeats
@@ -307,7 +309,7 @@ def test_retrieval_equals_dictionary_pool_of_algorithm_1():
         for b in range(B):
             L = int(lens[b])
             t = toks[b, :L].tolist()
-            klen, hits = _pool_lookup(t, n_min, n_max, C)
+            klen, hits = _suffix_match_lookup(t, n_min, n_max, C)
             assert out["key_len"][b] == klen
             assert out["n_cand"][b] == len(hits)
             assert out["src_pos"][b].tolist() == hits + [-1] * (C - len(hits))
