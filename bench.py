@@ -43,10 +43,10 @@ def parse():
     ap.add_argument("--extras-mode", default="top", choices=["top", "sample", "gumbel"],
                     help="how alignment sampling chooses the extras: best-ranked (Fig. 2), seeded draws among the top-c, "
                          "or seeded draws from the whole row (a second, ALU-bound kernel over the misaligned rows)")
-    ap.add_argument("--streams", type=int, default=1, choices=[1, 2],
-                    help="1 (default): every call on one stream, so that kernel durations are their own; 2: alignment sampling "
-                         "(prefill rows) is enqueued on a second HIP stream of the same priority and overlaps with retrieval "
-                         "and verification, which do not depend on it (about 7 %% more rows/s)")
+    ap.add_argument("--streams", type=int, default=2, choices=[1, 2],
+                    help="2 (default): alignment sampling (the prefill rows of new requests) is enqueued on a second HIP stream of the "
+                         "same priority and overlaps with retrieval and verification of the running batch, which do not depend on it; "
+                         "1: every call on one stream.  Kernel times for the roofline block are always taken on one stream")
     ap.add_argument("--retrieval", default="scan", choices=["scan", "pool"],
                     help="n-gram retrieval by the stateless scan of the token buffer, or through the persistent draft pool "
                          "(built in set-up; the latency loop then does an incremental update and a lookup per step)")

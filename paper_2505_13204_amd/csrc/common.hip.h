@@ -54,32 +54,12 @@ __device__ __forceinline__ void unpack(const u32x4& v, float (&z)[Elt<DT>::kPerV
     }
 }
 
-// Butterfly reductions over the 64 lanes of a wave; every lane ends with the result and the
-// combination order is fixed, so sums are reproducible.
-__device__ __forceinline__ float wave_sum(float v)
-{
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-    return v;
-}
-__device__ __forceinline__ unsigned wave_sum(unsigned v)
-{
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-    return v;
-}
-__device__ __forceinline__ int wave_min(int v)
-{
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = min(v, __shfl_xor(v, o));
-    return v;
-}
-
-// The same reductions through the cross-lane data path of the vector ALU instead of LDS permutes: four steps
-// inside each row of 16 lanes (swap neighbours, swap pairs, mirror the half row, mirror the row), after which
-// every lane holds its row's result, then the four rows' results through scalar registers.  A tenth of the
-// latency of the butterflies above; used where a wave's epilogue is not hidden behind other waves.  The
-// combination order is fixed (and differs from the butterflies': sums may differ from theirs in the last bit).
+// Reductions over the 64 lanes of a wave; every lane ends with the result and the combination order is fixed,
+// so sums are reproducible.  They go through the cross-lane data path of the vector ALU, not through LDS
+// permutes: four steps inside each row of 16 lanes (swap neighbours, swap pairs, mirror the half row, mirror the
+// row), after which every lane holds its row's result, then the four rows' results through scalar registers.
+// (A butterfly of six LDS permutes has ten times the latency, and a wave's epilogue is a chain of such
+// reductions.)
 template <int CTRL>
 __device__ __forceinline__ float dpp_move(float v)
 {
@@ -92,7 +72,15 @@ __device__ __forceinline__ int dpp_move(int v)
 }
 constexpr int kDppSwap1 = 0xB1, kDppSwap2 = 0x4E, kDppHalfMirror = 0x141, kDppMirror = 0x140;
 __device__ __forceinline__ float lane_value(float v, int lane) { return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane)); }
-__device__ __forceinline__ float wave_sum_dpp(float v)
+__device__ __forceinline__ int lane_value(int v, int lane) { return __builtin_amdgcn_readlane(v, lane); }
+
+// maximum of the lane's group of four lanes (lanes 4g .. 4g+3)
+__device__ __forceinline__ float quad_max(float v)
+{
+    v = fmaxf(v, dpp_move<kDppSwap1>(v));
+    return fmaxf(v, dpp_move<kDppSwap2>(v));
+}
+__device__ __forceinline__ float wave_sum(float v)
 {
     v += dpp_move<kDppSwap1>(v);
     v += dpp_move<kDppSwap2>(v);
@@ -100,22 +88,29 @@ __device__ __forceinline__ float wave_sum_dpp(float v)
     v += dpp_move<kDppMirror>(v);
     return (lane_value(v, 0) + lane_value(v, 16)) + (lane_value(v, 32) + lane_value(v, 48));
 }
-__device__ __forceinline__ float wave_max_dpp(float v)
+__device__ __forceinline__ unsigned wave_sum(unsigned u)
 {
-    v = fmaxf(v, dpp_move<kDppSwap1>(v));
-    v = fmaxf(v, dpp_move<kDppSwap2>(v));
+    int v = (int)u;
+    v += dpp_move<kDppSwap1>(v);
+    v += dpp_move<kDppSwap2>(v);
+    v += dpp_move<kDppHalfMirror>(v);
+    v += dpp_move<kDppMirror>(v);
+    return (unsigned)(lane_value(v, 0) + lane_value(v, 16) + lane_value(v, 32) + lane_value(v, 48));
+}
+__device__ __forceinline__ float wave_max(float v)
+{
+    v = quad_max(v);
     v = fmaxf(v, dpp_move<kDppHalfMirror>(v));
     v = fmaxf(v, dpp_move<kDppMirror>(v));
     return fmaxf(fmaxf(lane_value(v, 0), lane_value(v, 16)), fmaxf(lane_value(v, 32), lane_value(v, 48)));
 }
-__device__ __forceinline__ int wave_min_dpp(int v)
+__device__ __forceinline__ int wave_min(int v)
 {
     v = min(v, dpp_move<kDppSwap1>(v));
     v = min(v, dpp_move<kDppSwap2>(v));
     v = min(v, dpp_move<kDppHalfMirror>(v));
     v = min(v, dpp_move<kDppMirror>(v));
-    return min(min(__builtin_amdgcn_readlane(v, 0), __builtin_amdgcn_readlane(v, 16)),
-               min(__builtin_amdgcn_readlane(v, 32), __builtin_amdgcn_readlane(v, 48)));
+    return min(min(lane_value(v, 0), lane_value(v, 16)), min(lane_value(v, 32), lane_value(v, 48)));
 }
 
 // Total order used for "best token": larger logit first, then smaller id.
@@ -125,12 +120,9 @@ __device__ __forceinline__ bool better(float za, int ia, float zb, int ib)
 }
 __device__ __forceinline__ void wave_best(float& z, int& i)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        float oz = __shfl_xor(z, o);
-        int oi = __shfl_xor(i, o);
-        if (better(oz, oi, z, i)) { z = oz; i = oi; }
-    }
+    const float bz = wave_max(z);
+    i = wave_min(z == bz ? i : 0x7fffffff);
+    z = bz;
 }
 
 // Plain fill of n 32-bit words (used where a memset node must not enter a captured graph).

@@ -150,9 +150,7 @@ __device__ __forceinline__ void row_topc_from_lists(const AlignFinishParams& p, 
     if (np >= p.c) {
         float v = lane < np ? wp.m : -INFINITY, kth = -INFINITY;
         for (int r = 0; r < p.c; ++r) {
-            float mx = v;
-#pragma unroll
-            for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+            const float mx = wave_max(v);
             kth = mx;
             const unsigned long long owners = __ballot(v == mx);
             if (lane == __ffsll((long long)owners) - 1) v = -INFINITY;   // one wave gives up its maximum per round
@@ -260,12 +258,8 @@ __global__ __launch_bounds__(kFinishBlock) void align_finish_kernel(AlignFinishP
     WavePartial wp;
     wp.m = -INFINITY; wp.S = 0.f; wp.T = 0.f; wp.code = 0x7fffffff; wp.cnt = 0; wp.nlist = 0; wp.thr2 = -INFINITY;
     if (lane < np) wp = p.partials[row * np + lane];
-    float m = wp.m, thr2 = wp.thr2;
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        m = fmaxf(m, __shfl_xor(m, o));
-        thr2 = fmaxf(thr2, __shfl_xor(thr2, o));  // each wave's bound holds for the row: take the tightest
-    }
+    const float m = wave_max(wp.m);
+    float thr2 = wave_max(wp.thr2);  // each wave's bound holds for the row: take the tightest
     const bool live = wp.S > 0.f;
     float dl = 0.f, f = 0.f;
     if (live) partial_scale(wp.m, m, dl, f);

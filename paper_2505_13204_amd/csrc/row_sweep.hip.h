@@ -155,9 +155,15 @@ __device__ __forceinline__ float accumulate(LaneAcc& a, const float (&z)[N], int
         const float ex = __builtin_amdgcn_exp2f(d2);
         a.s[e % kNumAcc] += ex;
         a.t[e % kNumAcc] = fmaf(d2, ex, a.t[e % kNumAcc]);
-        if (COUNT) {
-            if (UNIFORM) a.cnt_u += (unsigned)__popcll(__ballot(z[e] > zcmp));
-            else a.cnt_l += (z[e] > zcmp) ? 1u : 0u;
+        if (COUNT && !UNIFORM) a.cnt_l += (z[e] > zcmp) ? 1u : 0u;
+    }
+    if (COUNT && UNIFORM) {
+        // Rank of the prompt's next token: elements above it, counted wave-wide.  Where that token is the row's
+        // greedy pick or close to it (most prompt positions), almost no chunk holds such an element: one test of
+        // the chunk maxima skips the per-element count for the whole wave.
+        if (__ballot(cmax > zcmp) != 0ull) {
+#pragma unroll
+            for (int e = 0; e < N; ++e) a.cnt_u += (unsigned)__popcll(__ballot(z[e] > zcmp));
         }
     }
     return cmax;
@@ -465,17 +471,8 @@ __device__ __forceinline__ bool process_wave(const SweepParams& p, const SegShap
     else sweep_lane<DT, CLAMP, ALIGN && COUNT, ALIGN, BLOCK, U, EXACT>(a, rs, tid, zcmp, want_cand && p.cm_enabled, cm_lane);
 
     // ---- wave maximum, and a lower bound on the c-th largest logit of the wave's share ----
-    float G = a.vmax;  // becomes the maximum of this lane's 4-lane group
-    float m;
-    if constexpr (RING > 0) {
-        m = wave_max_dpp(a.vmax);
-    } else {
-        G = fmaxf(G, __shfl_xor(G, 1));
-        G = fmaxf(G, __shfl_xor(G, 2));
-        m = G;
-#pragma unroll
-        for (int o = 4; o < 64; o <<= 1) m = fmaxf(m, __shfl_xor(m, o));
-    }
+    const float G = quad_max(a.vmax);  // the maximum of this lane's 4-lane group
+    const float m = wave_max(a.vmax);
     float thr2 = -INFINITY;
     if (ALIGN && want_cand && znext < m) {   // the same in every lane
         // The 16 group maxima are 16 distinct elements, so the c-th largest of them (c <= 8) bounds the
@@ -501,8 +498,8 @@ __device__ __forceinline__ bool process_wave(const SweepParams& p, const SegShap
     const float tsum = (a.t[0] + a.t[1]) + (a.t[2] + a.t[3]);
     const float dlt = (a.r2 - M2) - res;
     const float f = __builtin_amdgcn_exp2f(dlt);
-    const float S = RING > 0 ? wave_sum_dpp(ssum * f) : wave_sum(ssum * f);
-    const float T = RING > 0 ? wave_sum_dpp((tsum + dlt * ssum) * f) : wave_sum((tsum + dlt * ssum) * f);
+    const float S = wave_sum(ssum * f);
+    const float T = wave_sum((tsum + dlt * ssum) * f);
     if (!CLAMP) {
         if (!(S > 0.f) || !(S < INFINITY) || T != T) return false;
     }
@@ -516,7 +513,7 @@ __device__ __forceinline__ bool process_wave(const SweepParams& p, const SegShap
         for (int e = EPV - 1; e >= 0; --e) off = zb[e] == m ? e : off;
         own = a.code + off;
     }
-    const int code = RING > 0 ? wave_min_dpp(own) : wave_min(own);
+    const int code = wave_min(own);
     unsigned cnt = 0;
     if (ALIGN && COUNT) cnt = a.cnt_u + wave_sum(a.cnt_l);
 

@@ -33,12 +33,8 @@ __global__ __launch_bounds__(kFinishBlock) void row_kth_kernel(RowKthParams q)
     WavePartial wp;
     wp.m = -INFINITY; wp.S = 0.f; wp.T = 0.f; wp.code = 0x7fffffff; wp.cnt = 0; wp.nlist = 0; wp.thr2 = -INFINITY;
     if (lane < np) wp = p.partials[row * np + lane];
-    float m = wp.m, thr2 = wp.thr2;
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        m = fmaxf(m, __shfl_xor(m, o));
-        thr2 = fmaxf(thr2, __shfl_xor(thr2, o));
-    }
+    const float m = wave_max(wp.m);
+    float thr2 = wave_max(wp.thr2);
     const int code = wave_min(wp.S > 0.f && wp.m == m ? wp.code : 0x7fffffff);
     const int64_t off = (row / q.rows_per_seq) * q.seq_stride + (row % q.rows_per_seq) * p.row_stride;
     const RowShape rs = row_shape<DT>(p.logits, off, V);
