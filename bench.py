@@ -650,7 +650,7 @@ def bench_tree(args, w, dev):
             return {k: v.cpu().numpy() for k, v in out.items() if v is not None and k != "workspace"}
 
     step_bytes = w.B * N * w.V * elt
-    max_steps_resident = max(1, min(w.steps, int(24 * 2 ** 30 // step_bytes)))
+    max_steps_resident = max(1, min(w.steps, int(96 * 2 ** 30 // step_bytes)))   # room for max_nodes rows per tree is held, a tree uses a few of them
     rec = Recorder()
     trace = harness.decode_tree(synth.scaled(w, steps=max_steps_resident), rec, streams, extras_h, n_extras_h,
                                 max_nodes=N)

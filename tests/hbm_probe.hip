@@ -1,7 +1,9 @@
-// hbm_probe: plain copy and read kernels of known size, timed with HIP events.
+// hbm_probe: plain copy and read kernels of known size and a plain arithmetic kernel of known instruction count,
+// timed with HIP events.
 // Two uses: (1) the practical HBM ceiling of this GPU, to put the row sweep's GB/s in context;
 // (2) a reference dispatch of known byte count for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE
-// counters (run it under `rocprofv3 --pmc FETCH_SIZE` and compare with the bytes printed here).
+// counters (run it under `rocprofv3 --pmc FETCH_SIZE` and compare with the bytes printed here);
+// (3) the vector-ALU issue rate this GPU sustains, the practical ceiling for the one ALU-bound kernel.
 //
 // Measurement tool, not part of the library: build with
 //   hipcc -O3 -std=c++17 --offload-arch=gfx950 -o tests/hbm_probe tests/hbm_probe.hip
@@ -51,6 +53,24 @@ __global__ __launch_bounds__(256) void probe_read_nt_kernel(const u32x4* __restr
     if (acc == 0x12345678u) sink[0] = acc;
 }
 
+// Vector-ALU issue rate: every lane runs `iters` rounds of 16 independent fused multiply-adds (full-rate fp32
+// instructions, no memory access).  wave instructions = waves x iters x 16.
+__global__ __launch_bounds__(256) void probe_valu_kernel(float* sink, int iters, float seed)
+{
+    float a[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) a[i] = seed + (float)(threadIdx.x + i);
+    const float m = 1.0000001f, c = 1e-7f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) a[i] = __builtin_fmaf(a[i], m, c);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s += a[i];
+    if (s == 12345.678f) sink[0] = s;   // practically never: keeps the arithmetic alive
+}
+
 int main(int argc, char** argv)
 {
     const size_t mib = argc > 1 ? (size_t)atoll(argv[1]) : 2048;
@@ -95,6 +115,18 @@ int main(int argc, char** argv)
     CHECK(hipEventElapsedTime(&ms, e0, e1));
     printf("read, non-temporal loads: %zu B read per launch, %.1f us, %.1f GB/s\n", bytes, ms * 1e3 / reps,
            bytes / (ms * 1e-3 / reps) / 1e9);
+    {   // vector-ALU issue rate with every SIMD holding 8 waves
+        const int iters = 4096, wgs = prop.multiProcessorCount * 8;
+        hipLaunchKernelGGL(probe_valu_kernel, dim3(wgs), dim3(256), 0, 0, (float*)sink, iters, 1.0f);
+        CHECK(hipEventRecord(e0));
+        for (int r = 0; r < reps; ++r) hipLaunchKernelGGL(probe_valu_kernel, dim3(wgs), dim3(256), 0, 0, (float*)sink, iters, 1.0f);
+        CHECK(hipEventRecord(e1));
+        CHECK(hipEventSynchronize(e1));
+        CHECK(hipEventElapsedTime(&ms, e0, e1));
+        const double insts = (double)wgs * 4.0 * iters * 16.0;
+        printf("valu: %.0f wave instructions (fma) per launch, %.1f us, %.1f G wave instructions/s = %.1f TFLOP/s fp32\n", insts,
+               ms * 1e3 / reps, insts / (ms * 1e-3 / reps) / 1e9, insts * 128.0 / (ms * 1e-3 / reps) / 1e12);
+    }
     CHECK(hipDeviceSynchronize());
     return 0;
 }
