@@ -437,24 +437,31 @@ def main():
     ms_per_step_instrumented = (time.perf_counter() - ti0) * 1e3 / K
     draws = None
     if mode == aasd.EXTRAS_GUMBEL:
-        # The draw kernel is bound by vector-instruction issue.  Its instruction count per token comes from a rocprofv3
-        # --pmc run of this command (profiles/gumbel_extras_counters.txt: SQ_INSTS_VALU, wave instructions, and the shader
-        # clock that the same run measured); a wave instruction occupies a SIMD's 16 lanes for 4 cycles, so the chip issues
-        # at most 256 CUs x 4 SIMDs x clock / 4 of them per second.
+        # The draw kernel is bound by the vector ALUs.  A rocprofv3 --pmc run of this command (profiles/
+        # gumbel_extras_counters.txt) gives, per launch: SQ_ACTIVE_INST_VALU (time the vector ALUs spend on instructions, in
+        # units of 4 cycles, summed over the SIMDs), SQ_INSTS_VALU (wave instructions) and GRBM_GUI_ACTIVE (cycles, summed
+        # over the 8 dies: the shader clock of that run).  Busy cycles scale with the tokens drawn; the cycles available are
+        # 256 CUs x 4 SIMDs x clock x this run's kernel time.  Waves of one SIMD overlap the end of one instruction with
+        # the start of the next, so the counter can exceed the cycles by a few percent: frac is capped at 1, frac_raw is not.
         draw_ms = float(np.mean([hip_elapsed(kev[i][4], kev[i][5]) for i in range(K)]))
         n_mis = int(align_out["misaligned"].sum().item())
         tokens = n_mis * w.V
         draws = {"kernel": "aasd::gumbel_extras_kernel", "rows_drawn": n_mis, "tokens": tokens, "kernel_ms": round(draw_ms, 4),
                  "Gtokens/s": round(tokens / (draw_ms * 1e-3) / 1e9, 1), "roofline": None}
         cnt = read_traffic(os.path.join(ROOT, "profiles", "gumbel_extras_counters.txt"))
-        if cnt.get("kernel_source_sha") == kernel_source_sha() and f"{w.name}.gumbel.valu_wave_insts" in cnt:
-            insts_per_token = float(cnt[f"{w.name}.gumbel.valu_wave_insts"]) / float(cnt[f"{w.name}.gumbel.tokens"])
-            clock_ghz = float(cnt.get(f"{w.name}.gumbel.shader_clock_ghz", 2.4))
-            peak = 256 * 4 * clock_ghz / 4          # G wave instructions per second
-            ach = tokens * insts_per_token / (draw_ms * 1e-3) / 1e9
-            draws["roofline"] = {"bound": "alu", "achieved": round(ach, 1), "peak": round(peak, 1), "unit": "G wave-instructions/s",
-                                 "frac": round(ach / peak, 4), "wave_insts_per_token": round(insts_per_token, 4),
-                                 "shader_clock_ghz": clock_ghz, "source": "profiles/gumbel_extras_counters.txt"}
+        if cnt.get("kernel_source_sha") == kernel_source_sha() and f"{w.name}.gumbel.valu_active_quadcycles" in cnt:
+            g = lambda k: float(cnt[f"{w.name}.gumbel.{k}"])
+            scale = tokens / g("tokens")
+            clock_ghz = g("shader_clock_ghz")
+            busy = g("valu_active_quadcycles") * 4 * scale              # SIMD-cycles of vector-ALU work per launch
+            ach = busy / (draw_ms * 1e-3) / 1e9
+            peak = 256 * 4 * clock_ghz                                  # G SIMD-cycles per second
+            draws["roofline"] = {"bound": "alu", "achieved": round(ach, 1), "peak": round(peak, 1),
+                                 "unit": "G SIMD-cycles/s of vector-ALU work", "frac": round(min(1.0, ach / peak), 4),
+                                 "frac_raw": round(ach / peak, 4), "shader_clock_ghz": clock_ghz,
+                                 "wave_insts_per_token": round(g("valu_wave_insts") / g("tokens"), 4),
+                                 "G_wave_insts/s": round(g("valu_wave_insts") * scale / (draw_ms * 1e-3) / 1e9, 1),
+                                 "source": "profiles/gumbel_extras_counters.txt"}
         else:
             draws["roofline_note"] = "no instruction counters under profiles/ for the kernel sources built now"
     align_ms = float(np.mean([ev[i][0].elapsed_time(ev[i][1]) for i in range(K)]))
