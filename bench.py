@@ -165,7 +165,7 @@ def time_steps(torch, fn, n, reps=3):
     return eager, graph_us
 
 
-def per_step_block(torch, np, aasd, label, logits_steps, tokens, lens, plens, w, note=""):
+def per_step_block(torch, np, aasd, label, logits_steps, tokens, lens, plens, w, note="", use_pool=False):
     """One decode step at its real shape: aasd_retrieve_drafts + aasd_verify (one-launch form) for the B sequences of a
     step, over per-step logits that rotate through more than the 256 MB Infinity Cache, so every step reads cold HBM.
     logits_steps: list of [B, R, V] tensors; tokens/lens/plens: per step [B, cap], [B], [B]."""
@@ -180,9 +180,28 @@ def per_step_block(torch, np, aasd, label, logits_steps, tokens, lens, plens, w,
     kw = dict(alpha=w.alpha, beta=w.beta, want_rows=False, want_tokens=False, want_near=True, workspace=ws)
     v = aasd.verify(logits_steps[0], r["drafts"], r["draft_len"], r["strict"], zeroed_workspace=True, **kw)
     v2 = aasd.verify(logits_steps[0], r["drafts"], r["draft_len"], r["strict"], **kw)
+    pool, pool_build_us = None, None
+    if use_pool:
+        # The persistent pool in place of the scan: built once over the longest context (timed: the cost at the end of
+        # prefill), then rebuilt at the first step's length; aasd_pool_step indexes what a step added and looks up.
+        # The step lengths ascend through the first pass over the buffers (real incremental updates); later passes
+        # look up at lengths that are indexed already.
+        pool = aasd.DraftPool(B, tokens[0].shape[1], w.n_min, w.n_max, dev)
+        pool.update(tokens[n - 1], lens[n - 1], reset=True)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            pool.update(tokens[n - 1], lens[n - 1], reset=True)
+        e1.record()
+        torch.cuda.synchronize()
+        pool_build_us = e0.elapsed_time(e1) * 1e3 / 10
+        pool.update(tokens[0], lens[0], reset=True)
 
     def step(i, one_launch=True, with_retrieve=True):
-        if with_retrieve:
+        if with_retrieve and pool is not None:
+            pool.step(tokens[i % n], lens[i % n], plens, w.k, w.C, out=r)
+        elif with_retrieve:
             aasd.retrieve_drafts(tokens[i % n], lens[i % n], plens, w.n_min, w.n_max, w.k, w.C, out=r)
         aasd.verify(logits_steps[i % n], r["drafts"], r["draft_len"], r["strict"], zeroed_workspace=one_launch,
                     out=v if one_launch else v2, **kw)
@@ -203,6 +222,8 @@ def per_step_block(torch, np, aasd, label, logits_steps, tokens, lens, plens, w,
     rnd = lambda x: None if x is None else round(x, 2)
     return {"shape": label, "sequences": B, "rows_per_step": B * R, "bytes_per_step": step_bytes,
             "rotating_step_buffers": n, "resident_MB": round(n * step_bytes / 1e6, 1),
+            "retrieval": "pool" if use_pool else "scan",
+            **({"pool_build_us": round(pool_build_us, 1), "pool_build_tokens": int(lens[n - 1].sum().item())} if use_pool else {}),
             "retrieve_plus_verify_us": {"eager": rnd(eager), "hip_graph": rnd(graph_us)},
             "verify_one_launch_us": {"eager": rnd(v_eager), "hip_graph": rnd(v_graph), "kernel_event_median": rnd(kern)},
             "verify_two_launches_us": {"eager": rnd(t_eager), "hip_graph": rnd(t_graph)},
@@ -517,7 +538,7 @@ def main():
             torch, np, aasd, f"{w.name}: B={w.B}, R={w.R}, V={w.V}",
             [verify_logits[s * w.B:(s + 1) * w.B] for s in range(n_own)],
             [tokens_b[s * w.B:(s + 1) * w.B] for s in range(n_own)], [len_b[s * w.B:(s + 1) * w.B] for s in range(n_own)],
-            plen_b[:w.B], w)
+            plen_b[:w.B], w, use_pool=use_pool)
         if n_own * step_bytes < 300e6:
             own["note"] += "; CAUTION: fewer step buffers resident than the 256 MB Infinity Cache holds"
         per_step.append(own)
@@ -537,7 +558,7 @@ def main():
             per_step.append(per_step_block(
                 torch, np, aasd, f"batched_serving: B={w4.B}, R={w4.R}, V={w4.V}", rec4.logits, [toks4] * S4,
                 [torch.from_numpy(st.length.astype(np.int32)).to(dev) for st in tr4.steps],
-                torch.full((w4.B,), w4.L, dtype=torch.int32, device=dev), w4))
+                torch.full((w4.B,), w4.L, dtype=torch.int32, device=dev), w4, use_pool=use_pool))
             rec4.logits = None
 
     # ---------------------------------------------------------------- CPU oracle on a bounded sample (context)

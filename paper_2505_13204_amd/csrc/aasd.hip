@@ -286,7 +286,7 @@ bool pool_layout(int32_t B, int32_t capacity, int32_t n_min, int32_t n_max, aasd
     if (B < 0 || capacity < 1 || capacity > kMaxPoolCapacity || n_min < 1 || n_min > n_max || n_max > AASD_MAX_KEY) return false;
     const int NL = n_max - n_min + 1;
     int lg = 6;
-    while (((int64_t)1 << lg) < 2 * ((int64_t)capacity + 1)) ++lg;   // load factor at most one half
+    while (lg < 25 && ((int64_t)1 << lg) < 2 * ((int64_t)capacity + 1)) ++lg;   // load factor at most one half; a bucket has at most 25 bits
     lay.B = B; lay.capacity = capacity; lay.n_min = n_min; lay.n_max = n_max; lay.log2_table = lg;
     lay.counters = 0;
     lay.tables = align16((size_t)B * NL * sizeof(int32_t));
@@ -720,7 +720,7 @@ int aasd_pool_update(void* pool, size_t pool_bytes, int32_t B, int32_t capacity,
     q.pool = (char*)pool; q.lay = lay; q.tokens = tokens; q.tok_stride = tok_stride; q.len = len; q.reset = reset ? 1 : 0;
     const int64_t grid = (int64_t)B * (n_max - n_min + 1);
     if (grid > kMaxUnitsPerLaunch) return fail(AASD_ERR_UNSUPPORTED, "pool_update: too many sequences for one launch");
-    hipLaunchKernelGGL(aasd::pool_update_kernel, dim3((unsigned)grid), dim3(aasd::kWave), 0, (hipStream_t)stream, q);
+    hipLaunchKernelGGL(aasd::pool_build_kernel, dim3((unsigned)grid), dim3(aasd::kPoolBuildBlock), 0, (hipStream_t)stream, q);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(AASD_ERR_LAUNCH, "pool_update launch failed: %s", hipGetErrorString(e));
     return AASD_OK;

@@ -37,7 +37,8 @@ struct PoolUpdateParams {
     int32_t reset;
 };
 
-// One wave per (sequence, key length).  Positions are taken 64 at a time in ascending order: a lane links its
+// One wave per (sequence, key length), for the few new positions of a decode step (and as the general case
+// of any range).  Positions are taken 64 at a time in ascending order: a lane links its
 // position to the nearest lower lane of the batch with the same bucket, else to the table's head as it was
 // before the batch; the highest lane of each bucket becomes the new head.  The batch's stores are fenced
 // before the next batch reads the heads (the reads bypass the vector cache).
@@ -87,11 +88,105 @@ __device__ __forceinline__ void pool_update_wave(const PoolUpdateParams& q, int 
     if (lane == 0) *counter = (len + 1 > start) ? len + 1 : start;
 }
 
-__global__ __launch_bounds__(kWave) void pool_update_kernel(PoolUpdateParams q)
+constexpr int kPoolBuildWaves = 16;                         // waves per workgroup of the build kernel
+constexpr int kPoolBuildBlock = kPoolBuildWaves * kWave;
+constexpr int kPoolBuildTile = 8192;                        // positions staged in LDS at a time
+constexpr int kPoolBuildDepth = 32;                         // batches whose head exchanges are in flight together
+constexpr uint32_t kPoolBucketMask = (1u << 25) - 1u;       // a bucket has at most 25 bits (capacity <= 2^24)
+
+// Many positions at once (the build over a prompt): a workgroup per (sequence, key length), a tile of positions
+// at a time, in two phases.  Phase 1, all waves, a batch of 64 consecutive positions each: the bucket of every
+// position; a lane links its position to the nearest lower lane of the batch with the same bucket; the lowest
+// and the highest lane of every bucket are noted in LDS (with the bucket: flag and lane in the 7 spare bits).
+// Phase 2, the first wave, batch by batch in ascending order: the highest lane of a bucket exchanges the head for
+// its position, and what the exchange returns (the head before the batch) becomes the link of the bucket's
+// lowest lane.  All exchanges come from one wave in program order, so the chains descend without a fence between
+// batches, and the exchanges of 32 batches are in flight together.  A decode step's few new positions take the
+// one-wave path above.
+__global__ __launch_bounds__(kPoolBuildBlock) void pool_build_kernel(PoolUpdateParams q)
 {
-    const int NL = q.lay.n_max - q.lay.n_min + 1;
-    const int b = blockIdx.x / NL;
-    pool_update_wave(q, b, blockIdx.x - b * NL, threadIdx.x);
+    __shared__ uint32_t linfo[kPoolBuildTile];
+    __shared__ int32_t ltok[kPoolBuildTile + AASD_MAX_KEY];   // ltok[i] = tok[t0 - AASD_MAX_KEY + i]
+    const PoolLayout& L = q.lay;
+    const int NL = L.n_max - L.n_min + 1;
+    const int b = blockIdx.x / NL, nl = blockIdx.x - b * NL;
+    const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
+    const int n = L.n_min + nl;
+    int32_t* counter = (int32_t*)(q.pool + L.counters) + (size_t)b * NL + nl;
+    int32_t* head = (int32_t*)(q.pool + L.tables + ((size_t)b * NL + nl) * L.table_stride);
+    int32_t* prev = head + ((size_t)1 << L.log2_table);
+    const int32_t* tok = q.tokens + (int64_t)b * q.tok_stride;
+    int len = q.len[b];
+    if (len < 0 || (int64_t)len > q.tok_stride) len = 0;
+    if (len > L.capacity) len = L.capacity;
+
+    int start = n;
+    if (!q.reset) {
+        start = *counter;
+        if (start < n) start = n;
+        if (len + 1 - start <= kWave) {
+            if (wid == 0) pool_update_wave(q, b, nl, lane);
+            return;
+        }
+    } else {
+        const int T = 1 << L.log2_table;
+        for (int i = tid; i < T; i += kPoolBuildBlock) head[i] = -1;
+        __threadfence();
+    }
+    __syncthreads();    // the table is empty; every wave has read the counter before it is written below
+
+    for (int t0 = start; t0 <= len; t0 += kPoolBuildTile) {
+        const int tile_n = min(kPoolBuildTile, len + 1 - t0);
+        // the tile's tokens and the AASD_MAX_KEY before them, all loads in flight together (start >= n, so every
+        // window of the tile lies at or after position 0)
+        for (int i = tid; i < tile_n + AASD_MAX_KEY; i += kPoolBuildBlock) {
+            const int src = t0 - AASD_MAX_KEY + i;
+            ltok[i] = (src >= 0 && src < len) ? tok[src] : 0;
+        }
+        __syncthreads();
+        // phase 1
+        for (int g0 = wid * kWave; g0 < tile_n; g0 += kPoolBuildBlock) {
+            const int i = g0 + lane;
+            const bool have = i < tile_n;
+            const uint32_t bucket = have ? pool_bucket(ltok, AASD_MAX_KEY + i, n, L.log2_table) : 0xFFFFFFFFu;
+            unsigned long long same = 0;
+#pragma unroll
+            for (int j = 0; j < kWave; ++j) {
+                const uint32_t bj = (uint32_t)__builtin_amdgcn_readlane((int)bucket, j);
+                if (bj == bucket) same |= 1ull << j;
+            }
+            if (have) {
+                const unsigned long long lower = same & ((1ull << lane) - 1ull);
+                const bool top = (same >> lane) == 1ull;
+                const int low = __ffsll((long long)same) - 1;
+                if (lower) prev[t0 + i] = t0 + g0 + (63 - __clzll((long long)lower));
+                linfo[i] = bucket | ((uint32_t)low << 25) | (top ? 0x80000000u : 0u);
+            }
+        }
+        __syncthreads();
+        // phase 2
+        if (wid == 0) {
+            for (int g0 = 0; g0 < tile_n; g0 += kWave * kPoolBuildDepth) {
+                int old[kPoolBuildDepth];
+#pragma unroll
+                for (int d = 0; d < kPoolBuildDepth; ++d) {
+                    const int i = g0 + d * kWave + lane;
+                    const uint32_t v = i < tile_n ? linfo[i] : 0u;
+                    old[d] = -1;
+                    if (v & 0x80000000u)
+                        old[d] = __hip_atomic_exchange(&head[v & kPoolBucketMask], t0 + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+#pragma unroll
+                for (int d = 0; d < kPoolBuildDepth; ++d) {
+                    const int i = g0 + d * kWave + lane;
+                    const uint32_t v = i < tile_n ? linfo[i] : 0u;
+                    if (v & 0x80000000u) prev[t0 + g0 + d * kWave + (int)((v >> 25) & 63u)] = old[d];
+                }
+            }
+        }
+        __syncthreads();   // the tile's notes are no longer read
+    }
+    if (tid == 0) *counter = (len + 1 > start) ? len + 1 : start;
 }
 
 struct PoolRetrieveParams {

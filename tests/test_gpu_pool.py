@@ -53,6 +53,33 @@ def test_pool_full_build_random_small_alphabet(n_min, n_max, k, C, cap):
     _check(pool, toks2_d, toks2, lens, plens, n_min, n_max, k, C)
 
 
+@pytest.mark.parametrize("alphabet", [2, 6, 5000])
+def test_pool_build_in_pieces_and_many_keys(alphabet):
+    """The build path taken for many positions at once (tiles of 8192, batches of 64): from empty tables, continued
+    without a reset across a tile boundary, then by a decode step's few tokens.  After each, lookups at 24 different
+    context lengths (so 24 different keys per sequence and key length) with C = 32 walk many chains to depth 32."""
+    rng = np.random.default_rng(alphabet)
+    B, cap, n_min, n_max, k, C = 5, 20000, 1, 5, 4, 32
+    toks = rng.integers(0, alphabet, size=(B, cap)).astype(np.int32)
+    for b in range(B):    # long repeats, so that the longest keys have several occurrences
+        for _ in range(30):
+            ln = int(rng.integers(5, 200))
+            s = int(rng.integers(0, cap - 2 * ln))
+            d = int(rng.integers(s + ln, cap - ln + 1))
+            toks[b, d:d + ln] = toks[b, s:s + ln]
+    toks_d = _t(toks, torch.int32)
+    pool = aasd.DraftPool(B, cap, n_min, n_max, DEV)
+    stages = [np.array([3000, 64, 8191, 9000, 70], np.int32), np.array([12000, 8300, 8192, 19999, 71], np.int32),
+              np.array([12040, 8364, 8200, 20000, 20000], np.int32)]
+    for si, lens in enumerate(stages):
+        pool.update(toks_d, _t(lens, torch.int32), reset=(si == 0))
+        for _ in range(24):
+            at = np.maximum(1, (lens * rng.uniform(0.05, 1.0, size=B)).astype(np.int32))
+            at = np.minimum(at, lens)
+            _check(pool, toks_d, toks, at, np.minimum(at, 2500), n_min, n_max, k, C)
+        _check(pool, toks_d, toks, lens, np.minimum(lens, 2500), n_min, n_max, k, C)
+
+
 def test_pool_incremental_updates_with_extras():
     """Prompt indexed once, then 60 steps that append 1..9 tokens each; after every update the pool answers
     like the oracle on the context of that step.  Updates cross the 64-position batches of the insert kernel."""
