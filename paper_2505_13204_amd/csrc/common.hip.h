@@ -104,6 +104,14 @@ __device__ __forceinline__ float wave_max(float v)
     v = fmaxf(v, dpp_move<kDppMirror>(v));
     return fmaxf(fmaxf(lane_value(v, 0), lane_value(v, 16)), fmaxf(lane_value(v, 32), lane_value(v, 48)));
 }
+__device__ __forceinline__ int wave_max(int v)
+{
+    v = max(v, dpp_move<kDppSwap1>(v));
+    v = max(v, dpp_move<kDppSwap2>(v));
+    v = max(v, dpp_move<kDppHalfMirror>(v));
+    v = max(v, dpp_move<kDppMirror>(v));
+    return max(max(lane_value(v, 0), lane_value(v, 16)), max(lane_value(v, 32), lane_value(v, 48)));
+}
 __device__ __forceinline__ int wave_min(int v)
 {
     v = min(v, dpp_move<kDppSwap1>(v));

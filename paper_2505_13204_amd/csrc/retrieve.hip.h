@@ -93,13 +93,22 @@ __global__ __launch_bounds__(BLOCK) void retrieve_kernel(RetrieveParams p)
     const int b = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
     const int32_t* tok = p.tokens + (int64_t)b * p.tok_stride;
+    // A buffer that fits one tile is staged before its length is known (the loads of the length and of the tokens
+    // are in flight together; positions at and after the length are never looked at), and the suffix and the
+    // continuations are then read from LDS instead of through further dependent loads from memory.  Only where few
+    // sequences are launched and latency is what counts: with many, reading whole buffers would add traffic.
+    const bool one_tile = BLOCK == kRetrieveBlock && p.tok_stride <= (int64_t)p.tile;
+    if (one_tile)
+        for (int i = tid; i < (int)p.tok_stride + AASD_MAX_KEY; i += BLOCK) ltok[i] = i >= AASD_MAX_KEY ? tok[i - AASD_MAX_KEY] : 0;
     int len = p.len[b];
     if (len < 0 || (int64_t)len > p.tok_stride) len = 0;
     const int plen = p.prompt_len[b];
     const int n_min = p.n_min, C = p.C, k = p.k;
     const int n_cap = min(p.n_max, len - 1);  // a key must be shorter than the context
 
-    if (tid < AASD_MAX_KEY) suffix[tid] = (len - 1 - tid >= 0) ? tok[len - 1 - tid] : 0;
+    if (one_tile) __syncthreads();
+    if (tid < AASD_MAX_KEY)
+        suffix[tid] = (len - 1 - tid >= 0) ? (one_tile ? ltok[len - 1 - tid + AASD_MAX_KEY] : tok[len - 1 - tid]) : 0;
     if (tid == 0) s_best = 0;
     for (int i = tid; i < kRetrieveTileSlots; i += BLOCK) tile_best[i] = 0;
     __syncthreads();
@@ -120,8 +129,10 @@ __global__ __launch_bounds__(BLOCK) void retrieve_kernel(RetrieveParams p)
             const int tlo = t * tile;
             const int thi = min(tlo + tile, len);
             const int first = tlo - AASD_MAX_KEY;
-            for (int i = tid; i < thi - first; i += BLOCK) ltok[i] = (first + i >= 0) ? tok[first + i] : 0;
-            __syncthreads();
+            if (!one_tile) {
+                for (int i = tid; i < thi - first; i += BLOCK) ltok[i] = (first + i >= 0) ? tok[first + i] : 0;
+                __syncthreads();
+            }
             int best = 0;
             const int pstart = tlo + tid * run;
             uint32_t h = 0;
@@ -158,13 +169,11 @@ __global__ __launch_bounds__(BLOCK) void retrieve_kernel(RetrieveParams p)
             int tb = stage_and_match(t);
             best = max(best, tb);
             if (t < kRetrieveTileSlots) {
-#pragma unroll
-                for (int o = 32; o > 0; o >>= 1) tb = max(tb, __shfl_xor(tb, o));
+                tb = wave_max(tb);
                 if (lane == 0 && tb > 0) atomicMax(&tile_best[t], tb);
             }
         }
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) best = max(best, __shfl_xor(best, o));
+        best = wave_max(best);
         if (lane == 0 && best > 0) atomicMax(&s_best, best);
         __syncthreads();
         n_star = s_best;
@@ -190,16 +199,19 @@ __global__ __launch_bounds__(BLOCK) void retrieve_kernel(RetrieveParams p)
                     const int pp = pstart + q;
                     if (pp < thi && ell[pp - tlo] >= n_star) ++mine;
                 }
-                // hits in threads with a higher index: suffix sum over the lanes, then over the waves
-                int incl = mine;
+                // hits in threads with a higher index: over the lanes bit by bit of the count (a count is below 64:
+                // ballots and population counts, no trips through LDS), then over the waves
+                const unsigned long long above = lane == 63 ? 0ull : (~0ull << (lane + 1));
+                int later = 0, wave_total = 0;
 #pragma unroll
-                for (int o = 1; o < 64; o <<= 1) {
-                    const int dn = __shfl_down(incl, o);
-                    if (lane + o < 64) incl += dn;
+                for (int bit = 0; bit < 6; ++bit) {
+                    const unsigned long long has = __ballot((mine >> bit) & 1);
+                    later += __popcll(has & above) << bit;
+                    wave_total += __popcll(has) << bit;
                 }
-                if (lane == 0) wave_cnt[wid] = incl;
+                if (lane == 0) wave_cnt[wid] = wave_total;
                 __syncthreads();
-                int later = incl - mine, total = 0;
+                int total = 0;
 #pragma unroll
                 for (int w = 0; w < NW; ++w) {
                     const int cw = wave_cnt[w];
@@ -218,7 +230,7 @@ __global__ __launch_bounds__(BLOCK) void retrieve_kernel(RetrieveParams p)
     }
     __syncthreads();
 
-    write_candidates<BLOCK>(p, b, tok, len, plen, pos, min(count, C), n_star, tid);
+    write_candidates<BLOCK>(p, b, one_tile ? ltok + AASD_MAX_KEY : tok, len, plen, pos, min(count, C), n_star, tid);
 }
 
 }  // namespace aasd
