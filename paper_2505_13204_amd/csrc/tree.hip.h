@@ -181,23 +181,70 @@ struct VerifyTreeParams {
     int32_t npart;
 };
 
-// One workgroup per sequence, a thread per node.  Node i is decided against the row of its parent
+// The decisions of one tree by one workgroup of NT threads.  Node i is decided against the row of its parent
 // (Eq. 4-6); it is accepted iff it and all its ancestors pass; the deepest accepted node wins.
-constexpr int kVerifyTreeBlock = 1024;  // many lanes so that the partials of a large tree arrive in few rounds of loads
+// (A one-launch form of sweep and decisions, as aasd_verify has, was built for trees too and measured no faster
+// than the two kernels - here the arrival protocol costs what the second launch costs - so there is none.)
+struct VerifyTreeShared {
+    float4 stats[AASD_MAX_TREE_NODES];   // per row {max logit, S, H, bits of argmax}
+    int par[AASD_MAX_TREE_NODES];
+    unsigned char pass[AASD_MAX_TREE_NODES];
+    unsigned char near[AASD_MAX_TREE_NODES];
+    unsigned red_key[16], red_near[16];
+};
 
-template <int DT>
-__global__ __launch_bounds__(kVerifyTreeBlock) void verify_tree_kernel(VerifyTreeParams p)
+// All-reduce over the lane's aligned group of G lanes (G a power of two, the same in every lane): inside a row of
+// 16 lanes through the vector ALU's cross-lane moves, beyond it through LDS permutes.  The order of combination is fixed.
+template <class T, class OP>
+__device__ __forceinline__ T group_reduce(T v, int G, OP op)
 {
-    __shared__ float4 stats[AASD_MAX_TREE_NODES];  // per row {max logit, S, H, bits of argmax}
-    __shared__ int par_s[AASD_MAX_TREE_NODES];
-    __shared__ unsigned char pass_s[AASD_MAX_TREE_NODES];
-    __shared__ unsigned red_key[kVerifyTreeBlock / kWave], red_near[kVerifyTreeBlock / kWave];
+    if (G > 1) v = op(v, dpp_move<kDppSwap1>(v));
+    if (G > 2) v = op(v, dpp_move<kDppSwap2>(v));
+    if (G > 4) v = op(v, dpp_move<kDppHalfMirror>(v));
+    if (G > 8) v = op(v, dpp_move<kDppMirror>(v));
+    for (int o = 16; o < G; o <<= 1) v = op(v, __shfl_xor(v, o));
+    return v;
+}
 
-    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
+template <int DT, int NT>
+__device__ __forceinline__ void verify_tree_block(const VerifyTreeParams& p, int b, VerifyTreeShared& sh)
+{
+    static_assert(NT / kWave <= 16, "one reduction slot per wave");
+    constexpr int kPer = (AASD_MAX_TREE_NODES + NT - 1) / NT;   // nodes per thread
+    const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
     const int N = p.N;
+
+    // Everything that does not depend on another load is asked for at once: the node count, and every node's
+    // parent, token and flag (slots at or beyond the count are read and ignored).
+    int par_r[kPer], tok_r[kPer];
+    unsigned char st_r[kPer];
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) {
+        const int i = tid + j * NT;
+        par_r[j] = -1; tok_r[j] = -1; st_r[j] = 0;
+        if (i >= 1 && i < N) {
+            const size_t bi = (size_t)b * N + i;
+            par_r[j] = p.node_parent[bi];
+            tok_r[j] = p.node_token[bi];
+            if (p.node_strict) st_r[j] = p.node_strict[bi];
+        }
+    }
     int n = p.n_nodes[b];
     n = n < 1 ? 1 : (n > N ? N : n);
-    for (int r = n + tid; r < N; r += kVerifyTreeBlock) {   // rows that are not in use
+
+    // the logit of every node's token in its parent's row: in flight while the row statistics are put together
+    float zt_r[kPer];
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) {
+        const int i = tid + j * NT;
+        if (i >= n || par_r[j] < 0 || par_r[j] >= i) par_r[j] = -1;   // parents precede their children
+        zt_r[j] = 0.f;
+        if (par_r[j] >= 0 && tok_r[j] >= 0 && tok_r[j] < p.V)
+            zt_r[j] = load_elt<DT>(p.logits, (int64_t)b * p.seq_stride + (int64_t)par_r[j] * p.row_stride + tok_r[j]);
+        if (i < N) sh.par[i] = par_r[j];
+    }
+
+    for (int r = n + tid; r < N; r += NT) {   // rows that are not in use
         const int64_t row = (int64_t)b * N + r;
         if (p.row_entropy) p.row_entropy[row] = 0.f;
         if (p.row_pmax) p.row_pmax[row] = 0.f;
@@ -208,7 +255,7 @@ __global__ __launch_bounds__(kVerifyTreeBlock) void verify_tree_kernel(VerifyTre
     {
         int G = 1;
         while (G < p.npart) G <<= 1;
-        const int rows_per_pass = kVerifyTreeBlock / G;
+        const int rows_per_pass = NT / G;
         const int sub = tid / G, s = tid - sub * G;
         for (int r0 = 0; r0 < n; r0 += rows_per_pass) {
             const int r = r0 + sub;
@@ -217,121 +264,117 @@ __global__ __launch_bounds__(kVerifyTreeBlock) void verify_tree_kernel(VerifyTre
             WavePartial wp;
             wp.m = -INFINITY; wp.S = 0.f; wp.T = 0.f; wp.code = 0x7fffffff;
             if (have_row && s < p.npart) wp = p.partials[row * p.npart + s];
-            float m = wp.m;
-            for (int o = 1; o < G; o <<= 1) m = fmaxf(m, __shfl_xor(m, o));
+            const float m = group_reduce(wp.m, G, [](float x, float y) { return fmaxf(x, y); });
             const bool live = wp.S > 0.f;
             float dl2 = 0.f, f = 0.f;
             if (live) partial_scale(wp.m, m, dl2, f);
-            float S = live ? wp.S * f : 0.f;
-            float T2 = live ? (wp.T + dl2 * wp.S) * f : 0.f;
-            int code = live && wp.m == m ? wp.code : 0x7fffffff;
-            for (int o = 1; o < G; o <<= 1) {
-                S += __shfl_xor(S, o);
-                T2 += __shfl_xor(T2, o);
-                code = min(code, __shfl_xor(code, o));
-            }
+            const float S = group_reduce(live ? wp.S * f : 0.f, G, [](float x, float y) { return x + y; });
+            const float T2 = group_reduce(live ? (wp.T + dl2 * wp.S) * f : 0.f, G, [](float x, float y) { return x + y; });
+            const int code = group_reduce(live && wp.m == m ? wp.code : 0x7fffffff, G, [](int x, int y) { return min(x, y); });
             if (have_row && s == 0) {
-                float H = 0.f, pmax = 0.f;
-                int am = -1;
-                {
+                int am = 0;
+                if ((unsigned)code < (unsigned)p.V) {
+                    am = code;    // the chunk that holds the maximum: the first element of it that attains it
                     const RowShape rs = row_shape<DT>(p.logits, (int64_t)b * p.seq_stride + (int64_t)r * p.row_stride, p.V);
-                    am = 0;
-                    if ((unsigned)code < (unsigned)p.V) {
-                        am = code;
-                        const int len = (code >= rs.head && code < rs.tail0) ? Elt<DT>::kPerVec : 1;
-                        for (int e = 0; e < len; ++e)
-                            if (load_elt<DT>(rs.base, code + e) == m) { am = code + e; break; }
-                    }
-                    H = entropy_from_sums(S, T2);
-                    pmax = 1.0f / S;
-                    stats[r] = make_float4(m, S, H, __int_as_float(am));
+                    const int len = (code >= rs.head && code < rs.tail0) ? Elt<DT>::kPerVec : 1;
+                    for (int e = 0; e < len; ++e)
+                        if (load_elt<DT>(rs.base, code + e) == m) { am = code + e; break; }
                 }
+                const float H = entropy_from_sums(S, T2);
+                const float pmax = 1.0f / S;
+                sh.stats[r] = make_float4(m, S, H, __int_as_float(am));
                 if (p.row_entropy) p.row_entropy[row] = H;
                 if (p.row_pmax) p.row_pmax[row] = pmax;
                 if (p.row_argmax) p.row_argmax[row] = am;
             }
         }
     }
-
-    // ---- per-node decision against the parent's row ----
-    const int i = tid;
-    const size_t bi = (size_t)b * N + (i < N ? i : 0);
-    int par = -1;
-    if (i >= 1 && i < n) {
-        par = p.node_parent[bi];
-        if (par < 0 || par >= i) par = -1;  // parents precede their children
-    }
-    if (i < N) par_s[i] = par;
     __syncthreads();
 
-    bool pass = false, near = false;
-    float pf = 0.f, df = 0.f;
-    if (par >= 0) {
-        const int t = p.node_token[bi];
-        const float4 st = stats[par];
-        const double m = (double)st.x, S = (double)st.y, H = (double)st.z;
-        const bool valid = t >= 0 && t < p.V;
-        float zt = 0.f;
-        if (valid) zt = load_elt<DT>(p.logits, (int64_t)b * p.seq_stride + (int64_t)par * p.row_stride + t);
-        const double pr = valid ? exp((double)zt - m) / S : 0.0;
-        const double Delta = 1.0 / S;                              // Eq. 6
-        const double thr = (double)p.alpha * H + (double)p.beta;   // Eq. 5
-        double delta;
-        if (p.flags & AASD_VERIFY_NO_CLAMP) {
-            delta = thr;
-            pass = valid && pr >= delta;
-        } else {
-            const bool is_strict = p.node_strict != nullptr && p.node_strict[bi] != 0;
-            delta = is_strict ? Delta : fmin(thr, Delta);
-            pass = valid && (pr >= delta || zt == st.x);           // Eq. 4; ties with the maximum pass
+    // ---- per-node decision against the parent's row ----
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) {
+        const int i = tid + j * NT;
+        if (i >= N) continue;
+        const size_t bi = (size_t)b * N + i;
+        const int par = par_r[j];
+        bool pass = false, near = false;
+        float pf = 0.f, df = 0.f;
+        if (par >= 0) {
+            const int t = tok_r[j];
+            const float4 st = sh.stats[par];
+            const double m = (double)st.x, S = (double)st.y, H = (double)st.z;
+            const bool valid = t >= 0 && t < p.V;
+            const float zt = zt_r[j];
+            const double pr = valid ? exp((double)zt - m) / S : 0.0;
+            const double Delta = 1.0 / S;                              // Eq. 6
+            const double thr = (double)p.alpha * H + (double)p.beta;   // Eq. 5
+            double delta;
+            if (p.flags & AASD_VERIFY_NO_CLAMP) {
+                delta = thr;
+                pass = valid && pr >= delta;
+            } else {
+                delta = st_r[j] ? Delta : fmin(thr, Delta);
+                pass = valid && (pr >= delta || zt == st.x);           // Eq. 4; ties with the maximum pass
+            }
+            near = fabs(pr - delta) < 1e-6;
+            pf = (float)pr;
+            df = (float)delta;
         }
-        near = fabs(pr - delta) < 1e-6;
-        pf = (float)pr;
-        df = (float)delta;
-    }
-    if (i < N) {
-        pass_s[i] = pass;
+        sh.pass[i] = pass;
+        sh.near[i] = near;
         if (p.node_p) p.node_p[bi] = pf;
         if (p.node_delta) p.node_delta[bi] = df;
     }
     __syncthreads();
 
     // ---- accepted iff the node and all its ancestors pass; depth by walking up (parents have smaller indices) ----
-    bool reached = par >= 0;  // all ancestors pass: the node is evaluated
-    int depth = 0;
-    if (par >= 0) {
-        depth = 1;
-        for (int a = par; a > 0; a = par_s[a]) {
-            reached = reached && pass_s[a];
+    int key = 0;
+    unsigned nr = 0u;
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) {
+        const int i = tid + j * NT;
+        const int par = par_r[j];
+        if (i >= N || par < 0) continue;
+        bool reached = true;  // all ancestors pass: the node is evaluated
+        int depth = 1;
+        for (int a = par; a > 0; a = sh.par[a]) {
+            reached = reached && sh.pass[a];
             ++depth;
         }
+        if (reached && sh.pass[i]) key = max(key, (depth << 16) | (0xffff - i));  // deepest, then lowest index
+        if (reached && sh.near[i]) ++nr;
     }
-    const bool ok = reached && pass;
-    unsigned key = ok ? ((unsigned)depth << 16) | (unsigned)(0xffff - i) : 0u;  // deepest, then lowest index
-    unsigned nr = (reached && near) ? 1u : 0u;
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        key = max(key, (unsigned)__shfl_xor((int)key, o));
-        nr += __shfl_xor(nr, o);
-    }
-    if (lane == 0) { red_key[wid] = key; red_near[wid] = nr; }
+    key = wave_max(key);
+    nr = wave_sum(nr);
+    if (lane == 0) { sh.red_key[wid] = (unsigned)key; sh.red_near[wid] = nr; }
     __syncthreads();
     if (tid == 0) {
         unsigned best_key = 0, near_total = 0;
-        for (int w = 0; w < kVerifyTreeBlock / kWave; ++w) { best_key = max(best_key, red_key[w]); near_total += red_near[w]; }
+        for (int w = 0; w < NT / kWave; ++w) { best_key = max(best_key, sh.red_key[w]); near_total += sh.red_near[w]; }
         const int best = best_key ? (int)(0xffff - (best_key & 0xffff)) : 0;
         const int best_depth = (int)(best_key >> 16);
         p.accept_len[b] = best_depth;
         p.best_node[b] = best;
-        p.next_token[b] = __float_as_int(stats[best].w);
+        p.next_token[b] = __float_as_int(sh.stats[best].w);
         if (p.near_count) p.near_count[b] = near_total;
         if (p.accept_path) {
             for (int d = 0; d < AASD_MAX_DRAFT; ++d) p.accept_path[(size_t)b * AASD_MAX_DRAFT + d] = -1;
             int d = best_depth;
-            for (int a = best; a > 0; a = par_s[a], --d)
+            for (int a = best; a > 0; a = sh.par[a], --d)
                 if (d >= 1 && d <= AASD_MAX_DRAFT) p.accept_path[(size_t)b * AASD_MAX_DRAFT + d - 1] = a;
         }
     }
+}
+
+// One workgroup per sequence; many lanes so that the partials of a large tree arrive in few rounds of loads.
+constexpr int kVerifyTreeBlock = 1024;
+
+template <int DT>
+__global__ __launch_bounds__(kVerifyTreeBlock) void verify_tree_kernel(VerifyTreeParams p)
+{
+    __shared__ VerifyTreeShared sh;
+    verify_tree_block<DT, kVerifyTreeBlock>(p, blockIdx.x, sh);
 }
 
 }  // namespace aasd

@@ -266,6 +266,34 @@ __device__ __forceinline__ bool arrive_is_last(unsigned* counter, unsigned expec
     return true;
 }
 
+// The partials of a workgroup's NW waves (in LDS) merged into one; called by the lanes of the first wave, the
+// result is complete in every lane.
+template <int NW>
+__device__ __forceinline__ WavePartial merge_wave_partials(const WavePartial* wave_part, int lane)
+{
+    WavePartial wp;
+    wp.m = -INFINITY; wp.S = 0.f; wp.T = 0.f; wp.code = 0x7fffffff;
+    if (lane < NW) wp = wave_part[lane];
+    float m = wp.m;
+#pragma unroll
+    for (int o = 1; o < NW; o <<= 1) m = fmaxf(m, __shfl_xor(m, o));
+    const bool live = wp.S > 0.f;
+    float dl2 = 0.f, f = 0.f;
+    if (live) partial_scale(wp.m, m, dl2, f);
+    float S = live ? wp.S * f : 0.f;
+    float T2 = live ? (wp.T + dl2 * wp.S) * f : 0.f;
+    int code = live && wp.m == m ? wp.code : 0x7fffffff;
+#pragma unroll
+    for (int o = 1; o < NW; o <<= 1) {
+        S += __shfl_xor(S, o);
+        T2 += __shfl_xor(T2, o);
+        code = min(code, __shfl_xor(code, o));
+    }
+    WavePartial out;
+    out.m = m; out.S = S; out.T = T2; out.code = code; out.cnt = 0; out.nlist = 0; out.thr2 = -INFINITY; out.pad = 0;
+    return out;
+}
+
 template <int DT, int BLOCK, int U>
 __global__ __launch_bounds__(BLOCK) void verify_fused_kernel(VerifyFusedParams p, int64_t unit0)
 {
@@ -292,27 +320,8 @@ __global__ __launch_bounds__(BLOCK) void verify_fused_kernel(VerifyFusedParams p
     // the first wave merges the workgroup's wave partials into ONE partial per (row, segment), sends it to
     // memory, waits until memory has it, and counts the workgroup in
     if (tid < kWave) {
-        WavePartial wp;
-        wp.m = -INFINITY; wp.S = 0.f; wp.T = 0.f; wp.code = 0x7fffffff;
-        if (tid < NW) wp = wave_part[tid];
-        float m = wp.m;
-#pragma unroll
-        for (int o = 1; o < NW; o <<= 1) m = fmaxf(m, __shfl_xor(m, o));
-        const bool live = wp.S > 0.f;
-        float dl2 = 0.f, f = 0.f;
-        if (live) partial_scale(wp.m, m, dl2, f);
-        float S = live ? wp.S * f : 0.f;
-        float T2 = live ? (wp.T + dl2 * wp.S) * f : 0.f;
-        int code = live && wp.m == m ? wp.code : 0x7fffffff;
-#pragma unroll
-        for (int o = 1; o < NW; o <<= 1) {
-            S += __shfl_xor(S, o);
-            T2 += __shfl_xor(T2, o);
-            code = min(code, __shfl_xor(code, o));
-        }
+        const WavePartial out = merge_wave_partials<NW>(wave_part, tid);
         if (tid == 0) {
-            WavePartial out;
-            out.m = m; out.S = S; out.T = T2; out.code = code; out.cnt = 0; out.nlist = 0; out.thr2 = -INFINITY; out.pad = 0;
             store_partial_coherent(p.s.partials + (row * p.s.nseg + seg), out);
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
