@@ -121,6 +121,19 @@ __device__ __forceinline__ int wave_min(int v)
     return min(min(lane_value(v, 0), lane_value(v, 16)), min(lane_value(v, 32), lane_value(v, 48)));
 }
 
+// All-reduce over the lane's aligned group of G lanes (G a power of two, the same in every lane): inside a row of
+// 16 lanes through the vector ALU's cross-lane moves, beyond it through LDS permutes.  The order of combination is fixed.
+template <class T, class OP>
+__device__ __forceinline__ T group_reduce(T v, int G, OP op)
+{
+    if (G > 1) v = op(v, dpp_move<kDppSwap1>(v));
+    if (G > 2) v = op(v, dpp_move<kDppSwap2>(v));
+    if (G > 4) v = op(v, dpp_move<kDppHalfMirror>(v));
+    if (G > 8) v = op(v, dpp_move<kDppMirror>(v));
+    for (int o = 16; o < G; o <<= 1) v = op(v, __shfl_xor(v, o));
+    return v;
+}
+
 // Total order used for "best token": larger logit first, then smaller id.
 __device__ __forceinline__ bool better(float za, int ia, float zb, int ib)
 {

@@ -93,20 +93,20 @@ __global__ __launch_bounds__(BLOCK) void retrieve_kernel(RetrieveParams p)
     const int b = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
     const int32_t* tok = p.tokens + (int64_t)b * p.tok_stride;
-    // A buffer that fits one tile is staged before its length is known (the loads of the length and of the tokens
-    // are in flight together; positions at and after the length are never looked at), and the suffix and the
-    // continuations are then read from LDS instead of through further dependent loads from memory.  Only where few
-    // sequences are launched and latency is what counts: with many, reading whole buffers would add traffic.
-    const bool one_tile = BLOCK == kRetrieveBlock && p.tok_stride <= (int64_t)p.tile;
-    if (one_tile)
-        for (int i = tid; i < (int)p.tok_stride + AASD_MAX_KEY; i += BLOCK) ltok[i] = i >= AASD_MAX_KEY ? tok[i - AASD_MAX_KEY] : 0;
     int len = p.len[b];
     if (len < 0 || (int64_t)len > p.tok_stride) len = 0;
     const int plen = p.prompt_len[b];
     const int n_min = p.n_min, C = p.C, k = p.k;
     const int n_cap = min(p.n_max, len - 1);  // a key must be shorter than the context
 
-    if (one_tile) __syncthreads();
+    // A context that fits one tile is staged at once, and the suffix and the continuations are then read from LDS
+    // instead of through further dependent loads from memory (the chain is: length, tokens; not length, suffix,
+    // tokens, continuations).
+    const bool one_tile = len <= p.tile;
+    if (one_tile) {
+        for (int i = tid; i < len + AASD_MAX_KEY; i += BLOCK) ltok[i] = i >= AASD_MAX_KEY ? tok[i - AASD_MAX_KEY] : 0;
+        __syncthreads();
+    }
     if (tid < AASD_MAX_KEY)
         suffix[tid] = (len - 1 - tid >= 0) ? (one_tile ? ltok[len - 1 - tid + AASD_MAX_KEY] : tok[len - 1 - tid]) : 0;
     if (tid == 0) s_best = 0;

@@ -193,19 +193,6 @@ struct VerifyTreeShared {
     unsigned red_key[16], red_near[16];
 };
 
-// All-reduce over the lane's aligned group of G lanes (G a power of two, the same in every lane): inside a row of
-// 16 lanes through the vector ALU's cross-lane moves, beyond it through LDS permutes.  The order of combination is fixed.
-template <class T, class OP>
-__device__ __forceinline__ T group_reduce(T v, int G, OP op)
-{
-    if (G > 1) v = op(v, dpp_move<kDppSwap1>(v));
-    if (G > 2) v = op(v, dpp_move<kDppSwap2>(v));
-    if (G > 4) v = op(v, dpp_move<kDppHalfMirror>(v));
-    if (G > 8) v = op(v, dpp_move<kDppMirror>(v));
-    for (int o = 16; o < G; o <<= 1) v = op(v, __shfl_xor(v, o));
-    return v;
-}
-
 template <int DT, int NT>
 __device__ __forceinline__ void verify_tree_block(const VerifyTreeParams& p, int b, VerifyTreeShared& sh)
 {

@@ -127,19 +127,13 @@ __device__ __forceinline__ void verify_tail_block(const VerifyTailParams& p, int
                 if (COHERENT) wp = load_partial_coherent(p.partials + row * p.npart + s);
                 else wp = p.partials[row * p.npart + s];
             }
-            float m = wp.m;
-            for (int o = 1; o < G; o <<= 1) m = fmaxf(m, __shfl_xor(m, o));
+            const float m = group_reduce(wp.m, G, [](float x, float y) { return fmaxf(x, y); });
             const bool live = wp.S > 0.f;
             float dl2 = 0.f, f = 0.f;
             if (live) partial_scale(wp.m, m, dl2, f);
-            float S = live ? wp.S * f : 0.f;
-            float T2 = live ? (wp.T + dl2 * wp.S) * f : 0.f;
-            int code = live && wp.m == m ? wp.code : 0x7fffffff;
-            for (int o = 1; o < G; o <<= 1) {
-                S += __shfl_xor(S, o);
-                T2 += __shfl_xor(T2, o);
-                code = min(code, __shfl_xor(code, o));
-            }
+            const float S = group_reduce(live ? wp.S * f : 0.f, G, [](float x, float y) { return x + y; });
+            const float T2 = group_reduce(live ? (wp.T + dl2 * wp.S) * f : 0.f, G, [](float x, float y) { return x + y; });
+            const int code = group_reduce(live && wp.m == m ? wp.code : 0x7fffffff, G, [](int x, int y) { return min(x, y); });
             if (have_row && s == 0) {
                 int am = 0;
                 if ((unsigned)code < (unsigned)p.V) {
@@ -274,21 +268,13 @@ __device__ __forceinline__ WavePartial merge_wave_partials(const WavePartial* wa
     WavePartial wp;
     wp.m = -INFINITY; wp.S = 0.f; wp.T = 0.f; wp.code = 0x7fffffff;
     if (lane < NW) wp = wave_part[lane];
-    float m = wp.m;
-#pragma unroll
-    for (int o = 1; o < NW; o <<= 1) m = fmaxf(m, __shfl_xor(m, o));
+    const float m = group_reduce(wp.m, NW, [](float x, float y) { return fmaxf(x, y); });
     const bool live = wp.S > 0.f;
     float dl2 = 0.f, f = 0.f;
     if (live) partial_scale(wp.m, m, dl2, f);
-    float S = live ? wp.S * f : 0.f;
-    float T2 = live ? (wp.T + dl2 * wp.S) * f : 0.f;
-    int code = live && wp.m == m ? wp.code : 0x7fffffff;
-#pragma unroll
-    for (int o = 1; o < NW; o <<= 1) {
-        S += __shfl_xor(S, o);
-        T2 += __shfl_xor(T2, o);
-        code = min(code, __shfl_xor(code, o));
-    }
+    const float S = group_reduce(live ? wp.S * f : 0.f, NW, [](float x, float y) { return x + y; });
+    const float T2 = group_reduce(live ? (wp.T + dl2 * wp.S) * f : 0.f, NW, [](float x, float y) { return x + y; });
+    const int code = group_reduce(live && wp.m == m ? wp.code : 0x7fffffff, NW, [](int x, int y) { return min(x, y); });
     WavePartial out;
     out.m = m; out.S = S; out.T = T2; out.code = code; out.cnt = 0; out.nlist = 0; out.thr2 = -INFINITY; out.pad = 0;
     return out;

@@ -101,8 +101,7 @@ __global__ __launch_bounds__(kWave) void verify_topk_tail_kernel(VerifyTopkTailP
     }
     // longest candidate, lowest index on ties
     int key = lane < p.C ? (a << 8) | (255 - lane) : -1;
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) key = max(key, __shfl_xor(key, o));
+    key = wave_max(key);
     const int best_a = key >> 8, best_c = 255 - (key & 255);
     if (lane == 0) {
         p.accept_len[b] = best_a;
