@@ -299,14 +299,17 @@ def main():
 
     def verify_ws(nseq):
         nbytes = (aasd.verify_topk_workspace_bytes if topk else aasd.verify_workspace_bytes)(nseq, w.C, w.k, w.V, dt_code)
-        return torch.empty(max(16, nbytes), dtype=torch.uint8, device=dev)
+        # zeroed once: aasd_verify may then take its one-launch form where all workgroups of the call fit the GPU at
+        # once (the `tiny` workload; the larger batches take the two launches), and leaves the counters zero
+        return torch.zeros(max(128, nbytes), dtype=torch.uint8, device=dev)
 
     def do_verify(logits, drafts, draft_len, strict, workspace=None, out=None):
         if topk:
             return aasd.verify_topk(logits, drafts, draft_len, topk=args.topk, want_rows=False, want_tokens=False,
                                     workspace=workspace, out=out)
         return aasd.verify(logits, drafts, draft_len, strict, alpha=w.alpha, beta=w.beta, want_rows=False,
-                           want_tokens=False, want_near=True, workspace=workspace, out=out)
+                           want_tokens=False, want_near=True, workspace=workspace, out=out,
+                           zeroed_workspace=workspace is not None)
 
     # ---------------------------------------------------------------- setup (untimed)
     t_setup = time.time()

@@ -80,6 +80,25 @@ def test_pool_build_in_pieces_and_many_keys(alphabet):
         _check(pool, toks_d, toks, lens, np.minimum(lens, 2500), n_min, n_max, k, C)
 
 
+def test_pool_at_the_largest_capacity():
+    """2^24 tokens, the most a pool takes: buckets use all 25 bits that the build kernel's notes leave them, the build
+    runs over 2048 tiles, and the lookup still returns what the scan of the whole context returns."""
+    cap = 1 << 24
+    rng = np.random.default_rng(24)
+    toks = rng.integers(0, 3000, size=(1, cap)).astype(np.int32)
+    toks[0, cap - 40:cap] = toks[0, 1000:1040]                       # the context ends in a copy of an early span
+    toks[0, 9_000_000:9_000_040] = toks[0, 1000:1040]                # which also occurs in the middle
+    lens = np.array([cap], np.int32)
+    toks_d = _t(toks, torch.int32)
+    pool = aasd.DraftPool(1, cap, 2, 6, DEV)
+    pool.update(toks_d, _t(lens, torch.int32), reset=True)
+    ref = _check(pool, toks_d, toks, lens, np.array([cap // 2], np.int32), 2, 6, 8, 8)
+    assert ref["n_cand"][0] >= 2 and ref["key_len"][0] == 6
+    shorter = np.array([9_000_030], np.int32)                         # a key that ends inside the middle copy
+    ref = _check(pool, toks_d, toks, shorter, shorter, 2, 6, 8, 8)
+    assert ref["n_cand"][0] >= 1
+
+
 def test_pool_incremental_updates_with_extras():
     """Prompt indexed once, then 60 steps that append 1..9 tokens each; after every update the pool answers
     like the oracle on the context of that step.  Updates cross the 64-position batches of the insert kernel."""
