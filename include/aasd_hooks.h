@@ -28,7 +28,8 @@ void aasd_hook_draw_events(void *start, void *stop);
  * Compiled shapes: 256 x {1, 2, 4}, 512 x {2, 4}, 1024 x {1, 2}; segments 1..16.  (0, 0, n) overrides
  * the segments only, (0, 0, 0) switches the override off.  Returns AASD_OK, or an error for a shape
  * that is not compiled (the override is then unchanged).  The workspace queries answer for the shape
- * in force, so set it before asking.
+ * in force, so set it before asking.  A segment count also caps the workgroups per row of the
+ * full-vocabulary draw kernel (which otherwise takes up to 16 while the rows are few).
  */
 int aasd_hook_sweep_plan(int32_t threads, int32_t loads, int32_t segments);
 

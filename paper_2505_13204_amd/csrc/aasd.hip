@@ -532,6 +532,7 @@ int aasd_align_sample(const void* logits, int32_t dt, int64_t rows, int32_t V, i
         const int64_t nquad = ((int64_t)V + 3) / 4;
         if (nseg > 16) nseg = 16;
         if (nseg > nquad / aasd::kGumbelBlock) nseg = nquad / aasd::kGumbelBlock;
+        if (g_plan_nseg > 0 && g_plan_nseg < nseg) nseg = g_plan_nseg;   // the hook's segment count also caps the shares per row
         if (nseg < 1) nseg = 1;
         gp.nseg = (int32_t)nseg;
         gp.part_z = (float*)workspace;

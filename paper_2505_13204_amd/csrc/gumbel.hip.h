@@ -41,7 +41,7 @@ __device__ __forceinline__ float gumbel_from_bits(uint32_t word)
 }
 
 // Keep the K largest keys a lane has seen, in descending order.  Elements arrive in ascending token id, so a
-// strict comparison keeps equal keys in id order.  Branch-free: some lane of a wave inserts at almost every step.
+// strict comparison keeps equal keys in id order.  Branch-free inside: the caller skips it for a whole wave.
 template <int K>
 __device__ __forceinline__ void keep_insert(float (&kz)[K], int (&ki)[K], float z, int i)
 {
@@ -103,24 +103,36 @@ __global__ __launch_bounds__(kGumbelBlock) void gumbel_extras_kernel(GumbelParam
 #pragma unroll
     for (int q = 0; q < K; ++q) { kz[q] = -INFINITY; ki[q] = 0x7fffffff; }
 
+    // Most tokens cannot be among the K best of the row and need not be inserted anywhere: the K-th largest of the
+    // wave's 64 lane maxima (tau) is a key that K tokens seen so far reach, so a token below it is out for good.
+    // tau is brought up to date after 1, 2, 4, 8, ... steps (it only rises, and a stale one only lets more tokens
+    // through); a token at or above it is inserted into its lane's list as before, and the insertion code is
+    // skipped whenever no lane of the wave has such a token, which is soon the usual case.  Every lane takes
+    // every step (a lane beyond the end of the share holds keys of -inf), so the wave-wide operations see all lanes.
+    float tau = -INFINITY;
     const int nquad = (V + 3) >> 2;
     const int per_seg = (nquad + p.nseg - 1) / p.nseg;
     const int q_end = min(nquad, (seg + 1) * per_seg);
-    for (int q = seg * per_seg + tid; q < q_end; q += kGumbelBlock) {
+    int step = 0, next_update = 1;
+    for (int q0 = seg * per_seg; q0 < q_end; q0 += kGumbelBlock, ++step) {
+        const int q = q0 + tid;
+        const bool have = q < q_end;
         const int v0 = q << 2;
-        float z[4];
-        if (wide && v0 + 3 < V) {
-            if constexpr (DT == AASD_BF16) {
-                const uint2 w = *(const uint2*)(base + (size_t)v0 * 2);
-                z[0] = bits_to_float(w.x << 16); z[1] = bits_to_float(w.x & 0xffff0000u);
-                z[2] = bits_to_float(w.y << 16); z[3] = bits_to_float(w.y & 0xffff0000u);
+        float z[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+        if (have) {
+            if (wide && v0 + 3 < V) {
+                if constexpr (DT == AASD_BF16) {
+                    const uint2 w = *(const uint2*)(base + (size_t)v0 * 2);
+                    z[0] = bits_to_float(w.x << 16); z[1] = bits_to_float(w.x & 0xffff0000u);
+                    z[2] = bits_to_float(w.y << 16); z[3] = bits_to_float(w.y & 0xffff0000u);
+                } else {
+                    const float4 w = *(const float4*)(base + (size_t)v0 * 4);
+                    z[0] = w.x; z[1] = w.y; z[2] = w.z; z[3] = w.w;
+                }
             } else {
-                const float4 w = *(const float4*)(base + (size_t)v0 * 4);
-                z[0] = w.x; z[1] = w.y; z[2] = w.z; z[3] = w.w;
-            }
-        } else {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) z[j] = v0 + j < V ? load_elt<DT>(base, v0 + j) : -INFINITY;
+                for (int j = 0; j < 4; ++j) z[j] = v0 + j < V ? load_elt<DT>(base, v0 + j) : -INFINITY;
+            }
         }
         uint32_t rnd[4];
         philox4x32_10(c0, c1, (uint32_t)q, 0x47554D42u, k0, k1, rnd);
@@ -128,8 +140,19 @@ __global__ __launch_bounds__(kGumbelBlock) void gumbel_extras_kernel(GumbelParam
         for (int j = 0; j < 4; ++j) {
             const int v = v0 + j;
             float key = z[j] + gumbel_from_bits(rnd[j]);
-            key = (v < V && v != nt) ? key : -INFINITY;   // -inf is never kept
-            keep_insert<K>(kz, ki, key, v);
+            key = (have && v < V && v != nt && key >= tau) ? key : -INFINITY;   // -inf is never kept
+            if (__ballot(key > -INFINITY) != 0ull) keep_insert<K>(kz, ki, key, v);
+        }
+        if (step == next_update - 1) {
+            next_update <<= 1;
+            float x = kz[0], t = -INFINITY;
+#pragma unroll
+            for (int r = 0; r < K; ++r) {   // the K-th largest lane maximum, equal values counted as often as they occur
+                t = wave_max(x);
+                const unsigned long long holders = __ballot(x == t);
+                if (lane == __ffsll((long long)holders) - 1) x = -INFINITY;
+            }
+            tau = t;
         }
     }
 

@@ -457,6 +457,32 @@ def test_gumbel_extras_parity(dtype, V, m):
     print("gumbel", dtype, V, m, tally)
 
 
+@pytest.mark.parametrize("segments", [1, 2, 5, 16])
+def test_gumbel_extras_with_few_and_many_shares_per_row(segments, forced_plan):
+    """The draw kernel skips tokens below the wave's running bound; how soon the bound bites depends on how many
+    tokens a lane sees, i.e. on the workgroups per row: 1 (500 tokens per lane at this V), 2, 5 and 16 (31 per lane).
+    Rows with a dominant token, with equal logits everywhere (every key then hangs on the random word alone) and with
+    most tokens at probability zero are in."""
+    forced_plan(f"0,0,{segments}")
+    rng = np.random.default_rng(segments)
+    rows, V, m = 24, 128256, 2
+    z = rng.standard_normal((rows, V)).astype(np.float32) * 2
+    z[0:4, 77] = 30.0                      # dominant
+    z[4:8, :] = 0.0                        # all equal
+    z[8:12, :] = -np.inf                   # nearly everything impossible
+    z[8:12, 1000:1010] = 1.0
+    zd = _dev_logits(z, "bf16")
+    nt = rng.integers(0, V, size=rows).astype(np.int32)
+    nt[8:12] = 5                           # a token of probability zero as the prompt's: the row is misaligned
+    tally = bk.Tally()
+    for seed in (3, 11):
+        ref = bk.oracle_align(zd, nt, m, m, oracle.EXTRAS_GUMBEL, seed=seed, row_id_base=1 << 33)
+        got = bk.hip_align(zd, nt, m, m, oracle.EXTRAS_GUMBEL, seed=seed, row_id_base=1 << 33)
+        bk.compare_align(got, ref, tally, oracle.EXTRAS_GUMBEL)
+    assert tally.near_disagreements <= tally.near_decisions
+    print("gumbel shares", segments, tally)
+
+
 def test_gumbel_extras_unaligned_rows_peaked_rows_and_near_counter():
     rng = np.random.default_rng(31)
     rows, V = 300, 5003
