@@ -14,12 +14,14 @@ extern "C" {
 
 /*
  * While two hipEvent_t handles (passed as void*) are set, aasd_align_sample, aasd_verify,
- * aasd_verify_tree and aasd_verify_topk record `start` on the stream immediately before and `stop`
- * immediately after their row-sweep kernel (for the one-launch form of aasd_verify: its only kernel),
- * so that a caller can time that kernel alone.  NULL, NULL switches it off.
+ * aasd_verify_tree and aasd_verify_topk launch their row-sweep kernel (for the one-launch form of
+ * aasd_verify: its only kernel) so that `start` takes the time at which the kernel begins and `stop`
+ * the time at which it ends (hipExtLaunchKernelGGL's events): their difference is that kernel's own
+ * duration, as a profiler's trace gives it.  Where a call launches the kernel several times, `start`
+ * belongs to the first and `stop` to the last launch.  NULL, NULL switches it off.
  */
 void aasd_hook_sweep_events(void *start, void *stop);
-/* The same around the kernel that makes the full-vocabulary draws of AASD_EXTRAS_GUMBEL. */
+/* The same for the kernel that makes the full-vocabulary draws of AASD_EXTRAS_GUMBEL. */
 void aasd_hook_draw_events(void *start, void *stop);
 
 /*

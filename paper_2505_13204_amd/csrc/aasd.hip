@@ -4,6 +4,7 @@
 #include "aasd_hooks.h"
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <cstdarg>
 #include <cstdio>
@@ -135,13 +136,22 @@ bool compiled_shape(int block, int unroll)
 constexpr size_t kMaxChunkMaxLds = 60 * 1024;      // dynamic LDS the sweep may use for chunk maxima
 constexpr int64_t kMaxUnitsPerLaunch = 1 << 22;    // keeps gridDim.x * blockDim.x below 2^32
 
+// A launch whose own begin and end are written to the hook's events, if any: the events then hold the kernel's
+// duration as a profiler sees it, without the stream's gaps before and after it.
+template <class Kernel, class... Args>
+void launch_timed(Kernel kernel, dim3 grid, dim3 block, size_t lds, hipStream_t stream, hipEvent_t start, hipEvent_t stop, Args... args)
+{
+    if (start || stop) hipExtLaunchKernelGGL(kernel, grid, block, (unsigned)lds, stream, start, stop, 0, args...);
+    else hipLaunchKernelGGL(kernel, grid, block, lds, stream, args...);
+}
+
 template <int DT, bool ALIGN, bool COUNT, int BLOCK, int U>
 hipError_t launch_sweep_one(const aasd::SweepParams& p, int64_t units, size_t dyn_lds, hipStream_t stream)
 {
     for (int64_t unit0 = 0; unit0 < units; unit0 += kMaxUnitsPerLaunch) {
         const int64_t n = units - unit0 < kMaxUnitsPerLaunch ? units - unit0 : kMaxUnitsPerLaunch;
-        hipLaunchKernelGGL((aasd::row_sweep_kernel<DT, ALIGN, COUNT, BLOCK, U>), dim3((unsigned)n), dim3(BLOCK),
-                           dyn_lds, stream, p, unit0);
+        launch_timed(aasd::row_sweep_kernel<DT, ALIGN, COUNT, BLOCK, U>, dim3((unsigned)n), dim3(BLOCK), dyn_lds, stream,
+                     unit0 == 0 ? g_sweep_start : nullptr, unit0 + n >= units ? g_sweep_stop : nullptr, p, unit0);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -153,7 +163,6 @@ int launch_sweep(const aasd::SweepParams& p, const SweepPlan& pl, int64_t rows, 
 {
     const int64_t units = rows * pl.nseg;
     hipError_t e;
-    if (g_sweep_start) (void)hipEventRecord(g_sweep_start, stream);
     if (pl.block == 256 && pl.unroll == 4) e = launch_sweep_one<DT, ALIGN, COUNT, 256, 4>(p, units, dyn_lds, stream);
     else if (pl.block == 256 && pl.unroll == 2) e = launch_sweep_one<DT, ALIGN, COUNT, 256, 2>(p, units, dyn_lds, stream);
     else if (pl.block == 256 && pl.unroll == 1) e = launch_sweep_one<DT, ALIGN, COUNT, 256, 1>(p, units, dyn_lds, stream);
@@ -162,7 +171,6 @@ int launch_sweep(const aasd::SweepParams& p, const SweepPlan& pl, int64_t rows, 
     else if (pl.block == 1024 && pl.unroll == 2) e = launch_sweep_one<DT, ALIGN, COUNT, 1024, 2>(p, units, dyn_lds, stream);
     else if (pl.block == 1024 && pl.unroll == 1) e = launch_sweep_one<DT, ALIGN, COUNT, 1024, 1>(p, units, dyn_lds, stream);
     else return fail(AASD_ERR_UNSUPPORTED, "sweep plan %d,%d is not a compiled launch shape", pl.block, pl.unroll);   // unreachable: plans are checked when set
-    if (g_sweep_stop) (void)hipEventRecord(g_sweep_stop, stream);
     if (e != hipSuccess) return fail(AASD_ERR_LAUNCH, "row sweep launch failed: %s", hipGetErrorString(e));
     return AASD_OK;
 }
@@ -173,7 +181,8 @@ hipError_t launch_fused_one(const aasd::VerifyFusedParams& p, int64_t units, hip
 {
     for (int64_t unit0 = 0; unit0 < units; unit0 += kMaxUnitsPerLaunch) {
         const int64_t n = units - unit0 < kMaxUnitsPerLaunch ? units - unit0 : kMaxUnitsPerLaunch;
-        hipLaunchKernelGGL((aasd::verify_fused_kernel<DT, BLOCK, U>), dim3((unsigned)n), dim3(BLOCK), 0, stream, p, unit0);
+        launch_timed(aasd::verify_fused_kernel<DT, BLOCK, U>, dim3((unsigned)n), dim3(BLOCK), 0, stream,
+                     unit0 == 0 ? g_sweep_start : nullptr, unit0 + n >= units ? g_sweep_stop : nullptr, p, unit0);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -185,7 +194,6 @@ int launch_fused(const aasd::VerifyFusedParams& p, const SweepPlan& pl, int64_t 
 {
     const int64_t units = rows * pl.nseg;
     hipError_t e;
-    if (g_sweep_start) (void)hipEventRecord(g_sweep_start, stream);
     if (pl.block == 256 && pl.unroll == 4) e = launch_fused_one<DT, 256, 4>(p, units, stream);
     else if (pl.block == 256 && pl.unroll == 2) e = launch_fused_one<DT, 256, 2>(p, units, stream);
     else if (pl.block == 256 && pl.unroll == 1) e = launch_fused_one<DT, 256, 1>(p, units, stream);
@@ -194,7 +202,6 @@ int launch_fused(const aasd::VerifyFusedParams& p, const SweepPlan& pl, int64_t 
     else if (pl.block == 1024 && pl.unroll == 2) e = launch_fused_one<DT, 1024, 2>(p, units, stream);
     else if (pl.block == 1024 && pl.unroll == 1) e = launch_fused_one<DT, 1024, 1>(p, units, stream);
     else return fail(AASD_ERR_UNSUPPORTED, "sweep plan %d,%d is not a compiled launch shape", pl.block, pl.unroll);   // unreachable
-    if (g_sweep_stop) (void)hipEventRecord(g_sweep_stop, stream);
     if (e != hipSuccess) return fail(AASD_ERR_LAUNCH, "verify launch failed: %s", hipGetErrorString(e));
     return AASD_OK;
 }
@@ -222,7 +229,8 @@ hipError_t launch_sweep_used_one(const aasd::SweepParams& p, const SweepPlan& pl
         const int nseq = (int)(sequences - seq0 < BLOCK ? sequences - seq0 : BLOCK);
         const int64_t most = (int64_t)nseq * p.rows_per_seq * pl.nseg;
         const unsigned grid = (unsigned)(most < resident ? most : resident);
-        hipLaunchKernelGGL((aasd::row_sweep_used_kernel<DT, BLOCK, U>), dim3(grid), dim3(BLOCK), 0, stream, p, seq0, nseq);
+        launch_timed(aasd::row_sweep_used_kernel<DT, BLOCK, U>, dim3(grid), dim3(BLOCK), 0, stream,
+                     seq0 == 0 ? g_sweep_start : nullptr, seq0 + nseq >= sequences ? g_sweep_stop : nullptr, p, seq0, nseq);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -233,7 +241,6 @@ template <int DT>
 int launch_sweep_used(const aasd::SweepParams& p, const SweepPlan& pl, int64_t sequences, hipStream_t stream)
 {
     hipError_t e;
-    if (g_sweep_start) (void)hipEventRecord(g_sweep_start, stream);
     if (pl.block == 256 && pl.unroll == 4) e = launch_sweep_used_one<DT, 256, 4>(p, pl, sequences, stream);
     else if (pl.block == 256 && pl.unroll == 2) e = launch_sweep_used_one<DT, 256, 2>(p, pl, sequences, stream);
     else if (pl.block == 256 && pl.unroll == 1) e = launch_sweep_used_one<DT, 256, 1>(p, pl, sequences, stream);
@@ -242,27 +249,26 @@ int launch_sweep_used(const aasd::SweepParams& p, const SweepPlan& pl, int64_t s
     else if (pl.block == 1024 && pl.unroll == 2) e = launch_sweep_used_one<DT, 1024, 2>(p, pl, sequences, stream);
     else if (pl.block == 1024 && pl.unroll == 1) e = launch_sweep_used_one<DT, 1024, 1>(p, pl, sequences, stream);
     else return fail(AASD_ERR_UNSUPPORTED, "sweep plan %d,%d is not a compiled launch shape", pl.block, pl.unroll);   // unreachable
-    if (g_sweep_stop) (void)hipEventRecord(g_sweep_stop, stream);
     if (e != hipSuccess) return fail(AASD_ERR_LAUNCH, "row sweep launch failed: %s", hipGetErrorString(e));
     return AASD_OK;
 }
 
 template <int DT>
-void launch_gumbel_dt(int m, unsigned grid, hipStream_t s, const aasd::GumbelParams& gp, int64_t u0)
+void launch_gumbel_dt(int m, unsigned grid, hipStream_t s, const aasd::GumbelParams& gp, int64_t u0, hipEvent_t start, hipEvent_t stop)
 {
     const dim3 g(grid), b(aasd::kGumbelBlock);
     switch (m) {  // the kernel keeps m + 1 keys per lane
-    case 1: hipLaunchKernelGGL((aasd::gumbel_extras_kernel<DT, 2>), g, b, 0, s, gp, u0); break;
-    case 2: hipLaunchKernelGGL((aasd::gumbel_extras_kernel<DT, 3>), g, b, 0, s, gp, u0); break;
-    case 3: hipLaunchKernelGGL((aasd::gumbel_extras_kernel<DT, 4>), g, b, 0, s, gp, u0); break;
-    default: hipLaunchKernelGGL((aasd::gumbel_extras_kernel<DT, 5>), g, b, 0, s, gp, u0); break;
+    case 1: launch_timed(aasd::gumbel_extras_kernel<DT, 2>, g, b, 0, s, start, stop, gp, u0); break;
+    case 2: launch_timed(aasd::gumbel_extras_kernel<DT, 3>, g, b, 0, s, start, stop, gp, u0); break;
+    case 3: launch_timed(aasd::gumbel_extras_kernel<DT, 4>, g, b, 0, s, start, stop, gp, u0); break;
+    default: launch_timed(aasd::gumbel_extras_kernel<DT, 5>, g, b, 0, s, start, stop, gp, u0); break;
     }
 }
 
-void launch_gumbel(int32_t dt, int m, unsigned grid, hipStream_t s, const aasd::GumbelParams& gp, int64_t u0)
+void launch_gumbel(int32_t dt, int m, unsigned grid, hipStream_t s, const aasd::GumbelParams& gp, int64_t u0, hipEvent_t start, hipEvent_t stop)
 {
-    if (dt == AASD_BF16) launch_gumbel_dt<AASD_BF16>(m, grid, s, gp, u0);
-    else launch_gumbel_dt<AASD_F32>(m, grid, s, gp, u0);
+    if (dt == AASD_BF16) launch_gumbel_dt<AASD_BF16>(m, grid, s, gp, u0, start, stop);
+    else launch_gumbel_dt<AASD_F32>(m, grid, s, gp, u0, start, stop);
 }
 
 void launch_gumbel_merge(int m, int64_t rows, hipStream_t s, const aasd::GumbelParams& gp)
@@ -537,11 +543,10 @@ int aasd_align_sample(const void* logits, int32_t dt, int64_t rows, int32_t V, i
         gp.nseg = (int32_t)nseg;
         gp.part_z = (float*)workspace;
         gp.part_i = (int32_t*)((char*)workspace + align16((size_t)rows * nseg * (m_draw + 1) * sizeof(float)));
-        if (g_draw_start) (void)hipEventRecord(g_draw_start, s);
         const int64_t units = rows * nseg;
         for (int64_t u0 = 0; u0 < units; u0 += kMaxUnitsPerLaunch) {
             const int64_t n = units - u0 < kMaxUnitsPerLaunch ? units - u0 : kMaxUnitsPerLaunch;
-            launch_gumbel(dt, m_draw, (unsigned)n, s, gp, u0);
+            launch_gumbel(dt, m_draw, (unsigned)n, s, gp, u0, u0 == 0 ? g_draw_start : nullptr, u0 + n >= units ? g_draw_stop : nullptr);
             const hipError_t e = hipGetLastError();
             if (e != hipSuccess) return fail(AASD_ERR_LAUNCH, "gumbel extras launch failed: %s", hipGetErrorString(e));
         }
@@ -550,7 +555,6 @@ int aasd_align_sample(const void* logits, int32_t dt, int64_t rows, int32_t V, i
             const hipError_t e = hipGetLastError();
             if (e != hipSuccess) return fail(AASD_ERR_LAUNCH, "gumbel merge launch failed: %s", hipGetErrorString(e));
         }
-        if (g_draw_stop) (void)hipEventRecord(g_draw_stop, s);
     }
     return AASD_OK;
 }
