@@ -692,3 +692,57 @@ def test_more_work_than_one_launch_covers():
     dl = rng.integers(0, k + 1, size=(B, C)).astype(np.int32)
     _verify_both(zv, drafts, dl, None, 0.1, 0.1, 0, tally)
     print("large counts", tally)
+
+
+# --------------------------------------------------------------------------- measurement hooks
+def test_event_hooks_time_the_kernel_and_change_nothing():
+    """With the hooks set, the sweep (and draw) kernels are launched with start and stop events: the results are
+    byte for byte those of a call without hooks, and the events hold a duration that is positive and no longer than
+    the whole call as the stream sees it."""
+    import ctypes
+    hip = ctypes.CDLL("libamdhip64.so")
+
+    def event():
+        e = ctypes.c_void_p()
+        assert hip.hipEventCreate(ctypes.byref(e)) == 0
+        return e
+
+    def elapsed_ms(a, b):
+        ms = ctypes.c_float()
+        assert hip.hipEventElapsedTime(ctypes.byref(ms), a, b) == 0
+        return ms.value
+
+    rng = np.random.default_rng(5)
+    z = _random_rows(rng, 600, 32000, "bf16")
+    nt = torch.from_numpy(rng.integers(0, 32000, size=600).astype(np.int32)).to(DEV)
+    zd, drafts, dl, strict = _verify_case(rng, 4, 2, 4, 32000, "bf16")
+    t = lambda a, dt: torch.as_tensor(np.ascontiguousarray(a), device=DEV).to(dt)
+    vargs = (zd, t(drafts, torch.int32), t(dl, torch.int32), t(strict, torch.uint8))
+    ws = torch.zeros(aasd.verify_workspace_bytes(4, 2, 4, 32000, aasd.BF16), dtype=torch.uint8, device=DEV)
+    calls = {
+        "align top": (aasd.set_sweep_events, lambda: aasd.align_sample(z, nt, m=2, c=4)),
+        "align gumbel, sweep": (aasd.set_sweep_events, lambda: aasd.align_sample(z, nt, m=2, c=2, mode=aasd.EXTRAS_GUMBEL, seed=3)),
+        "align gumbel, draws": (aasd.set_draw_events, lambda: aasd.align_sample(z, nt, m=2, c=2, mode=aasd.EXTRAS_GUMBEL, seed=3)),
+        "verify, two launches": (aasd.set_sweep_events, lambda: aasd.verify(*vargs)),
+        "verify, one launch": (aasd.set_sweep_events, lambda: aasd.verify(*vargs, workspace=ws, zeroed_workspace=True)),
+        "verify top-k": (aasd.set_sweep_events, lambda: aasd.verify_topk(*vargs[:3], topk=3)),
+    }
+    for name, (hook, call) in calls.items():
+        plain = bk.to_np(call())
+        torch.cuda.synchronize()
+        a, b = event(), event()
+        o0, o1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        hook(a, b)
+        try:
+            o0.record()
+            timed = bk.to_np(call())
+            o1.record()
+        finally:
+            hook(None, None)
+        torch.cuda.synchronize()
+        for key, v in plain.items():
+            if v is not None:
+                assert v.tobytes() == timed[key].tobytes(), (name, key)
+        inner, outer = elapsed_ms(a, b), o0.elapsed_time(o1)
+        assert 0.0 < inner <= outer, (name, inner, outer)
+        assert hip.hipEventDestroy(a) == 0 and hip.hipEventDestroy(b) == 0
