@@ -434,29 +434,34 @@ def main():
         torch.cuda.synchronize()
         ms_per_step_one_stream = (time.perf_counter() - ts0) * 1e3 / K
 
-    # ---------------------------------------------------------------- the same K steps again, instrumented
-    # HIP events on the stream the kernels run on: one pair around each API call, and (through the library's
-    # measurement hook) one pair around each row-sweep kernel alone.  Every event record is a packet of its own
-    # between two kernels and costs a few microseconds of idle GPU, which is why the throughput above is timed
-    # without them; the kernels themselves run as in the timed region.
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(K)]
+    # ---------------------------------------------------------------- the same K steps again, instrumented (one stream)
+    # (a) With the library's measurement hook only: the sweep (and draw) kernels are launched with start and stop
+    # events that take the kernel's own begin and end; no packet is added to the stream, the kernels follow one another
+    # as in the timed region.  (b) With one pair of events around each API call, for the call times: every event record
+    # is a packet of its own between two kernels and costs a few microseconds of idle GPU.
     kev = [[hip_event() for _ in range(6)] for _ in range(K)]
     torch.cuda.synchronize()
-    ti0 = time.perf_counter()
     for i in range(K):
-        ev[i][0].record()
         aasd.set_sweep_events(kev[i][0], kev[i][1])
         if mode == aasd.EXTRAS_GUMBEL:
             aasd.set_draw_events(kev[i][4], kev[i][5])
         aasd.align_sample(prefill, next_tok_d, m=w.m, c=w.c, mode=mode, seed=w.seed, out=align_out)
+        aasd.set_draw_events(None, None)
+        do_retrieve(out=r_out)
+        aasd.set_sweep_events(kev[i][2], kev[i][3])
+        do_verify(verify_logits, r_out["drafts"], r_out["draft_len"], r_out["strict"], workspace=ws, out=v_out)
+    aasd.set_sweep_events(None, None)
+    torch.cuda.synchronize()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(K)]
+    ti0 = time.perf_counter()
+    for i in range(K):
+        ev[i][0].record()
+        aasd.align_sample(prefill, next_tok_d, m=w.m, c=w.c, mode=mode, seed=w.seed, out=align_out)
         ev[i][1].record()
         do_retrieve(out=r_out)
         ev[i][2].record()
-        aasd.set_sweep_events(kev[i][2], kev[i][3])
         do_verify(verify_logits, r_out["drafts"], r_out["draft_len"], r_out["strict"], workspace=ws, out=v_out)
         ev[i][3].record()
-    aasd.set_sweep_events(None, None)
-    aasd.set_draw_events(None, None)
     torch.cuda.synchronize()
     ms_per_step_instrumented = (time.perf_counter() - ti0) * 1e3 / K
     draws = None
@@ -524,9 +529,10 @@ def main():
                             **({"pool_build_ms": round(pool_build_ms, 3), "pool_MB": round(pool.nbytes / 1e6, 1)} if use_pool else {})},
         "ms_per_step_one_stream": round(ms_per_step_one_stream, 4),
         "ms_per_step_instrumented": round(ms_per_step_instrumented, 4),
-        "note": "kernel times: HIP events recorded by the library around the sweep kernel alone, over a one-stream repeat of the K timed "
-                "steps with the events switched on (they cost idle time between kernels, so the timed region runs without "
-                "them); call times include the finish kernels",
+        "note": "kernel times: the sweep kernels' own begin and end (start and stop events of their launches, set through the "
+                "library's measurement hook) over a one-stream repeat of the K timed steps; call times: events around every "
+                "call in a second repeat (ms_per_step_instrumented; the events cost idle time between kernels, so the timed "
+                "region runs without them) and include the finish kernels",
     }
 
     # ---------------------------------------------------------------- the decode step at its real shape
@@ -727,7 +733,8 @@ def bench_tree(args, w, dev):
     side = torch.cuda.Stream(device=dev)   # default priority, like the main stream
 
     def one_pass(i=None, ev=None, kev=None, two_streams=False):
-        if ev: ev[0].record(); aasd.set_sweep_events(kev[0], kev[1])
+        if ev: ev[0].record()
+        if kev: aasd.set_sweep_events(kev[0], kev[1])
         if two_streams:     # prefill alignment does not feed the decode steps of this batch: it may overlap with them
             with torch.cuda.stream(side):
                 aasd.align_sample(prefill, next_tok_d, m=w.m, c=w.c, mode=aasd.EXTRAS_TOP, seed=w.seed, out=align_out)
@@ -739,7 +746,8 @@ def bench_tree(args, w, dev):
         if ev: ev[2].record()
         aasd.build_tree(r_out["drafts"], r_out["draft_len"], r_out["strict"], r_out["draft_extras"], root_b, max_nodes=N,
                         out=t_out)
-        if ev: ev[3].record(); aasd.set_sweep_events(kev[2], kev[3])
+        if ev: ev[3].record()
+        if kev: aasd.set_sweep_events(kev[2], kev[3])
         aasd.verify_tree(tree_logits, t_out["node_token"], t_out["node_parent"], t_out["n_nodes"], t_out["node_strict"],
                          alpha=w.alpha, beta=w.beta, workspace=ws, want_rows=False, want_nodes=False, out=v_out)
         if ev: ev[4].record()
@@ -764,14 +772,18 @@ def bench_tree(args, w, dev):
             one_pass()
         torch.cuda.synchronize()
         ms_per_step_one_stream = (time.perf_counter() - ts0) * 1e3 / K
-    # the same K steps again with HIP events around every call and around the sweep kernels (see main())
+    # the same K steps again: with the hook's events that take the sweep kernels' own begin and end, then with events
+    # around every call (see main())
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(K)]
     kev = [[hip_event() for _ in range(4)] for _ in range(K)]
     torch.cuda.synchronize()
+    for i in range(K):
+        one_pass(i, None, kev[i])
+    aasd.set_sweep_events(None, None)
+    torch.cuda.synchronize()
     ti0 = time.perf_counter()
     for i in range(K):
-        one_pass(i, ev[i], kev[i])
-    aasd.set_sweep_events(None, None)
+        one_pass(i, ev[i], None)
     torch.cuda.synchronize()
     ms_per_step_instrumented = (time.perf_counter() - ti0) * 1e3 / K
     mean = lambda a, b: float(np.mean([ev[i][a].elapsed_time(ev[i][b]) for i in range(K)]))
@@ -803,8 +815,9 @@ def bench_tree(args, w, dev):
                        "max_nodes": int(n_nodes_h.max())},
         "ms_per_step_one_stream": round(ms_per_step_one_stream, 4),
         "ms_per_step_instrumented": round(ms_per_step_instrumented, 4),
-        "note": "only the rows of existing tree nodes are read and counted; kernel times from HIP events around the sweep kernel "
-                "alone, over a repeat of the K timed steps with the events switched on",
+        "note": "only the rows of existing tree nodes are read and counted; kernel times: the sweep kernels' own begin and end "
+                "(start and stop events of their launches) over a one-stream repeat of the K timed steps; call times from a "
+                "second repeat with events around every call",
     }
 
     # ---------------------------------------------------------------- sequential per-step latency (context)
