@@ -180,26 +180,24 @@ def per_step_block(torch, np, aasd, label, logits_steps, tokens, lens, plens, w,
     kw = dict(alpha=w.alpha, beta=w.beta, want_rows=False, want_tokens=False, want_near=True, workspace=ws)
     v = aasd.verify(logits_steps[0], r["drafts"], r["draft_len"], r["strict"], zeroed_workspace=True, **kw)
     v2 = aasd.verify(logits_steps[0], r["drafts"], r["draft_len"], r["strict"], **kw)
-    pool, pool_build_us = None, None
-    if use_pool:
-        # The persistent pool in place of the scan: built once over the longest context (timed: the cost at the end of
-        # prefill), then rebuilt at the first step's length; aasd_pool_step indexes what a step added and looks up.
-        # The step lengths ascend through the first pass over the buffers (real incremental updates); later passes
-        # look up at lengths that are indexed already.
-        pool = aasd.DraftPool(B, tokens[0].shape[1], w.n_min, w.n_max, dev)
+    # Retrieval both ways: the stateless scan, and the persistent pool: built once over the longest context (timed:
+    # the cost at the end of prefill), then rebuilt at the first step's length; aasd_pool_step indexes what a step
+    # added and looks up.  The step lengths ascend through the first pass over the buffers (real incremental updates);
+    # later passes look up at lengths that are indexed already.
+    pool = aasd.DraftPool(B, tokens[0].shape[1], w.n_min, w.n_max, dev)
+    pool.update(tokens[n - 1], lens[n - 1], reset=True)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(10):
         pool.update(tokens[n - 1], lens[n - 1], reset=True)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(10):
-            pool.update(tokens[n - 1], lens[n - 1], reset=True)
-        e1.record()
-        torch.cuda.synchronize()
-        pool_build_us = e0.elapsed_time(e1) * 1e3 / 10
-        pool.update(tokens[0], lens[0], reset=True)
+    e1.record()
+    torch.cuda.synchronize()
+    pool_build_us = e0.elapsed_time(e1) * 1e3 / 10
+    pool.update(tokens[0], lens[0], reset=True)
 
-    def step(i, one_launch=True, with_retrieve=True):
-        if with_retrieve and pool is not None:
+    def step(i, one_launch=True, with_retrieve=True, through_pool=use_pool):
+        if with_retrieve and through_pool:
             pool.step(tokens[i % n], lens[i % n], plens, w.k, w.C, out=r)
         elif with_retrieve:
             aasd.retrieve_drafts(tokens[i % n], lens[i % n], plens, w.n_min, w.n_max, w.k, w.C, out=r)
@@ -207,7 +205,9 @@ def per_step_block(torch, np, aasd, label, logits_steps, tokens, lens, plens, w,
                     out=v if one_launch else v2, **kw)
 
     m = max(n, 64)
-    eager, graph_us = time_steps(torch, step, m)
+    scan_eager, scan_graph = time_steps(torch, lambda i: step(i, through_pool=False), m)
+    pool_eager, pool_graph = time_steps(torch, lambda i: step(i, through_pool=True), m)
+    eager, graph_us = (pool_eager, pool_graph) if use_pool else (scan_eager, scan_graph)
     v_eager, v_graph = time_steps(torch, lambda i: step(i, True, False), m)
     t_eager, t_graph = time_steps(torch, lambda i: step(i, False, False), m)
     # the verify kernel alone, from the library's hook (HIP events around it on the stream it runs on)
@@ -223,8 +223,10 @@ def per_step_block(torch, np, aasd, label, logits_steps, tokens, lens, plens, w,
     return {"shape": label, "sequences": B, "rows_per_step": B * R, "bytes_per_step": step_bytes,
             "rotating_step_buffers": n, "resident_MB": round(n * step_bytes / 1e6, 1),
             "retrieval": "pool" if use_pool else "scan",
-            **({"pool_build_us": round(pool_build_us, 1), "pool_build_tokens": int(lens[n - 1].sum().item())} if use_pool else {}),
+            "pool_build_us": round(pool_build_us, 1), "pool_build_tokens": int(lens[n - 1].sum().item()),
             "retrieve_plus_verify_us": {"eager": rnd(eager), "hip_graph": rnd(graph_us)},
+            "scan_plus_verify_us": {"eager": rnd(scan_eager), "hip_graph": rnd(scan_graph)},
+            "pool_step_plus_verify_us": {"eager": rnd(pool_eager), "hip_graph": rnd(pool_graph)},
             "verify_one_launch_us": {"eager": rnd(v_eager), "hip_graph": rnd(v_graph), "kernel_event_median": rnd(kern)},
             "verify_two_launches_us": {"eager": rnd(t_eager), "hip_graph": rnd(t_graph)},
             "verify_GB/s": round(step_bytes / best / 1e3, 1), "verify_frac_of_hbm_peak": round(step_bytes / best / 1e3 / HBM_PEAK_GBS, 4),
