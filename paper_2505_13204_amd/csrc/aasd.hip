@@ -136,6 +136,9 @@ bool compiled_shape(int block, int unroll)
 constexpr size_t kMaxChunkMaxLds = 60 * 1024;      // dynamic LDS the sweep may use for chunk maxima
 constexpr int64_t kMaxUnitsPerLaunch = 1 << 22;    // keeps gridDim.x * blockDim.x below 2^32
 
+// floor(2^32 / d) + 1: x / d = (x * magic) >> 32 for x < 2^32 / d (the kernels divide small unit and row indices so)
+uint32_t div_magic(int32_t d) { return d > 1 ? (uint32_t)(((uint64_t)1 << 32) / (uint64_t)d + 1) : 0u; }
+
 // A launch whose own begin and end are written to the hook's events, if any: the events then hold the kernel's
 // duration as a profiler sees it, without the stream's gaps before and after it.
 template <class Kernel, class... Args>
@@ -148,10 +151,11 @@ void launch_timed(Kernel kernel, dim3 grid, dim3 block, size_t lds, hipStream_t 
 template <int DT, bool ALIGN, bool COUNT, int BLOCK, int U>
 hipError_t launch_sweep_one(const aasd::SweepParams& p, int64_t units, size_t dyn_lds, hipStream_t stream)
 {
-    for (int64_t unit0 = 0; unit0 < units; unit0 += kMaxUnitsPerLaunch) {
-        const int64_t n = units - unit0 < kMaxUnitsPerLaunch ? units - unit0 : kMaxUnitsPerLaunch;
+    const int64_t chunk = kMaxUnitsPerLaunch / p.nseg * p.nseg;   // whole rows per launch
+    for (int64_t unit0 = 0; unit0 < units; unit0 += chunk) {
+        const int64_t n = units - unit0 < chunk ? units - unit0 : chunk;
         launch_timed(aasd::row_sweep_kernel<DT, ALIGN, COUNT, BLOCK, U>, dim3((unsigned)n), dim3(BLOCK), dyn_lds, stream,
-                     unit0 == 0 ? g_sweep_start : nullptr, unit0 + n >= units ? g_sweep_stop : nullptr, p, unit0);
+                     unit0 == 0 ? g_sweep_start : nullptr, unit0 + n >= units ? g_sweep_stop : nullptr, p, unit0 / p.nseg);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -179,10 +183,11 @@ int launch_sweep(const aasd::SweepParams& p, const SweepPlan& pl, int64_t rows, 
 template <int DT, int BLOCK, int U>
 hipError_t launch_fused_one(const aasd::VerifyFusedParams& p, int64_t units, hipStream_t stream)
 {
-    for (int64_t unit0 = 0; unit0 < units; unit0 += kMaxUnitsPerLaunch) {
-        const int64_t n = units - unit0 < kMaxUnitsPerLaunch ? units - unit0 : kMaxUnitsPerLaunch;
+    const int64_t chunk = kMaxUnitsPerLaunch / p.s.nseg * p.s.nseg;   // whole rows per launch
+    for (int64_t unit0 = 0; unit0 < units; unit0 += chunk) {
+        const int64_t n = units - unit0 < chunk ? units - unit0 : chunk;
         launch_timed(aasd::verify_fused_kernel<DT, BLOCK, U>, dim3((unsigned)n), dim3(BLOCK), 0, stream,
-                     unit0 == 0 ? g_sweep_start : nullptr, unit0 + n >= units ? g_sweep_stop : nullptr, p, unit0);
+                     unit0 == 0 ? g_sweep_start : nullptr, unit0 + n >= units ? g_sweep_stop : nullptr, p, unit0 / p.s.nseg);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -370,7 +375,7 @@ int verify_launch(const void* logits, int32_t dt, int32_t B, int32_t C, int32_t 
     }
     aasd::SweepParams sp{};
     sp.logits = logits; sp.V = V; sp.row_stride = row_stride; sp.seq_stride = seq_stride; sp.rows_per_seq = (int32_t)R;
-    sp.c = 1; sp.nseg = pl.nseg; sp.seg_vecs = pl.seg_vecs; sp.partials = (aasd::WavePartial*)partials;
+    sp.c = 1; sp.nseg = pl.nseg; sp.nseg_magic = div_magic(pl.nseg); sp.seg_vecs = pl.seg_vecs; sp.partials = (aasd::WavePartial*)partials;
 
     aasd::VerifyTailParams tp{};
     tp.logits = logits; tp.B = B; tp.C = C; tp.k = k; tp.V = V; tp.row_stride = row_stride; tp.seq_stride = seq_stride;
@@ -385,6 +390,7 @@ int verify_launch(const void* logits, int32_t dt, int32_t B, int32_t C, int32_t 
         aasd::VerifyFusedParams fp{};
         fp.s = sp; fp.t = tp; fp.counters = counters; fp.ngroups = verify_groups(rows, R * pl.nseg);
         fp.t.npart = pl.nseg;   // this form leaves one partial per workgroup, not per wave
+        fp.rps_magic = div_magic((int32_t)R);   // R >= 2
         return dt == AASD_BF16 ? launch_fused<AASD_BF16>(fp, pl, rows, s) : launch_fused<AASD_F32>(fp, pl, rows, s);
     }
     const int rc = dt == AASD_BF16 ? launch_sweep<AASD_BF16, false, false>(sp, pl, rows, 0, s)
@@ -486,7 +492,7 @@ int aasd_align_sample(const void* logits, int32_t dt, int64_t rows, int32_t V, i
     aasd::SweepParams p{};
     p.logits = logits; p.V = V; p.row_stride = row_stride; p.seq_stride = row_stride; p.rows_per_seq = 1;
     p.next_tok = next_tok; p.want_cand = m > 0; p.c = c;
-    p.nseg = pl.nseg; p.seg_vecs = pl.seg_vecs; p.partials = partials; p.lists = lists;
+    p.nseg = pl.nseg; p.nseg_magic = div_magic(pl.nseg); p.seg_vecs = pl.seg_vecs; p.partials = partials; p.lists = lists;
     // one chunk maximum per 16-byte vector of a segment, kept in LDS (lane-contiguous) when it fits
     size_t dyn = 0;
     if (m > 0 && next_tok) {
@@ -843,7 +849,7 @@ int aasd_verify_topk(const void* logits, int32_t dt, int32_t B, int32_t C, int32
     aasd::SweepParams sp{};
     sp.logits = logits; sp.V = V; sp.row_stride = row_stride; sp.seq_stride = seq_stride; sp.rows_per_seq = R;
     sp.next_tok = nullptr; sp.want_cand = 1; sp.cand_all = 1; sp.c = topk;
-    sp.nseg = pl.nseg; sp.seg_vecs = pl.seg_vecs; sp.partials = partials; sp.lists = lists;
+    sp.nseg = pl.nseg; sp.nseg_magic = div_magic(pl.nseg); sp.seg_vecs = pl.seg_vecs; sp.partials = partials; sp.lists = lists;
     size_t dyn = 0;
     {
         const size_t per_lane = (size_t)(pl.seg_vecs / pl.block) * elt_size(dt);
@@ -947,7 +953,7 @@ int aasd_verify_tree(const void* logits, int32_t dt, int32_t B, int32_t N, int32
     aasd::SweepParams sp{};
     sp.logits = logits; sp.V = V; sp.row_stride = row_stride; sp.seq_stride = seq_stride; sp.rows_per_seq = N;
     sp.rows_used = n_nodes;
-    sp.c = 1; sp.nseg = pl.nseg; sp.seg_vecs = pl.seg_vecs; sp.partials = (aasd::WavePartial*)workspace;
+    sp.c = 1; sp.nseg = pl.nseg; sp.nseg_magic = div_magic(pl.nseg); sp.seg_vecs = pl.seg_vecs; sp.partials = (aasd::WavePartial*)workspace;
     int rc = dt == AASD_BF16 ? launch_sweep_used<AASD_BF16>(sp, pl, B, s) : launch_sweep_used<AASD_F32>(sp, pl, B, s);
     if (rc != AASD_OK) return rc;
 

@@ -86,6 +86,7 @@ struct SweepParams {
     int32_t cm_enabled;    // chunk maxima fit in LDS
     int32_t cm_stride;     // bytes between the chunk-maximum rows of neighbouring lanes
     int32_t nseg;          // segments per row
+    uint32_t nseg_magic;   // floor(2^32 / nseg) + 1 (0 for nseg = 1): u / nseg = (u * magic) >> 32, exact for u < 2^28
     int32_t seg_vecs;      // 16-byte vectors per segment (a multiple of the block size)
     WavePartial* partials; // [rows][nseg * waves per block]
     int32_t* lists;        // [rows][nseg * waves per block][kListCap] first-element indices of listed chunks
@@ -610,7 +611,10 @@ __device__ __forceinline__ void sweep_unit(const SweepParams& p, int64_t row, in
                                            unsigned char* cm, WavePartial* local_out = nullptr)
 {
     constexpr int NW = BLOCK / kWave;
-    const int64_t off = (row / p.rows_per_seq) * p.seq_stride + (row % p.rows_per_seq) * p.row_stride;
+    // rows of consecutive sequences that follow one another in memory (the usual case) need no division
+    const int64_t off = p.seq_stride == (int64_t)p.rows_per_seq * p.row_stride
+                            ? row * p.row_stride
+                            : (row / p.rows_per_seq) * p.seq_stride + (row % p.rows_per_seq) * p.row_stride;
     const RowShape row_s = row_shape<DT>(p.logits, off, p.V);
     const SegShape rs = seg_shape<DT>(row_s, p.V, seg, p.nseg, p.seg_vecs);
     const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
@@ -646,18 +650,23 @@ __device__ __forceinline__ void sweep_unit(const SweepParams& p, int64_t row, in
         process_wave<DT, ALIGN, COUNT, true, BLOCK, U, COHERENT, EXACT, RING>(p, rs, has_next, znext, sh, cm_lane, row_s, out, out_list);
 }
 
-// Streaming kernel: grid = rows x segments.
+// u / nseg for a unit index below 2^28 (a launch has at most 2^22) without an integer division: one multiply.
+__device__ __forceinline__ uint32_t div_by_segments(uint32_t u, int nseg, uint32_t magic)
+{
+    return nseg == 1 ? u : __umulhi(u, magic);
+}
+
+// Streaming kernel: grid = rows x segments; the launch starts at row row0.
 template <int DT, bool ALIGN, bool COUNT, int BLOCK, int U>
-__global__ __launch_bounds__(BLOCK) void row_sweep_kernel(SweepParams p, int64_t unit0)
+__global__ __launch_bounds__(BLOCK) void row_sweep_kernel(SweepParams p, int64_t row0)
 {
     constexpr int NW = BLOCK / kWave;
     extern __shared__ __align__(16) unsigned char cm[];  // chunk maxima of this segment (alignment sampling only)
     __shared__ SweepShared<ALIGN ? NW : 1> sh_store;
     SweepShared<NW>& sh = *reinterpret_cast<SweepShared<NW>*>(&sh_store);  // not touched unless ALIGN
 
-    const int64_t unit = unit0 + blockIdx.x;
-    const int64_t row = unit / p.nseg;
-    sweep_unit<DT, ALIGN, COUNT, BLOCK, U>(p, row, (int)(unit - row * p.nseg), sh, cm);
+    const uint32_t q = div_by_segments(blockIdx.x, p.nseg, p.nseg_magic);
+    sweep_unit<DT, ALIGN, COUNT, BLOCK, U>(p, row0 + q, (int)(blockIdx.x - q * (uint32_t)p.nseg), sh, cm);
 }
 
 // The same sweep for sequences that use only their first max(rows_used[seq], 1) rows (tree verification).
@@ -698,7 +707,7 @@ __global__ __launch_bounds__(BLOCK) void row_sweep_used_kernel(SweepParams p, in
 
     const int units = __builtin_amdgcn_readfirstlane(offs[nseq]) * p.nseg;
     for (int unit = blockIdx.x; unit < units; unit += gridDim.x) {
-        const int crow = unit / p.nseg;
+        const int crow = (int)div_by_segments((uint32_t)unit, p.nseg, p.nseg_magic);
         int lo = 0, hi = nseq;   // the sequence s with offs[s] <= crow < offs[s + 1]
         while (hi - lo > 1) {
             const int mid = (lo + hi) >> 1;

@@ -250,6 +250,7 @@ struct VerifyFusedParams {
     VerifyTailParams t;
     unsigned* counters;   // [B][1 + (ngroups > 1 ? ngroups : 0)][kCounterWords]
     int32_t ngroups;      // 1: the sequence's counter alone
+    uint32_t rps_magic;   // floor(2^32 / rows_per_seq) + 1: row / rows_per_seq = (row * magic) >> 32, exact for row < 2^22
 };
 
 __device__ __forceinline__ bool arrive_is_last(unsigned* counter, unsigned expected)
@@ -281,7 +282,7 @@ __device__ __forceinline__ WavePartial merge_wave_partials(const WavePartial* wa
 }
 
 template <int DT, int BLOCK, int U>
-__global__ __launch_bounds__(BLOCK) void verify_fused_kernel(VerifyFusedParams p, int64_t unit0)
+__global__ __launch_bounds__(BLOCK) void verify_fused_kernel(VerifyFusedParams p, int64_t row0)
 {
     constexpr int NW = BLOCK / kWave;
     __shared__ SweepShared<1> sh_store;
@@ -290,10 +291,10 @@ __global__ __launch_bounds__(BLOCK) void verify_fused_kernel(VerifyFusedParams p
     __shared__ WavePartial wave_part[NW];
     __shared__ int s_last;
 
-    const int64_t unit = unit0 + blockIdx.x;
-    const int64_t row = unit / p.s.nseg;
-    const int seg = (int)(unit - row * p.s.nseg);
-    const int b = (int)(row / p.s.rows_per_seq);
+    const uint32_t q = div_by_segments(blockIdx.x, p.s.nseg, p.s.nseg_magic);
+    const int64_t row = row0 + q;
+    const int seg = (int)(blockIdx.x - q * (uint32_t)p.s.nseg);
+    const int b = (int)__umulhi((uint32_t)row, p.rps_magic);   // row / rows_per_seq: this form's launches have few rows
     const int tid = threadIdx.x;
 
     sweep_unit<DT, false, false, BLOCK, U, false, true, 4 * U>(p.s, row, seg, sh, nullptr, wave_part);   // 4, 8 or 16 loads per lane in flight
