@@ -746,3 +746,26 @@ def test_event_hooks_time_the_kernel_and_change_nothing():
         inner, outer = elapsed_ms(a, b), o0.elapsed_time(o1)
         assert 0.0 < inner <= outer, (name, inner, outer)
         assert hip.hipEventDestroy(a) == 0 and hip.hipEventDestroy(b) == 0
+
+
+def test_more_workgroups_than_one_launch_takes(forced_plan):
+    """1.5 million verify rows cut into 3 segments each are 4.5 million workgroups: more than one launch takes
+    (2^22), so the sweep is launched twice, the second time starting at a row far from zero.  Every sequence is checked."""
+    forced_plan("0,0,3")
+    rng = np.random.default_rng(4500000)
+    B, C, k, V = 500_000, 1, 2, 64
+    R = 1 + C * k
+    z = (rng.standard_normal((B, R, V)) * 2).astype(np.float32)
+    z[:, :, 7] += 9.0
+    drafts = rng.integers(0, V, size=(B, C, k)).astype(np.int32)
+    drafts[rng.random((B, C, k)) < 0.5] = 7
+    dl = rng.integers(0, k + 1, size=(B, C)).astype(np.int32)
+    zd = _dev_logits(z.reshape(B * R, V), "bf16").view(B, R, V)
+    t = lambda a, dt: torch.as_tensor(np.ascontiguousarray(a), device=DEV).to(dt)
+    out = bk.to_np(aasd.verify(zd, t(drafts, torch.int32), t(dl, torch.int32), None, alpha=0.1, beta=0.1))
+    torch.cuda.synchronize()
+    ref = bk.oracle_verify_seqs(synth.to_host_bits(zd), drafts, dl, None, bk.f32(0.1), bk.f32(0.1))
+    tally = bk.Tally()
+    bk.compare_verify(out, ref, tally)
+    assert ref["accept_len"].max() == 2 and 0.2 < (ref["accept_len"] > 0).mean() < 0.9
+    print("4.5 million workgroups", tally)
