@@ -193,6 +193,23 @@ __device__ __forceinline__ RowShape row_shape(const void* logits, int64_t elt_of
     return s;
 }
 
+// Index of the first element equal to m in the chunk that starts at `code` (the sweep names the chunk that holds a
+// row's maximum, not the element): one 16-byte load for a chunk of the aligned body, the element itself otherwise.
+template <int DT>
+__device__ __forceinline__ int first_equal_in_chunk(const RowShape& rs, int code, float m)
+{
+    constexpr int EPV = Elt<DT>::kPerVec;
+    if (code < rs.head || code >= rs.tail0) return code;
+    const u32x4 v = rs.vbase[(code - rs.head) / EPV];
+    float z[EPV];
+    unpack<DT>(v, z);
+    int at = code;
+#pragma unroll
+    for (int e = EPV - 1; e >= 0; --e)
+        if (z[e] == m) at = code + e;
+    return at;
+}
+
 // The part of a row one workgroup sweeps: a run of vectors, plus the unaligned head elements
 // (first segment) and tail elements (last segment) of the row.
 struct SegShape {

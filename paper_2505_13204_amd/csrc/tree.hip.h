@@ -261,11 +261,9 @@ __device__ __forceinline__ void verify_tree_block(const VerifyTreeParams& p, int
             if (have_row && s == 0) {
                 int am = 0;
                 if ((unsigned)code < (unsigned)p.V) {
-                    am = code;    // the chunk that holds the maximum: the first element of it that attains it
+                    // the chunk that holds the maximum: the first element of it that attains it
                     const RowShape rs = row_shape<DT>(p.logits, (int64_t)b * p.seq_stride + (int64_t)r * p.row_stride, p.V);
-                    const int len = (code >= rs.head && code < rs.tail0) ? Elt<DT>::kPerVec : 1;
-                    for (int e = 0; e < len; ++e)
-                        if (load_elt<DT>(rs.base, code + e) == m) { am = code + e; break; }
+                    am = first_equal_in_chunk<DT>(rs, code, m);
                 }
                 const float H = entropy_from_sums(S, T2);
                 const float pmax = 1.0f / S;

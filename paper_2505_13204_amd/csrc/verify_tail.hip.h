@@ -140,9 +140,7 @@ __device__ __forceinline__ void verify_tail_block(const VerifyTailParams& p, int
                     am = code;
                     if (!EXACT) {
                         const RowShape rs = row_shape<DT>(p.logits, (int64_t)b * p.seq_stride + (int64_t)r * p.row_stride, p.V);
-                        const int len = (code >= rs.head && code < rs.tail0) ? Elt<DT>::kPerVec : 1;
-                        for (int e = 0; e < len; ++e)
-                            if (load_elt<DT>(rs.base, code + e) == m) { am = code + e; break; }
+                        am = first_equal_in_chunk<DT>(rs, code, m);
                     }
                 }
                 const float H = entropy_from_sums(S, T2);
