@@ -227,7 +227,9 @@ def per_step_block(torch, np, aasd, label, logits_steps, tokens, lens, plens, w,
             "retrieve_plus_verify_us": {"eager": rnd(eager), "hip_graph": rnd(graph_us)},
             "scan_plus_verify_us": {"eager": rnd(scan_eager), "hip_graph": rnd(scan_graph)},
             "pool_step_plus_verify_us": {"eager": rnd(pool_eager), "hip_graph": rnd(pool_graph)},
-            "verify_one_launch_us": {"eager": rnd(v_eager), "hip_graph": rnd(v_graph), "kernel_event_median": rnd(kern)},
+            "verify_us": {"eager": rnd(v_eager), "hip_graph": rnd(v_graph), "sweep_kernel_event_median": rnd(kern),
+                          "launches": aasd.verify_launches(B, w.C, w.k, V, dt_code, True),
+                          "note": "aasd_verify with a zeroed workspace: the library takes the one-launch form where it is the faster one"},
             "verify_two_launches_us": {"eager": rnd(t_eager), "hip_graph": rnd(t_graph)},
             "verify_GB/s": round(step_bytes / best / 1e3, 1), "verify_frac_of_hbm_peak": round(step_bytes / best / 1e3 / HBM_PEAK_GBS, 4),
             "note": ("logit bytes of one step / time of the aasd_verify call alone (its faster launch mode); the time includes "

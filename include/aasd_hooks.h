@@ -35,6 +35,12 @@ void aasd_hook_draw_events(void *start, void *stop);
  */
 int aasd_hook_sweep_plan(int32_t threads, int32_t loads, int32_t segments);
 
+/*
+ * How many kernels aasd_verify would enqueue for these sizes and flags under the plan in force: 1 (sweep and
+ * decisions in one launch: needs AASD_VERIFY_ZEROED_WORKSPACE and a call small enough) or 2; 0 for invalid sizes.
+ */
+int aasd_hook_verify_launches(int32_t B, int32_t C, int32_t k, int32_t V, int32_t dt, uint32_t flags);
+
 #ifdef __cplusplus
 }
 #endif

@@ -53,6 +53,11 @@ def set_sweep_plan(threads: int = 0, loads: int = 0, segments: int = 0):
     _check(_lib.load().aasd_hook_sweep_plan(threads, loads, segments))
 
 
+def verify_launches(B: int, C: int, k: int, V: int, dt: int, zeroed_workspace: bool = False) -> int:
+    """Measurement hook: the number of kernels aasd_verify would enqueue for these sizes (1 = the one-launch form)."""
+    return int(_lib.load().aasd_hook_verify_launches(B, C, k, V, dt, VERIFY_ZEROED_WORKSPACE if zeroed_workspace else 0))
+
+
 def _dtype_code(t: torch.Tensor) -> int:
     if t.dtype == torch.float32:
         return F32

@@ -36,6 +36,8 @@ def load():
     lib.aasd_hook_draw_events.argtypes = [c_void_p, c_void_p]
     lib.aasd_hook_sweep_plan.restype = c_int32
     lib.aasd_hook_sweep_plan.argtypes = [c_int32, c_int32, c_int32]
+    lib.aasd_hook_verify_launches.restype = c_int32
+    lib.aasd_hook_verify_launches.argtypes = [c_int32, c_int32, c_int32, c_int32, c_int32, c_uint32]
     lib.aasd_align_sample.restype = c_int32
     lib.aasd_align_sample.argtypes = [
         c_void_p, c_int32, c_int64, c_int32, c_int64, c_void_p, c_int32, c_int32, c_int32, c_uint64, c_uint64,

@@ -121,8 +121,9 @@ __device__ __forceinline__ int wave_min(int v)
     return min(min(lane_value(v, 0), lane_value(v, 16)), min(lane_value(v, 32), lane_value(v, 48)));
 }
 
-// All-reduce over the lane's aligned group of G lanes (G a power of two, the same in every lane): inside a row of
-// 16 lanes through the vector ALU's cross-lane moves, beyond it through LDS permutes.  The order of combination is fixed.
+// All-reduce over the lane's aligned group of G <= 64 lanes (G a power of two, the same in every lane; every lane of
+// the wave takes part): inside a row of 16 lanes through the vector ALU's cross-lane moves, beyond it through scalar
+// registers.  The order of combination is fixed.
 template <class T, class OP>
 __device__ __forceinline__ T group_reduce(T v, int G, OP op)
 {
@@ -130,7 +131,11 @@ __device__ __forceinline__ T group_reduce(T v, int G, OP op)
     if (G > 2) v = op(v, dpp_move<kDppSwap2>(v));
     if (G > 4) v = op(v, dpp_move<kDppHalfMirror>(v));
     if (G > 8) v = op(v, dpp_move<kDppMirror>(v));
-    for (int o = 16; o < G; o <<= 1) v = op(v, __shfl_xor(v, o));
+    if (G > 16) {   // 32 or 64 lanes: every row of 16 holds its result by now; the rows' results through scalar registers
+        const T r0 = lane_value(v, 0), r1 = lane_value(v, 16), r2 = lane_value(v, 32), r3 = lane_value(v, 48);
+        if (G >= 64) v = op(op(r0, r1), op(r2, r3));
+        else v = (threadIdx.x & 32) ? op(r2, r3) : op(r0, r1);
+    }
     return v;
 }
 

@@ -135,23 +135,34 @@ __device__ __forceinline__ void verify_tail_block(const VerifyTailParams& p, int
             const float T2 = group_reduce(live ? (wp.T + dl2 * wp.S) * f : 0.f, G, [](float x, float y) { return x + y; });
             const int code = group_reduce(live && wp.m == m ? wp.code : 0x7fffffff, G, [](int x, int y) { return min(x, y); });
             if (have_row && s == 0) {
-                int am = 0;
-                if ((unsigned)code < (unsigned)p.V) {
-                    am = code;
-                    if (!EXACT) {
-                        const RowShape rs = row_shape<DT>(p.logits, (int64_t)b * p.seq_stride + (int64_t)r * p.row_stride, p.V);
-                        am = first_equal_in_chunk<DT>(rs, code, m);
-                    }
-                }
+                // EXACT: the code is the greedy pick itself.  Otherwise it names the chunk that holds it, and the pick is
+                // found below, by a load that is in flight while the tokens are decided (they do not need it).
+                const int am = (unsigned)code < (unsigned)p.V ? code : (EXACT ? 0 : -1);
                 const float H = entropy_from_sums(S, T2);
                 sh.stats[r] = make_float4(m, S, H, __int_as_float(am));
                 if (p.row_entropy) p.row_entropy[row] = H;
                 if (p.row_pmax) p.row_pmax[row] = 1.0f / S;
-                if (p.row_argmax) p.row_argmax[row] = am;
+                if (EXACT && p.row_argmax) p.row_argmax[row] = am;
             }
         }
     }
     __syncthreads();
+
+    // the chunks that hold the rows' maxima (a thread per row): asked for here, used after the decisions
+    constexpr int kRowsPerThread = EXACT ? 0 : (kMaxVerifyRows + NT - 1) / NT;
+    u32x4 am_chunk[kRowsPerThread > 0 ? kRowsPerThread : 1];
+    if (!EXACT) {
+#pragma unroll
+        for (int q = 0; q < kRowsPerThread; ++q) {
+            const int r = tid + q * NT;
+            am_chunk[q] = u32x4{0u, 0u, 0u, 0u};
+            if (r < R) {
+                const int code = __float_as_int(sh.stats[r].w);
+                const RowShape rs = row_shape<DT>(p.logits, (int64_t)b * p.seq_stride + (int64_t)r * p.row_stride, p.V);
+                if (code >= rs.head && code < rs.tail0) am_chunk[q] = rs.vbase[(code - rs.head) / Elt<DT>::kPerVec];
+            }
+        }
+    }
 
 #pragma unroll
     for (int ps = 0; ps < kPasses; ++ps) {
@@ -201,6 +212,27 @@ __device__ __forceinline__ void verify_tail_block(const VerifyTailParams& p, int
             // evaluated tokens: the accepted ones and the first failure
             const unsigned ev = (a + 1 >= 32) ? 0xffffffffu : ((1u << (a + 1)) - 1u);
             sh.near_c[cand] = (unsigned)__popc(nfield & ev);
+        }
+    }
+    if (!EXACT) {
+#pragma unroll
+        for (int q = 0; q < kRowsPerThread; ++q) {
+            const int r = tid + q * NT;
+            if (r < R) {
+                const int code = __float_as_int(sh.stats[r].w);
+                int am = code < 0 ? 0 : code;   // a chunk of the aligned body: its first element equal to the maximum
+                const RowShape rs = row_shape<DT>(p.logits, (int64_t)b * p.seq_stride + (int64_t)r * p.row_stride, p.V);
+                if (code >= rs.head && code < rs.tail0) {
+                    float z[Elt<DT>::kPerVec];
+                    unpack<DT>(am_chunk[q], z);
+                    const float m = sh.stats[r].x;
+#pragma unroll
+                    for (int e = Elt<DT>::kPerVec - 1; e >= 0; --e)
+                        if (z[e] == m) am = code + e;
+                }
+                sh.stats[r].w = __int_as_float(am);
+                if (p.row_argmax) p.row_argmax[(int64_t)b * R + r] = am;
+            }
         }
     }
     __syncthreads();

@@ -257,3 +257,17 @@ def test_header_is_plain_c(tmp_path):
     src.write_text('#include "aasd.h"\n#include "aasd_hooks.h"\nint main(void) { return (int)sizeof(aasd_status) + AASD_MAX_TREE_NODES > 0 ? 0 : 1; }\n')
     subprocess.check_call(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-fsyntax-only",
                            "-I", os.path.join(ROOT, "include"), str(src)])
+
+
+def test_which_form_a_verification_takes(lib):
+    """One launch only with a zeroed counter area and for a small call (measured: from about 128 rows on two are faster)."""
+    lib.aasd_hook_verify_launches.restype = ctypes.c_int32
+    lib.aasd_hook_verify_launches.argtypes = [ctypes.c_int32] * 5 + [ctypes.c_uint32]
+    ZEROED = 2
+    assert lib.aasd_hook_verify_launches(1, 1, 8, 128256, 1, ZEROED) == 1      # 9 rows
+    assert lib.aasd_hook_verify_launches(14, 1, 8, 128256, 1, ZEROED) == 1     # 126 rows
+    assert lib.aasd_hook_verify_launches(32, 1, 8, 128256, 1, ZEROED) == 2     # 288 rows
+    assert lib.aasd_hook_verify_launches(1, 1, 8, 128256, 1, 0) == 2           # nobody vouches for the counters
+    assert lib.aasd_hook_verify_launches(1, 16, 8, 152064, 1, ZEROED) == 2     # 129 rows
+    assert lib.aasd_hook_verify_launches(0, 1, 8, 128256, 1, ZEROED) == 0 and lib.aasd_hook_verify_launches(1, 1, 8, 0, 1, 0) == 0
+

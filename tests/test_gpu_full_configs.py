@@ -48,7 +48,8 @@ def _check_align(w, z, nt, mode, tally, row_id_base=0, chunk=8192):
 def _decode_and_check(w, tally, keep_steps=None, one_launch=False):
     """The decode loop on the HIP path (one aasd_retrieve_drafts and one aasd_verify per step, the per-step shape),
     then the oracle: every retrieval of every step, and the verify rows of the kept steps (all steps if
-    keep_steps is None).  As every checked step's outputs equal the oracle's on the same inputs, the loop has
+    keep_steps is None).  one_launch: the steps pass a zeroed workspace, and the library takes the one-launch form
+    where it is the faster one (9-row steps; the 288-row steps of batched_serving go out as two kernels).  As every checked step's outputs equal the oracle's on the same inputs, the loop has
     followed the oracle's trajectory up to that step.  Returns the trace and the number of verify rows checked."""
     hip = bk.HipBackend(DEV, one_launch=one_launch)
     kept = {}
@@ -105,7 +106,7 @@ def test_long_context_in_full():
     assert len(trace.steps) == w.steps == 1024 and rows == 1024 * 9
     near = _check_batched_verify(w, trace, kept, tally)
     print(f"long_context covered: prefill rows {w.L} of {w.L} x 2 modes, retrievals {w.steps} of {w.steps}, "
-          f"verify rows {rows} of {w.steps * w.R} (per step, one launch each) and again as one batch; near {near}; {tally}")
+          f"verify rows {rows} of {w.steps * w.R} (per step, in the one-launch form) and again as one batch; near {near}; {tally}")
 
 
 def test_batched_serving_in_full():
