@@ -259,22 +259,30 @@ __device__ __forceinline__ void verify_tree_block(const VerifyTreeParams& p, int
             const float T2 = group_reduce(live ? (wp.T + dl2 * wp.S) * f : 0.f, G, [](float x, float y) { return x + y; });
             const int code = group_reduce(live && wp.m == m ? wp.code : 0x7fffffff, G, [](int x, int y) { return min(x, y); });
             if (have_row && s == 0) {
-                int am = 0;
-                if ((unsigned)code < (unsigned)p.V) {
-                    // the chunk that holds the maximum: the first element of it that attains it
-                    const RowShape rs = row_shape<DT>(p.logits, (int64_t)b * p.seq_stride + (int64_t)r * p.row_stride, p.V);
-                    am = first_equal_in_chunk<DT>(rs, code, m);
-                }
+                // the code names the chunk that holds the row's maximum; the greedy pick is found below, by a load that
+                // is in flight while the nodes are decided (they do not need it)
                 const float H = entropy_from_sums(S, T2);
                 const float pmax = 1.0f / S;
-                sh.stats[r] = make_float4(m, S, H, __int_as_float(am));
+                sh.stats[r] = make_float4(m, S, H, __int_as_float((unsigned)code < (unsigned)p.V ? code : -1));
                 if (p.row_entropy) p.row_entropy[row] = H;
                 if (p.row_pmax) p.row_pmax[row] = pmax;
-                if (p.row_argmax) p.row_argmax[row] = am;
             }
         }
     }
     __syncthreads();
+
+    static_assert(kPer * NT >= AASD_MAX_TREE_NODES, "a thread per row as well");
+    u32x4 am_chunk[kPer];
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) {
+        const int r = tid + j * NT;
+        am_chunk[j] = u32x4{0u, 0u, 0u, 0u};
+        if (r < n) {
+            const int code = __float_as_int(sh.stats[r].w);
+            const RowShape rs = row_shape<DT>(p.logits, (int64_t)b * p.seq_stride + (int64_t)r * p.row_stride, p.V);
+            if (code >= rs.head && code < rs.tail0) am_chunk[j] = rs.vbase[(code - rs.head) / Elt<DT>::kPerVec];
+        }
+    }
 
     // ---- per-node decision against the parent's row ----
 #pragma unroll
@@ -310,6 +318,26 @@ __device__ __forceinline__ void verify_tree_block(const VerifyTreeParams& p, int
         sh.near[i] = near;
         if (p.node_p) p.node_p[bi] = pf;
         if (p.node_delta) p.node_delta[bi] = df;
+    }
+    // the rows' greedy picks: the first element of the chunk that equals the maximum
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) {
+        const int r = tid + j * NT;
+        if (r < n) {
+            const int code = __float_as_int(sh.stats[r].w);
+            int am = code < 0 ? 0 : code;
+            const RowShape rs = row_shape<DT>(p.logits, (int64_t)b * p.seq_stride + (int64_t)r * p.row_stride, p.V);
+            if (code >= rs.head && code < rs.tail0) {
+                float z[Elt<DT>::kPerVec];
+                unpack<DT>(am_chunk[j], z);
+                const float m = sh.stats[r].x;
+#pragma unroll
+                for (int e = Elt<DT>::kPerVec - 1; e >= 0; --e)
+                    if (z[e] == m) am = code + e;
+            }
+            sh.stats[r].w = __int_as_float(am);
+            if (p.row_argmax) p.row_argmax[(int64_t)b * N + r] = am;
+        }
     }
     __syncthreads();
 
