@@ -127,15 +127,15 @@ SweepPlan plan_fused(int64_t rows, int32_t V, int32_t dt)
 }
 
 // Whether a verification with a zeroed counter area goes out as one launch.  Measured (graph-replayed calls, V = 128256
-// bf16): one launch wins while the call is small (9 rows: 6.8 us against 7.5 in two launches; 72 rows: 11.0 against
-// 11.4); from about 128 rows on the two kernels win (288 rows: 18.9 against 19.4), because the sweep kernel may then
-// cut rows into more and shorter workgroups than the GPU holds at once, which the one-launch form must not (its
-// workgroups end with a trip to memory and an arrival, hidden only while they all run together; 8256 rows: 413 us
-// against 397).
-constexpr int64_t kOneLaunchMaxRows = 128;
-bool takes_one_launch(int64_t rows, const SweepPlan& pf)
+// bf16): one launch wins while the call is small (9 rows: 6.9 us against 7.5 in two launches; 72 rows: 11.0 against
+// 11.4); from about 128 rows = 32 MiB of logits on the two kernels win (288 rows: 18.7 against 19.4), because the sweep
+// kernel may then cut rows into more and shorter workgroups than the GPU holds at once, which the one-launch form must
+// not (its workgroups end with a trip to memory and an arrival, hidden only while they all run together; 8256 rows:
+// 413 us against 397).
+constexpr int64_t kOneLaunchMaxBytes = (int64_t)32 << 20;
+bool takes_one_launch(int64_t rows, int32_t V, int32_t dt, const SweepPlan& pf)
 {
-    return rows <= kOneLaunchMaxRows && rows * pf.nseg <= fused_resident(pf.block, pf.unroll);
+    return rows * V * (int64_t)elt_size(dt) <= kOneLaunchMaxBytes && rows * pf.nseg <= fused_resident(pf.block, pf.unroll);
 }
 
 // the (threads, loads in flight) shapes the sweep kernels are compiled for
@@ -379,7 +379,7 @@ int verify_launch(const void* logits, int32_t dt, int32_t B, int32_t C, int32_t 
     SweepPlan pl = plan_sweep(false, rows, V, dt);
     if (one_launch) {
         const SweepPlan pf = plan_fused(rows, V, dt);
-        if (takes_one_launch(rows, pf)) pl = pf;
+        if (takes_one_launch(rows, V, dt, pf)) pl = pf;
         else one_launch = false;
     }
     aasd::SweepParams sp{};
@@ -432,7 +432,7 @@ int aasd_hook_verify_launches(int32_t B, int32_t C, int32_t k, int32_t V, int32_
 {
     if (B < 1 || C < 1 || C > AASD_MAX_CANDIDATES || k < 1 || k > AASD_MAX_DRAFT || V <= 0 || !valid_dtype(dt)) return 0;
     const int64_t rows = (int64_t)B * (1 + (int64_t)C * k);
-    return (flags & AASD_VERIFY_ZEROED_WORKSPACE) && takes_one_launch(rows, plan_fused(rows, V, dt)) ? 1 : 2;
+    return (flags & AASD_VERIFY_ZEROED_WORKSPACE) && takes_one_launch(rows, V, dt, plan_fused(rows, V, dt)) ? 1 : 2;
 }
 
 void aasd_hook_draw_events(void* start, void* stop)
