@@ -192,9 +192,9 @@ size_t aasd_verify_workspace_bytes(int32_t B, int32_t C, int32_t k, int32_t V, i
  * workspace : DEVICE scratch of at least aasd_verify_workspace_bytes(B, C, k, V, dt) bytes, 128-byte
  *             aligned; it needs no initialisation and holds nothing of value afterwards.
  *             The call enqueues two kernels (row sweep, then decisions).  With
- *             AASD_VERIFY_ZEROED_WORKSPACE it may enqueue ONE instead (it does when the rows are few
- *             enough for all workgroups of the launch to be on the GPU at once, the case of a decode
- *             step), in which the last workgroup to finish a
+ *             AASD_VERIFY_ZEROED_WORKSPACE it may enqueue ONE instead (it does for a small call, up
+ *             to 32 MiB of logits, the case of a decode step of a few sequences, where one launch is
+ *             the faster form), in which the last workgroup to finish a
  *             sequence's rows also takes that sequence's decisions; this form counts finished
  *             workgroups in counters at the start of the workspace, which must be zero when the
  *             kernel starts and are zero again when it ends.  By setting the flag the caller vouches
@@ -223,7 +223,7 @@ int aasd_verify(const void *logits, int32_t dt, int32_t B, int32_t C, int32_t k,
  *     aasd_verify_workspace_bytes(B, C, k, V, dt) minus its counters; this covers every decode step up to
  *     32768 rows (B * (1 + C*k)).  Larger calls return AASD_ERR_UNSUPPORTED and enqueue nothing: use
  *     aasd_verify with a workspace for them.
- *   - Decode-step shapes run as one launch (the form AASD_VERIFY_ZEROED_WORKSPACE selects in aasd_verify;
+ *   - Small calls run as one launch (the form AASD_VERIFY_ZEROED_WORKSPACE selects in aasd_verify;
  *     the flag itself is not accepted here): the library keeps its own counters at zero.
  *   - Every call on one GPU uses that GPU's one scratch array: calls that overlap in time on the same GPU
  *     (two streams, two threads) race and give undefined outputs; calls ordered on one stream are safe.
