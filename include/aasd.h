@@ -193,8 +193,9 @@ size_t aasd_verify_workspace_bytes(int32_t B, int32_t C, int32_t k, int32_t V, i
  *             aligned; it needs no initialisation and holds nothing of value afterwards.
  *             The call enqueues two kernels (row sweep, then decisions).  With
  *             AASD_VERIFY_ZEROED_WORKSPACE it may enqueue ONE instead (it does for a small call, up
- *             to 32 MiB of logits, the case of a decode step of a few sequences, where one launch is
- *             the faster form), in which the last workgroup to finish a
+ *             to 32 MiB of logits, the case of a decode step of a few sequences, where the launches
+ *             are what the call costs the host; replayed from a graph the two kernels are as fast),
+ *             in which the last workgroup to finish a
  *             sequence's rows also takes that sequence's decisions; this form counts finished
  *             workgroups in counters at the start of the workspace, which must be zero when the
  *             kernel starts and are zero again when it ends.  By setting the flag the caller vouches

@@ -126,12 +126,13 @@ SweepPlan plan_fused(int64_t rows, int32_t V, int32_t dt)
     return pl;
 }
 
-// Whether a verification with a zeroed counter area goes out as one launch.  Measured (graph-replayed calls, V = 128256
-// bf16): one launch wins while the call is small (9 rows: 6.9 us against 7.5 in two launches; 72 rows: 11.0 against
-// 11.4); from about 128 rows = 32 MiB of logits on the two kernels win (288 rows: 18.7 against 19.4), because the sweep
-// kernel may then cut rows into more and shorter workgroups than the GPU holds at once, which the one-launch form must
-// not (its workgroups end with a trip to memory and an arrival, hidden only while they all run together; 8256 rows:
-// 413 us against 397).
+// Whether a verification with a zeroed counter area goes out as one launch.  One launch saves the host a launch
+// (V = 128256 bf16, 9 rows, calls issued back to back: 10.6 us per call against 13.0); on the GPU the two kernels are
+// by now as fast or faster (replayed from a graph: 9 rows 6.9 us in one launch, 6.7 in two; 288 rows 19.4 and 18.1),
+// because the sweep kernel may cut rows into more and shorter workgroups than the GPU holds at once, which the
+// one-launch form must not (its workgroups end with a trip to memory and an arrival, hidden only while they all run
+// together; 8256 rows: 413 us against 397).  So the flag buys one launch where launches are what a call costs: up to
+// 32 MiB of logits (128 rows at this V).
 constexpr int64_t kOneLaunchMaxBytes = (int64_t)32 << 20;
 bool takes_one_launch(int64_t rows, int32_t V, int32_t dt, const SweepPlan& pf)
 {
@@ -401,6 +402,12 @@ int verify_launch(const void* logits, int32_t dt, int32_t B, int32_t C, int32_t 
         fp.t.npart = pl.nseg;   // this form leaves one partial per workgroup, not per wave
         fp.rps_magic = div_magic((int32_t)R);   // R >= 2
         return dt == AASD_BF16 ? launch_fused<AASD_BF16>(fp, pl, rows, s) : launch_fused<AASD_F32>(fp, pl, rows, s);
+    }
+    if (pl.nseg >= 8 && pl.block > aasd::kWave) {
+        // a short launch cut into many segments: one partial per workgroup instead of one per wave (up to 64 per row
+        // otherwise), so that the tail merges a sequence's rows in one pass
+        sp.merge_waves = 1;
+        tp.npart = pl.nseg;
     }
     const int rc = dt == AASD_BF16 ? launch_sweep<AASD_BF16, false, false>(sp, pl, rows, 0, s)
                                    : launch_sweep<AASD_F32, false, false>(sp, pl, rows, 0, s);

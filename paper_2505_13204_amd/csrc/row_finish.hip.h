@@ -20,13 +20,6 @@ struct RowStats {
     unsigned cnt;
 };
 
-// Scale factor and exponent shift that bring a partial with maximum pm to the row maximum m.
-__device__ __forceinline__ void partial_scale(float pm, float m, float& dl, float& f)
-{
-    dl = (pm - m) * kLog2e;  // <= 0, log2 units
-    f = __builtin_amdgcn_exp2f(dl);
-}
-
 __device__ __forceinline__ float entropy_from_sums(float S, float T2)
 {
     const float H = logf(S) - (float)kLn2 * T2 / S;

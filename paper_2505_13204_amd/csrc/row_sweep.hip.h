@@ -87,6 +87,7 @@ struct SweepParams {
     int32_t cm_stride;     // bytes between the chunk-maximum rows of neighbouring lanes
     int32_t nseg;          // segments per row
     uint32_t nseg_magic;   // floor(2^32 / nseg) + 1 (0 for nseg = 1): u / nseg = (u * magic) >> 32, exact for u < 2^28
+    int32_t merge_waves;   // verification sweep: the workgroup merges its waves' partials and writes ONE per (row, segment)
     int32_t seg_vecs;      // 16-byte vectors per segment (a multiple of the block size)
     WavePartial* partials; // [rows][nseg * waves per block]
     int32_t* lists;        // [rows][nseg * waves per block][kListCap] first-element indices of listed chunks
@@ -667,6 +668,33 @@ __device__ __forceinline__ void sweep_unit(const SweepParams& p, int64_t row, in
         process_wave<DT, ALIGN, COUNT, true, BLOCK, U, COHERENT, EXACT, RING>(p, rs, has_next, znext, sh, cm_lane, row_s, out, out_list);
 }
 
+// Scale factor and exponent shift that bring a partial with maximum pm to the row maximum m.
+__device__ __forceinline__ void partial_scale(float pm, float m, float& dl, float& f)
+{
+    dl = (pm - m) * kLog2e;  // <= 0, log2 units
+    f = __builtin_amdgcn_exp2f(dl);
+}
+
+// The partials of a workgroup's NW waves (in LDS) merged into one; called by the lanes of the first wave, the
+// result is complete in every lane.
+template <int NW>
+__device__ __forceinline__ WavePartial merge_wave_partials(const WavePartial* wave_part, int lane)
+{
+    WavePartial wp;
+    wp.m = -INFINITY; wp.S = 0.f; wp.T = 0.f; wp.code = 0x7fffffff;
+    if (lane < NW) wp = wave_part[lane];
+    const float m = group_reduce(wp.m, NW, [](float x, float y) { return fmaxf(x, y); });
+    const bool live = wp.S > 0.f;
+    float dl2 = 0.f, f = 0.f;
+    if (live) partial_scale(wp.m, m, dl2, f);
+    const float S = group_reduce(live ? wp.S * f : 0.f, NW, [](float x, float y) { return x + y; });
+    const float T2 = group_reduce(live ? (wp.T + dl2 * wp.S) * f : 0.f, NW, [](float x, float y) { return x + y; });
+    const int code = group_reduce(live && wp.m == m ? wp.code : 0x7fffffff, NW, [](int x, int y) { return min(x, y); });
+    WavePartial out;
+    out.m = m; out.S = S; out.T = T2; out.code = code; out.cnt = 0; out.nlist = 0; out.thr2 = -INFINITY; out.pad = 0;
+    return out;
+}
+
 // u / nseg for a unit index below 2^28 (a launch has at most 2^22) without an integer division: one multiply.
 __device__ __forceinline__ uint32_t div_by_segments(uint32_t u, int nseg, uint32_t magic)
 {
@@ -683,7 +711,21 @@ __global__ __launch_bounds__(BLOCK) void row_sweep_kernel(SweepParams p, int64_t
     SweepShared<NW>& sh = *reinterpret_cast<SweepShared<NW>*>(&sh_store);  // not touched unless ALIGN
 
     const uint32_t q = div_by_segments(blockIdx.x, p.nseg, p.nseg_magic);
-    sweep_unit<DT, ALIGN, COUNT, BLOCK, U>(p, row0 + q, (int)(blockIdx.x - q * (uint32_t)p.nseg), sh, cm);
+    const int64_t row = row0 + q;
+    const int seg = (int)(blockIdx.x - q * (uint32_t)p.nseg);
+    if constexpr (!ALIGN) {
+        if (p.merge_waves) {   // one partial per workgroup: a short launch with many segments per row, whose tail is then shorter
+            __shared__ WavePartial wave_part[NW];
+            sweep_unit<DT, ALIGN, COUNT, BLOCK, U>(p, row, seg, sh, cm, wave_part);
+            __syncthreads();
+            if (threadIdx.x < kWave) {
+                const WavePartial out = merge_wave_partials<NW>(wave_part, threadIdx.x);
+                if (threadIdx.x == 0) p.partials[row * p.nseg + seg] = out;
+            }
+            return;
+        }
+    }
+    sweep_unit<DT, ALIGN, COUNT, BLOCK, U>(p, row, seg, sh, cm);
 }
 
 // The same sweep for sequences that use only their first max(rows_used[seq], 1) rows (tree verification).

@@ -291,26 +291,6 @@ __device__ __forceinline__ bool arrive_is_last(unsigned* counter, unsigned expec
     return true;
 }
 
-// The partials of a workgroup's NW waves (in LDS) merged into one; called by the lanes of the first wave, the
-// result is complete in every lane.
-template <int NW>
-__device__ __forceinline__ WavePartial merge_wave_partials(const WavePartial* wave_part, int lane)
-{
-    WavePartial wp;
-    wp.m = -INFINITY; wp.S = 0.f; wp.T = 0.f; wp.code = 0x7fffffff;
-    if (lane < NW) wp = wave_part[lane];
-    const float m = group_reduce(wp.m, NW, [](float x, float y) { return fmaxf(x, y); });
-    const bool live = wp.S > 0.f;
-    float dl2 = 0.f, f = 0.f;
-    if (live) partial_scale(wp.m, m, dl2, f);
-    const float S = group_reduce(live ? wp.S * f : 0.f, NW, [](float x, float y) { return x + y; });
-    const float T2 = group_reduce(live ? (wp.T + dl2 * wp.S) * f : 0.f, NW, [](float x, float y) { return x + y; });
-    const int code = group_reduce(live && wp.m == m ? wp.code : 0x7fffffff, NW, [](int x, int y) { return min(x, y); });
-    WavePartial out;
-    out.m = m; out.S = S; out.T = T2; out.code = code; out.cnt = 0; out.nlist = 0; out.thr2 = -INFINITY; out.pad = 0;
-    return out;
-}
-
 template <int DT, int BLOCK, int U>
 __global__ __launch_bounds__(BLOCK) void verify_fused_kernel(VerifyFusedParams p, int64_t row0)
 {
