@@ -48,8 +48,9 @@ def _check_align(w, z, nt, mode, tally, row_id_base=0, chunk=8192):
 def _decode_and_check(w, tally, keep_steps=None, one_launch=False):
     """The decode loop on the HIP path (one aasd_retrieve_drafts and one aasd_verify per step, the per-step shape),
     then the oracle: every retrieval of every step, and the verify rows of the kept steps (all steps if
-    keep_steps is None).  one_launch: the steps pass a zeroed workspace, and the library takes the one-launch form
-    where it is the faster one (9-row steps; the 288-row steps of batched_serving go out as two kernels).  As every checked step's outputs equal the oracle's on the same inputs, the loop has
+    keep_steps is None).  one_launch: the steps pass a zeroed workspace with AASD_VERIFY_ZEROED_WORKSPACE, and the
+    library takes the one-launch form up to 32 MiB of logits (9-row steps; the 288-row steps of batched_serving go out
+    as two kernels, the sweep writing one partial per workgroup).  As every checked step's outputs equal the oracle's on the same inputs, the loop has
     followed the oracle's trajectory up to that step.  Returns the trace and the number of verify rows checked."""
     hip = bk.HipBackend(DEV, one_launch=one_launch)
     kept = {}
