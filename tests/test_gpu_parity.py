@@ -346,6 +346,31 @@ def test_verify_strided_sequences_and_determinism():
             assert a[name].tobytes() == b[name].tobytes(), name
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_verify_short_launch_of_many_segments_with_masked_logits_and_unaligned_rows(dtype):
+    """Few rows of a large vocabulary: the sweep cuts every row into many segments and its workgroups merge their
+    waves' partials.  Rows start at any element offset (odd row stride inside a larger buffer), a third of the
+    logits are -inf, one row has a single finite logit and one segment of one row is -inf throughout."""
+    rng = np.random.default_rng(77)
+    B, C, k, V = 2, 2, 3, 40003
+    R = 1 + C * k
+    zd, drafts, dl, strict = _verify_case(rng, B, C, k, V, dtype, peaked=True)
+    z = zd.float().cpu().numpy()
+    z[rng.random(z.shape) < 0.33] = -np.inf
+    z[0, 1, :] = -np.inf; z[0, 1, 31111] = 0.5
+    z[1, 2, 10000:13000] = -np.inf
+    for b in range(B):      # the first draft of every candidate is the bonus row's best finite token: something is accepted
+        drafts[b, :, 0] = int(np.argmax(z[b, 0]))
+    big = torch.full((B, R + 1, V + 7), 77.0, dtype=zd.dtype, device=DEV)     # the padding would win every row if it were read
+    big[:, :R, :V] = torch.from_numpy(z).to(DEV).to(zd.dtype)
+    tally = bk.Tally()
+    for alpha, beta, flags, st in [(0.1, 0.1, 0, strict), (0.3, 0.05, 0, None), (0.0, 0.2, aasd.VERIFY_NO_CLAMP, None)]:
+        ref = _verify_both(big[:, :R, :V], drafts, dl, st, alpha, beta, flags, tally)
+    assert aasd.verify_launches(B, C, k, V, aasd.BF16 if dtype == "bf16" else aasd.F32) == 2
+    assert ref["accept_len"].max() >= 1
+    print("masked short launch", dtype, tally)
+
+
 # --------------------------------------------------------------------------- the five workloads
 def _align_workload(w, b, rows, tally, peaked=False, mode=oracle.EXTRAS_TOP):
     g, copied = synth.token_stream(w, b)
