@@ -927,6 +927,7 @@ int aasd_build_tree(const int32_t* drafts, const int32_t* draft_len, const uint8
     aasd::BuildTreeParams p{};
     p.drafts = drafts; p.draft_len = draft_len; p.strict = strict; p.draft_extras = draft_extras; p.m_x = m;
     p.root_tok = root_tok; p.B = B; p.C = C; p.k = k; p.max_nodes = max_nodes;
+    p.w_magic = div_magic((max_nodes + 31) / 32);
     p.node_token = node_token; p.node_parent = node_parent; p.node_depth = node_depth; p.node_strict = node_strict;
     p.n_nodes = n_nodes; p.mask = mask; p.cand_node = cand_node;
     hipLaunchKernelGGL(aasd::build_tree_kernel, dim3((unsigned)B), dim3(aasd::kTreeBlock), 0, (hipStream_t)stream, p);

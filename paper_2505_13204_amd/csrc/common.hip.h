@@ -176,4 +176,10 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
     out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
 }
 
+// u / d by one multiply, for u < 2^32 / d: magic = floor(2^32 / d) + 1, computed by the host (0 for d = 1).
+__device__ __forceinline__ uint32_t div_small(uint32_t u, int d, uint32_t magic)
+{
+    return d == 1 ? u : __umulhi(u, magic);
+}
+
 }  // namespace aasd

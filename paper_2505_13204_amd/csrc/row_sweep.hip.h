@@ -698,7 +698,7 @@ __device__ __forceinline__ WavePartial merge_wave_partials(const WavePartial* wa
 // u / nseg for a unit index below 2^28 (a launch has at most 2^22) without an integer division: one multiply.
 __device__ __forceinline__ uint32_t div_by_segments(uint32_t u, int nseg, uint32_t magic)
 {
-    return nseg == 1 ? u : __umulhi(u, magic);
+    return div_small(u, nseg, magic);
 }
 
 // Streaming kernel: grid = rows x segments; the launch starts at row row0.

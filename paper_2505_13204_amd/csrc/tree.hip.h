@@ -18,6 +18,7 @@ struct BuildTreeParams {
     int32_t m_x;
     const int32_t* root_tok;      // [B] or null
     int32_t B, C, k, max_nodes;
+    uint32_t w_magic;             // floor(2^32 / W) + 1 for W = ceil(max_nodes / 32) mask words per row (0 for W = 1)
     int32_t* node_token;
     int32_t* node_parent;
     int32_t* node_depth;
@@ -26,6 +27,89 @@ struct BuildTreeParams {
     uint32_t* mask;               // [B, max_nodes, W] or null
     int32_t* cand_node;           // [B, C, k] or null
 };
+
+// The layer loop of build_tree_kernel for a sequence whose events of one layer fit one wave (C * (1 + m) <= 64:
+// the paper's 16 candidates with two extras each are 48).  One wave, a lane per event, no barrier and no LDS
+// traffic between lanes except the nodes' own arrays.  The events of a layer are grouped by key, one group per
+// trip of a loop: the lowest lane not yet grouped names a key (two lane reads), a ballot finds the lanes that
+// share it, and since the trips go through the first events in ascending order the group's node is simply the
+// next free one, which is the numbering of a serial insertion into a (parent, token) dictionary.  Every lane
+// of a candidate keeps the node at the end of the candidate's path in a register.  The lane of a node's first
+// event writes its mask row (the parent's row plus the node's own bit) with 16-byte LDS accesses.
+// Same events, same order, same node numbers as the workgroup-wide loop of the kernel.  Returns the node count.
+__device__ __forceinline__ int tree_layers_one_wave(int lane, int C, int k, int m, int N, int Wp,
+                                                    const int* s_tok, const int* s_x, const unsigned char* s_strict,
+                                                    const int* s_dl, int* s_cn, int* n_tok, int* n_par, int* n_dep,
+                                                    unsigned char* n_str, uint32_t* n_mask)
+{
+    const int per = 1 + m, E = C * per;
+    const int e = lane, c = e < E ? e / per : 0, slot = e - (e / per) * per;
+    const int dl = e < E ? s_dl[c] : 0;
+    const int own_lane = c * per;   // the lane of the candidate's own token (slot 0)
+    // this lane's event of layer j: what it would add does not depend on where the candidate's path stands
+    auto load_event = [&](int j, int& main_tok, int& x, int& st) {
+        const bool have = e < E && j <= dl;
+        const int at = c * k + (j - 1);
+        main_tok = have ? s_tok[at] : -1;
+        x = (have && slot > 0) ? s_x[at * m + (slot - 1)] : -1;
+        st = (have && slot == 0) ? s_strict[at] : 0;   // extras are verified conditionally
+    };
+    int main_tok, x, st;
+    load_event(1, main_tok, x, st);
+    int cur = 0;                    // node at the end of the candidate's path; every path starts at the root
+    int n = 1;
+    for (int j = 1; j <= k; ++j) {
+        const int par = cur;
+        const int tok = slot == 0 ? main_tok : x;
+        const int at = c * k + (j - 1);
+        // a missing token ends the candidate's path, extras included
+        const bool valid = e < E && j <= dl && par >= 0 && main_tok >= 0 && tok >= 0;
+        const bool conditional_event = valid && st == 0;
+        unsigned long long remaining = __ballot(valid);
+        if (remaining == 0ull) break;   // no candidate reaches this layer
+        const unsigned long long conditional = __ballot(conditional_event);
+        if (j < k) load_event(j + 1, main_tok, x, st);   // the next layer's event, in flight behind this layer's work
+        // Per trip the lanes do one select; everything else is kept in scalar masks and read out after the loop.
+        int nid = -1, created = 0;
+        unsigned long long firsts = 0ull, cond_groups = 0ull;
+        while (remaining != 0ull) {   // one trip per distinct key of the layer
+            const int L = __ffsll((long long)remaining) - 1;
+            const int bpar = __builtin_amdgcn_readlane(par, L), btok = __builtin_amdgcn_readlane(tok, L);
+            const bool in = valid && par == bpar && tok == btok;
+            const unsigned long long grp = __ballot(in);
+            if (in) nid = n + created < N ? n + created : -1;   // beyond the node budget: dropped
+            firsts |= 1ull << L;
+            if ((grp & conditional) != 0ull) cond_groups |= grp;   // one conditional source makes the node conditional
+            remaining &= ~grp;
+            ++created;
+        }
+        const bool first = ((firsts >> lane) & 1ull) != 0ull;
+        const bool cond_node = ((cond_groups >> lane) & 1ull) != 0ull;
+        const int cur_next = __shfl(nid, own_lane);   // the node of the candidate's own token; -1 if that is missing
+        if (first && nid >= 0) {
+            n_tok[nid] = tok; n_par[nid] = par; n_dep[nid] = j; n_str[nid] = cond_node ? 0 : 1;
+            // the mask row: the parent's row (an earlier layer's) plus the node's own bit; rows are 16-byte aligned
+            const u32x4* src = reinterpret_cast<const u32x4*>(n_mask + par * Wp);
+            u32x4* dst = reinterpret_cast<u32x4*>(n_mask + nid * Wp);
+            constexpr int kMaxQ = AASD_MAX_TREE_NODES / 128;
+            u32x4 row[kMaxQ];
+#pragma unroll
+            for (int q = 0; q < kMaxQ; ++q)
+                if (q * 4 < Wp) row[q] = src[q];
+#pragma unroll
+            for (int q = 0; q < kMaxQ; ++q)
+                if (q * 4 < Wp) dst[q] = row[q];
+            __hip_atomic_fetch_or(n_mask + nid * Wp + (nid >> 5), 1u << (nid & 31), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+        }
+        cur = cur_next;   // -1 if the candidate's own token is missing: its path has ended
+        if (valid && slot == 0) s_cn[at] = nid;
+        n = n + created < N ? n + created : N;
+        // One wave issues its LDS instructions in order, so the next layer's reads of these rows need no wait: the
+        // fence only keeps the compiler from moving them.
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+    }
+    return n;
+}
 
 // One workgroup per sequence.  The candidates, their flags and their extras are first staged in LDS in one
 // coalesced pass, so that the layer loop touches no global memory.  The tree grows layer by layer.  In layer j
@@ -49,12 +133,13 @@ __global__ __launch_bounds__(kTreeBlock) void build_tree_kernel(BuildTreeParams 
     __shared__ int cur[AASD_MAX_CANDIDATES];
     __shared__ int n_tok[AASD_MAX_TREE_NODES], n_par[AASD_MAX_TREE_NODES], n_dep[AASD_MAX_TREE_NODES];
     __shared__ unsigned char n_str[AASD_MAX_TREE_NODES];
-    __shared__ uint32_t n_mask[AASD_MAX_TREE_NODES * kMaxW];
+    __shared__ __align__(16) uint32_t n_mask[AASD_MAX_TREE_NODES * kMaxW];   // rows of Wp words (W rounded up to 4)
     __shared__ int wave_cnt[kTreeBlock / kWave];
+    __shared__ int s_n;
 
     const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
     const int C = p.C, k = p.k, m = p.draft_extras ? p.m_x : 0, N = p.max_nodes;
-    const int W = (N + 31) / 32;
+    const int W = (N + 31) / 32, Wp = (W + 3) & ~3;
     const int per = 1 + m, E = C * per, CK = C * k;
     const int e = tid, c = e < E ? e / per : 0, slot = e - (e / per) * per;
     const size_t bck = (size_t)b * CK;
@@ -74,12 +159,21 @@ __global__ __launch_bounds__(kTreeBlock) void build_tree_kernel(BuildTreeParams 
         n_tok[0] = p.root_tok ? p.root_tok[b] : -1;
         n_par[0] = -1; n_dep[0] = 0; n_str[0] = 0;
     }
-    if (tid < W) n_mask[tid] = tid == 0 ? 1u : 0u;   // the root sees itself
+    if (tid < Wp) n_mask[tid] = tid == 0 ? 1u : 0u;   // the root sees itself
     __syncthreads();
     const int dl = e < E ? s_dl[c] : 0;
 
     int n = 1;  // nodes so far: the same value in every thread
-    for (int j = 1; j <= k; ++j) {
+    const bool one_wave = E <= kWave;
+    if (one_wave) {   // the usual case: one wave builds the layers without a barrier
+        if (wid == 0) {
+            const int nn = tree_layers_one_wave(lane, C, k, m, N, Wp, s_tok, s_x, s_strict, s_dl, s_cn, n_tok, n_par, n_dep, n_str, n_mask);
+            if (lane == 0) s_n = nn;
+        }
+        __syncthreads();
+        n = s_n;
+    }
+    for (int j = 1; !one_wave && j <= k; ++j) {   // more events per layer than a wave has lanes: a thread per event, barriers between the phases
         bool valid = false;
         int tok = -1, par = -1, st = 0;
         if (e < E) {
@@ -125,8 +219,8 @@ __global__ __launch_bounds__(kTreeBlock) void build_tree_kernel(BuildTreeParams 
             ev_node[e] = id;
             if (id >= 0) {
                 n_tok[id] = tok; n_par[id] = par; n_dep[id] = j;
-                for (int wi = 0; wi < W; ++wi)   // the parent's row (an earlier layer) plus the node's own bit
-                    n_mask[id * W + wi] = n_mask[par * W + wi] | ((id >> 5) == wi ? 1u << (id & 31) : 0u);
+                for (int wi = 0; wi < Wp; ++wi)   // the parent's row (an earlier layer) plus the node's own bit
+                    n_mask[id * Wp + wi] = n_mask[par * Wp + wi] | ((id >> 5) == wi ? 1u << (id & 31) : 0u);
             }
         }
         __syncthreads();
@@ -152,7 +246,10 @@ __global__ __launch_bounds__(kTreeBlock) void build_tree_kernel(BuildTreeParams 
         p.node_strict[bi] = used ? n_str[i] : 0;
     }
     if (p.mask)
-        for (int i = tid; i < N * W; i += kTreeBlock) p.mask[(size_t)b * N * W + i] = i < n * W ? n_mask[i] : 0u;
+        for (int i = tid; i < N * W; i += kTreeBlock) {
+            const int q = (int)div_small((uint32_t)i, W, p.w_magic);   // node q, word i - q * W
+            p.mask[(size_t)b * N * W + i] = q < n ? n_mask[q * Wp + (i - q * W)] : 0u;
+        }
     if (p.cand_node)
         for (int i = tid; i < CK; i += kTreeBlock) p.cand_node[bck + i] = s_cn[i];
 }
