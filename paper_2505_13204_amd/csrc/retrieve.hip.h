@@ -99,16 +99,15 @@ __global__ __launch_bounds__(BLOCK) void retrieve_kernel(RetrieveParams p)
     const int n_min = p.n_min, C = p.C, k = p.k;
     const int n_cap = min(p.n_max, len - 1);  // a key must be shorter than the context
 
-    // A context that fits one tile is staged at once, and the suffix and the continuations are then read from LDS
-    // instead of through further dependent loads from memory (the chain is: length, tokens; not length, suffix,
-    // tokens, continuations).
+    // A context that fits one tile is staged at once, and the continuations are then read from LDS instead of
+    // through further dependent loads from memory.  The last tokens (the keys) are asked for beside the tile's,
+    // so the chain of dependent loads is: length, tokens.
     const bool one_tile = len <= p.tile;
-    if (one_tile) {
+    int32_t last_tok = 0;
+    if (tid < AASD_MAX_KEY && len - 1 - tid >= 0) last_tok = tok[len - 1 - tid];
+    if (one_tile)
         for (int i = tid; i < len + AASD_MAX_KEY; i += BLOCK) ltok[i] = i >= AASD_MAX_KEY ? tok[i - AASD_MAX_KEY] : 0;
-        __syncthreads();
-    }
-    if (tid < AASD_MAX_KEY)
-        suffix[tid] = (len - 1 - tid >= 0) ? (one_tile ? ltok[len - 1 - tid + AASD_MAX_KEY] : tok[len - 1 - tid]) : 0;
+    if (tid < AASD_MAX_KEY) suffix[tid] = last_tok;
     if (tid == 0) s_best = 0;
     for (int i = tid; i < kRetrieveTileSlots; i += BLOCK) tile_best[i] = 0;
     __syncthreads();
@@ -121,7 +120,10 @@ __global__ __launch_bounds__(BLOCK) void retrieve_kernel(RetrieveParams p)
             hs = hs * kHashBase + (uint32_t)suffix[n_min - 1 - i];
             bpow *= kHashBase;
         }
-        const int tile = p.tile, run = p.run;
+        // A short context is spread over all threads: a thread's run of positions is a serial loop, so it is made
+        // as short as the context allows (odd, like the host's choice for a full tile).
+        const int tile = p.tile;
+        const int run = one_tile ? min(p.run, ((len + BLOCK - 1) / BLOCK) | 1) : p.run;
         const int ntiles = (len + tile - 1) / tile;
 
         // Stage tile t and compute the match length of each of its positions.
@@ -168,7 +170,7 @@ __global__ __launch_bounds__(BLOCK) void retrieve_kernel(RetrieveParams p)
             if (t > 0) __syncthreads();  // the previous tile is no longer read
             int tb = stage_and_match(t);
             best = max(best, tb);
-            if (t < kRetrieveTileSlots) {
+            if (ntiles > 1 && t < kRetrieveTileSlots) {   // which tiles hold the longest key matters only if there are several
                 tb = wave_max(tb);
                 if (lane == 0 && tb > 0) atomicMax(&tile_best[t], tb);
             }
@@ -184,13 +186,12 @@ __global__ __launch_bounds__(BLOCK) void retrieve_kernel(RetrieveParams p)
         if (n_star > 0) {
             int resident = ntiles - 1;   // the tile whose match lengths are in LDS
             for (int t = ntiles - 1; t >= 0 && count < C; --t) {
-                if (t < kRetrieveTileSlots && tile_best[t] < n_star) continue;   // the same in every thread
-                if (t != resident) {
-                    __syncthreads();
+                if (ntiles > 1 && t < kRetrieveTileSlots && tile_best[t] < n_star) continue;   // the same in every thread
+                if (t != resident) {   // every thread is past the barrier that ended its reads of the tile before
                     stage_and_match(t);
                     resident = t;
                 }
-                __syncthreads();
+                // a thread reads the match lengths of its own run only: no barrier between writing and counting them
                 const int tlo = t * tile;
                 const int thi = min(tlo + tile, len);
                 const int pstart = tlo + tid * run;
