@@ -27,6 +27,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+# the oracle leg repeats its sample until it has run this long (a short workload alone gives too short a timing)
+CPU_BASELINE_MIN_S = 10.0
+CPU_BASELINE_MAX_PASSES = 8
 
 
 def parse():
@@ -588,17 +591,20 @@ def main():
         len_h = len_b[:nb].cpu().numpy()
         plen_h = plen_b[:nb].cpu().numpy()
         tc = time.perf_counter()
-        oracle.align_sample(bits_a, next_tok[:n_a], m_x=w.m, c=w.c, mode=mode)
-        r = oracle.retrieve_drafts(tok_h, len_h, plen_h, w.n_min, w.n_max, w.k, w.C)
-        if topk:
-            oracle.verify_topk(bits_v, r["drafts"], r["draft_len"], topk=args.topk)
-        else:
-            oracle.verify(bits_v, r["drafts"], r["draft_len"], r["strict"], alpha=float(np.float32(w.alpha)),
-                          beta=float(np.float32(w.beta)))
+        passes = 0
+        while passes < CPU_BASELINE_MAX_PASSES and (passes == 0 or time.perf_counter() - tc < CPU_BASELINE_MIN_S):
+            oracle.align_sample(bits_a, next_tok[:n_a], m_x=w.m, c=w.c, mode=mode)
+            r = oracle.retrieve_drafts(tok_h, len_h, plen_h, w.n_min, w.n_max, w.k, w.C)
+            if topk:
+                oracle.verify_topk(bits_v, r["drafts"], r["draft_len"], topk=args.topk)
+            else:
+                oracle.verify(bits_v, r["drafts"], r["draft_len"], r["strict"], alpha=float(np.float32(w.alpha)),
+                              beta=float(np.float32(w.beta)))
+            passes += 1
         dt = time.perf_counter() - tc
-        cpu = {"value": round((n_a + nb * w.R) / dt, 1), "unit": "rows/s", "cores": 1, "kind": "oracle",
+        cpu = {"value": round(passes * (n_a + nb * w.R) / dt, 1), "unit": "rows/s", "cores": 1, "kind": "oracle",
                "sample": f"first {n_a} prefill rows + first {n_s} decode steps ({nb * w.R} verify rows) of the same "
-                         f"workload, {dt:.1f} s", "host_cores_present": os.cpu_count()}
+                         f"workload, {passes} pass{'es' if passes > 1 else ''}, {dt:.1f} s", "host_cores_present": os.cpu_count()}
 
     out = {
         "metric": "logit rows/sec verified+sampled at V=%d %s" % (w.V, w.dtype),
@@ -871,16 +877,20 @@ def bench_tree(args, w, dev):
         ex_h, nx_h = extras_b[:nb * w.L].cpu().numpy(), n_extras_b[:nb * w.L].cpu().numpy()
         root_h = root_b[:nb].cpu().numpy()
         tc = time.perf_counter()
-        oracle.align_sample(bits_a, next_tok[:n_a], m_x=w.m, c=w.c)
-        r = oracle.retrieve_drafts(tok_h, len_h[:nb], np.full(nb, w.L, np.int32), w.n_min, w.n_max, w.k, w.C,
-                                   extras=ex_h, n_extras=nx_h, m_x=w.m, extras_stride=w.L)
-        t = oracle.build_tree(r["drafts"], r["draft_len"], r["strict"], r["draft_extras"], root_tok=root_h, max_nodes=N)
-        oracle.verify_tree(bits_v, t["node_token"], t["node_parent"], t["node_strict"], t["n_nodes"],
-                           alpha=float(np.float32(w.alpha)), beta=float(np.float32(w.beta)))
+        passes = 0
+        while passes < CPU_BASELINE_MAX_PASSES and (passes == 0 or time.perf_counter() - tc < CPU_BASELINE_MIN_S):
+            oracle.align_sample(bits_a, next_tok[:n_a], m_x=w.m, c=w.c)
+            r = oracle.retrieve_drafts(tok_h, len_h[:nb], np.full(nb, w.L, np.int32), w.n_min, w.n_max, w.k, w.C,
+                                       extras=ex_h, n_extras=nx_h, m_x=w.m, extras_stride=w.L)
+            t = oracle.build_tree(r["drafts"], r["draft_len"], r["strict"], r["draft_extras"], root_tok=root_h, max_nodes=N)
+            oracle.verify_tree(bits_v, t["node_token"], t["node_parent"], t["node_strict"], t["n_nodes"],
+                               alpha=float(np.float32(w.alpha)), beta=float(np.float32(w.beta)))
+            passes += 1
         dtc = time.perf_counter() - tc
         used = int(t["n_nodes"].sum())
-        cpu = {"value": round((n_a + used) / dtc, 1), "unit": "rows/s", "cores": 1, "kind": "oracle",
-               "sample": f"first {n_a} prefill rows + first {nb} trees ({used} tree rows) of the same workload, {dtc:.1f} s",
+        cpu = {"value": round(passes * (n_a + used) / dtc, 1), "unit": "rows/s", "cores": 1, "kind": "oracle",
+               "sample": f"first {n_a} prefill rows + first {nb} trees ({used} tree rows) of the same workload, "
+                         f"{passes} pass{'es' if passes > 1 else ''}, {dtc:.1f} s",
                "host_cores_present": os.cpu_count()}
 
     out = {
