@@ -121,6 +121,21 @@ __device__ __forceinline__ int wave_min(int v)
     return min(min(lane_value(v, 0), lane_value(v, 16)), min(lane_value(v, 32), lane_value(v, 48)));
 }
 
+// Inclusive prefix sum over the 64 lanes of a wave (every lane takes part), through the vector ALU's cross-lane
+// moves: shifts by 1, 2, 4, 8 inside each row of 16 lanes (lanes without a source add zero), then the last lane of
+// row 0 (and of row 2) is added to the next row, and the last lane of row 1 to rows 2 and 3.
+__device__ __forceinline__ int wave_inclusive_scan(int v)
+{
+    constexpr int kRowShr1 = 0x111, kRowShr2 = 0x112, kRowShr4 = 0x114, kRowShr8 = 0x118, kRowBcast15 = 0x142, kRowBcast31 = 0x143;
+    v += __builtin_amdgcn_update_dpp(0, v, kRowShr1, 0xf, 0xf, true);
+    v += __builtin_amdgcn_update_dpp(0, v, kRowShr2, 0xf, 0xf, true);
+    v += __builtin_amdgcn_update_dpp(0, v, kRowShr4, 0xf, 0xf, true);
+    v += __builtin_amdgcn_update_dpp(0, v, kRowShr8, 0xf, 0xf, true);
+    v += __builtin_amdgcn_update_dpp(0, v, kRowBcast15, 0xa, 0xf, false);   // into rows 1 and 3
+    v += __builtin_amdgcn_update_dpp(0, v, kRowBcast31, 0xc, 0xf, false);   // into rows 2 and 3
+    return v;
+}
+
 // All-reduce over the lane's aligned group of G <= 64 lanes (G a power of two, the same in every lane; every lane of
 // the wave takes part): inside a row of 16 lanes through the vector ALU's cross-lane moves, beyond it through scalar
 // registers.  The order of combination is fixed.

@@ -73,9 +73,9 @@ __device__ __forceinline__ void pool_update_wave(const PoolUpdateParams& q, int 
         if (have) h = __hip_atomic_load(&head[bucket], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         int last = -1;
         bool later = false;
-#pragma unroll
-        for (int j = 0; j < kWave; ++j) {
-            const int bj = __shfl(bucket, j);
+        const int cnt = min(kWave, len + 1 - p0);   // the batch's positions sit in lanes 0 .. cnt-1 (a decode step: a few)
+        for (int j = 0; j < cnt; ++j) {
+            const int bj = __builtin_amdgcn_readlane(bucket, j);
             if (bj == bucket && j < lane) last = j;
             if (bj == bucket && j > lane) later = true;
         }

@@ -61,7 +61,8 @@ __device__ __forceinline__ void write_candidates(const RetrieveParams& p, int b,
                 // prefill row pp+j-1 predicted the token at pp+j; it has a next prompt token iff pp+j <= plen-1
                 if (in && pp + j <= plen - 1 && (int64_t)(pp + j - 1) < p.extras_stride) {
                     const size_t row = (size_t)b * p.extras_stride + (size_t)(pp + j - 1);
-                    if (e < (int)p.n_extras[row]) val = p.extras[row * p.m_x + e];
+                    const int32_t x = p.extras[row * p.m_x + e];   // asked for beside the count, not after it
+                    if (e < (int)p.n_extras[row]) val = x;
                 }
                 p.draft_extras[(bc * k + j) * p.m_x + e] = val;
             }

@@ -153,12 +153,7 @@ __device__ __forceinline__ void row_topc_from_lists(const AlignFinishParams& p, 
     // inclusive prefix of the list lengths: entry e of the row belongs to the first partial whose prefix exceeds e.
     // A partial whose maximum is below the row's bound (or not above znext) cannot hold a candidate: its list is
     // skipped, which matters when a row was cut into many segments (up to 64 lists).
-    int incl = (lane < np && wp.m >= thr2 && wp.m > znext) ? wp.nlist : 0;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        const int up = __shfl_up(incl, o);
-        if (lane >= o) incl += up;
-    }
+    const int incl = wave_inclusive_scan((lane < np && wp.m >= thr2 && wp.m > znext) ? wp.nlist : 0);
     const int total = __shfl(incl, 63);
     auto locate = [&](int e, int& part, int& entry) {  // all lanes call it together
         // binary search for the number of partials whose inclusive prefix is <= e

@@ -749,12 +749,7 @@ __global__ __launch_bounds__(BLOCK) void row_sweep_used_kernel(SweepParams p, in
         v = p.rows_used[seq0 + tid];
         v = v < 1 ? 1 : (v > p.rows_per_seq ? p.rows_per_seq : v);
     }
-    int incl = v;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        const int up = __shfl_up(incl, o);
-        if (lane >= o) incl += up;
-    }
+    const int incl = wave_inclusive_scan(v);
     if (lane == 63) wave_total[wid] = incl;
     __syncthreads();
     int before = 0;
