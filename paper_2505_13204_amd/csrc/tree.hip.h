@@ -115,9 +115,11 @@ __device__ __forceinline__ int tree_layers_one_wave(int lane, int C, int k, int 
 // coalesced pass, so that the layer loop touches no global memory.  The tree grows layer by layer.  In layer j
 // every (candidate, slot) pair is an event (slot 0 = the candidate's j-th token, slots 1..m = its extras) with
 // the key (node at the end of the candidate's path, token).  An event whose key no earlier event of the
-// layer has opens a node; nodes are numbered in event order by a ballot/popcount prefix, which is exactly
-// the order a serial insertion into a (parent, token) dictionary would give.  The mask row of a new node is
-// its parent's row plus its own bit.
+// layer has opens a node; nodes are numbered in event order, which is exactly the order a serial insertion
+// into a (parent, token) dictionary would give.  The mask row of a new node is its parent's row plus its own
+// bit.  A layer of at most 64 events is built by one wave (tree_layers_one_wave above); a larger one by a
+// thread per event: the earliest event with the same key by an all-pairs compare over LDS, the numbers by a
+// ballot/popcount prefix over the waves, with barriers between the phases.
 __global__ __launch_bounds__(kTreeBlock) void build_tree_kernel(BuildTreeParams p)
 {
     constexpr int kMaxW = AASD_MAX_TREE_NODES / 32;
