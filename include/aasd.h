@@ -25,8 +25,10 @@
  *   - All reductions have a fixed order and no floating-point atomics are
  *     used: the same inputs give byte-identical outputs on every run.
  *   - The library reads no environment variable and keeps no state between
- *     calls besides the last error message.  (Measurement and test hooks, off
- *     by default, are declared apart in aasd_hooks.h.)
+ *     calls besides the last error message and, once aasd_verify_static has
+ *     been called on a GPU, the address and the state of that GPU's scratch
+ *     array.  (Measurement and test hooks, off by default, are declared apart
+ *     in aasd_hooks.h.)
  */
 #ifndef AASD_H
 #define AASD_H
