@@ -44,7 +44,7 @@ def _build_both(drafts, dl, strict, dx, root, N):
 @pytest.mark.parametrize("C,k,m,N", [(1, 1, 0, 1), (1, 4, 0, 8), (3, 4, 2, 64), (8, 8, 2, 40), (16, 8, 2, 256),
                                      (32, 16, 4, 256), (4, 6, 3, 5), (32, 16, 4, 33), (16, 8, 0, 129),
                                      (16, 8, 2, 385), (16, 8, 2, 512), (32, 16, 4, 512), (16, 8, 2, 300),
-                                     (16, 5, 3, 200), (13, 5, 4, 200)])   # 64 and 65 events per layer: the last shape one wave builds, the first it does not
+                                     (16, 5, 3, 200), (13, 5, 4, 200), (8, 16, 2, 300), (32, 3, 1, 97), (21, 4, 2, 33)])   # 64 and 65 events per layer: the last shape one wave builds, the first it does not
 def test_build_tree_random_small_alphabet(C, k, m, N):
     rng = np.random.default_rng(C * 100 + k)
     for B, alphabet in [(12, 3), (5, 50), (1, 2)]:
