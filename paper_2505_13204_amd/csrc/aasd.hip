@@ -64,11 +64,8 @@ SweepPlan plan_sweep(bool align, int64_t rows, int32_t V, int32_t dt)
     const int per_vec = dt == AASD_BF16 ? 8 : 4;
     const int nvec_max = V / per_vec > 0 ? V / per_vec : 1;
     SweepPlan pl{256, 2, 1, 0, 0};
-    // A verification of 8192 to 16383 rows is still cut in two: its last workgroups run alone for as long as one of
-    // them takes, which is felt in a launch of four rounds (8256 rows of V = 152064: 368 us against 376).
-    if (rows > 0 && rows < (align ? kSplitBelowRows : 2 * kSplitBelowRows)) {
-        // workgroups wanted (measured: 2048 alignment rows are fastest in 3 segments, 4608 verify rows in 2)
-        const int64_t target = align ? 6144 : (rows < kSplitBelowRows ? 8192 : 16384);
+    if (rows > 0 && rows < kSplitBelowRows) {
+        const int64_t target = align ? 6144 : 8192;   // workgroups wanted (measured: 2048 alignment rows are fastest in 3 segments, 4608 verify rows in 2)
         const int64_t want = (target + rows - 1) / rows;
         const int by_len = nvec_max / (pl.block * 2) > 0 ? nvec_max / (pl.block * 2) : 1;  // >= 2 vectors per lane
         const int by_part = aasd::kMaxPartials / (pl.block / aasd::kWave);

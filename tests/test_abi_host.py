@@ -139,10 +139,8 @@ def test_sweep_plan_hook_accepts_compiled_shapes_only(lib):
 def test_workspace_query(lib):
     """Arrival counters (a 128-byte line per sequence, plus one per group of workgroups in short launches), then one
     32-byte partial per wave of the sweep; alignment sampling adds a list of 48 chunk positions."""
-    mid = lib.aasd_verify_workspace_bytes(64, 16, 8, 152064, 1)      # 8256 rows: still cut in two, 2 x 4 waves per row
-    assert mid == 64 * 128 + 64 * 129 * 2 * 4 * 32
-    big = lib.aasd_verify_workspace_bytes(128, 16, 8, 152064, 1)     # 16512 rows, one workgroup of 4 waves per row
-    assert big == 128 * 128 + 128 * 129 * 4 * 32
+    big = lib.aasd_verify_workspace_bytes(64, 16, 8, 152064, 1)      # 8256 rows, one workgroup of 4 waves per row
+    assert big == 64 * 128 + 64 * 129 * 4 * 32
     small = lib.aasd_verify_workspace_bytes(1, 1, 8, 128256, 1)        # 9 rows: rows are cut into 16 segments, 144 workgroups in 12 groups
     assert small == 13 * 128 + 9 * 16 * 4 * 32
     assert lib.aasd_verify_workspace_bytes(1, 0, 4, 100, 1) == 0
@@ -194,8 +192,7 @@ def test_verify_tree_rejects_invalid_arguments(lib):
     assert _verify_tree(lib, wsb=lib.aasd_verify_tree_workspace_bytes(2, 16, 100, 1) - 1) == WORKSPACE
     assert _verify_tree(lib, ws=FAKE + 4) == WORKSPACE
     assert _verify_tree(lib, B=0) == 0
-    assert lib.aasd_verify_tree_workspace_bytes(128, 64, 128256, 1) == 128 * 64 * 2 * 4 * 32   # 8192 rows: two segments of 4 waves per row
-    assert lib.aasd_verify_tree_workspace_bytes(256, 64, 128256, 1) == 256 * 64 * 4 * 32       # 16384 rows: 4 waves per row
+    assert lib.aasd_verify_tree_workspace_bytes(128, 64, 128256, 1) == 128 * 64 * 4 * 32   # 8192 rows, 4 waves per row
     assert lib.aasd_verify_tree_workspace_bytes(1, 0, 100, 1) == 0
     assert lib.aasd_verify_tree_workspace_bytes(1, 513, 100, 1) == 0
 
