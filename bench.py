@@ -178,11 +178,13 @@ def per_step_block(torch, np, aasd, label, logits_steps, tokens, lens, plens, w,
     elt = logits_steps[0].element_size()
     dt_code = aasd.BF16 if elt == 2 else aasd.F32
     step_bytes = B * R * V * elt
-    ws = torch.zeros(max(128, aasd.verify_workspace_bytes(B, w.C, w.k, V, dt_code)), dtype=torch.uint8, device=dev)
+    ws_bytes = max(128, aasd.verify_workspace_bytes(B, w.C, w.k, V, dt_code))
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    ws_zeroed = torch.zeros(ws_bytes, dtype=torch.uint8, device=dev)   # only ever passed with AASD_VERIFY_ZEROED_WORKSPACE
     r = aasd.retrieve_drafts(tokens[0], lens[0], plens, w.n_min, w.n_max, w.k, w.C)
-    kw = dict(alpha=w.alpha, beta=w.beta, want_rows=False, want_tokens=False, want_near=True, workspace=ws)
-    v = aasd.verify(logits_steps[0], r["drafts"], r["draft_len"], r["strict"], zeroed_workspace=True, **kw)
-    v2 = aasd.verify(logits_steps[0], r["drafts"], r["draft_len"], r["strict"], **kw)
+    kw = dict(alpha=w.alpha, beta=w.beta, want_rows=False, want_tokens=False, want_near=True)
+    v = aasd.verify(logits_steps[0], r["drafts"], r["draft_len"], r["strict"], zeroed_workspace=True, workspace=ws_zeroed, **kw)
+    v2 = aasd.verify(logits_steps[0], r["drafts"], r["draft_len"], r["strict"], workspace=ws, **kw)
     # Retrieval both ways: the stateless scan, and the persistent pool: built once over the longest context (timed:
     # the cost at the end of prefill), then rebuilt at the first step's length; aasd_pool_step indexes what a step
     # added and looks up.  The step lengths ascend through the first pass over the buffers (real incremental updates);
@@ -205,7 +207,7 @@ def per_step_block(torch, np, aasd, label, logits_steps, tokens, lens, plens, w,
         elif with_retrieve:
             aasd.retrieve_drafts(tokens[i % n], lens[i % n], plens, w.n_min, w.n_max, w.k, w.C, out=r)
         aasd.verify(logits_steps[i % n], r["drafts"], r["draft_len"], r["strict"], zeroed_workspace=one_launch,
-                    out=v if one_launch else v2, **kw)
+                    workspace=ws_zeroed if one_launch else ws, out=v if one_launch else v2, **kw)
 
     m = max(n, 64)
     scan_eager, scan_graph = time_steps(torch, lambda i: step(i, through_pool=False), m)
