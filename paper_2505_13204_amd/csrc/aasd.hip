@@ -95,6 +95,15 @@ SweepPlan plan_sweep(bool align, int64_t rows, int32_t V, int32_t dt)
     return pl;
 }
 
+// Plan of the tree-verification sweep.  The logits have room for max_nodes rows per tree, but a tree rarely fills its
+// budget and the host does not know the counts, so the rows are cut as if a quarter of them were in use: a sparse
+// batch then still has enough workgroups to fill the GPU (256 trees with 1695 of 24832 rows in use: 2 segments per
+// row), and a full one only gets more, shorter workgroups, which a long launch does not feel.
+SweepPlan plan_tree_sweep(int64_t rows, int32_t V, int32_t dt)
+{
+    return plan_sweep(false, rows >= 4 ? rows / 4 : 1, V, dt);
+}
+
 // Plan of the one-launch form of verification.  Its workgroups do not end with the sweep: each sends its partial
 // to memory, waits, and is counted in (about a microsecond without loads in flight).  That costs nothing while
 // all workgroups of the launch are on the GPU at once (it is paid once, at the end), so a short launch is cut into
@@ -940,7 +949,7 @@ size_t aasd_verify_tree_workspace_bytes(int32_t B, int32_t N, int32_t V, int32_t
 {
     if (B < 0 || N < 1 || N > AASD_MAX_TREE_NODES || V <= 0 || !valid_dtype(dt)) return 0;
     const int64_t rows = (int64_t)B * N;
-    const SweepPlan pl = plan_sweep(false, rows, V, dt);
+    const SweepPlan pl = plan_tree_sweep(rows, V, dt);
     return (size_t)rows * pl.npart * sizeof(aasd::WavePartial);
 }
 
@@ -973,7 +982,7 @@ int aasd_verify_tree(const void* logits, int32_t dt, int32_t B, int32_t N, int32
 
     hipStream_t s = (hipStream_t)stream;
     const int64_t rows = (int64_t)B * N;
-    const SweepPlan pl = plan_sweep(false, rows, V, dt);
+    const SweepPlan pl = plan_tree_sweep(rows, V, dt);
     aasd::SweepParams sp{};
     sp.logits = logits; sp.V = V; sp.row_stride = row_stride; sp.seq_stride = seq_stride; sp.rows_per_seq = N;
     sp.rows_used = n_nodes;

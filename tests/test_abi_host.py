@@ -192,7 +192,9 @@ def test_verify_tree_rejects_invalid_arguments(lib):
     assert _verify_tree(lib, wsb=lib.aasd_verify_tree_workspace_bytes(2, 16, 100, 1) - 1) == WORKSPACE
     assert _verify_tree(lib, ws=FAKE + 4) == WORKSPACE
     assert _verify_tree(lib, B=0) == 0
-    assert lib.aasd_verify_tree_workspace_bytes(128, 64, 128256, 1) == 128 * 64 * 4 * 32   # 8192 rows, 4 waves per row
+    # the sweep is planned as if a quarter of the rows were in use: 8192 rows -> 4 segments of 4 waves per row
+    assert lib.aasd_verify_tree_workspace_bytes(128, 64, 128256, 1) == 128 * 64 * 4 * 4 * 32
+    assert lib.aasd_verify_tree_workspace_bytes(512, 64, 128256, 1) == 512 * 64 * 4 * 32      # 32768 rows: 4 waves per row
     assert lib.aasd_verify_tree_workspace_bytes(1, 0, 100, 1) == 0
     assert lib.aasd_verify_tree_workspace_bytes(1, 513, 100, 1) == 0
 
