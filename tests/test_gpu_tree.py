@@ -56,6 +56,23 @@ def test_build_tree_random_small_alphabet(C, k, m, N):
     _build_both(drafts, dl, None, None, None, N)
 
 
+@pytest.mark.parametrize("block", range(4))
+def test_build_tree_random_shapes(block):
+    """Random candidate counts, draft lengths, extras, node budgets and alphabets: layers of up to 64 events are
+    built by one wave, larger ones by the whole workgroup; both against the oracle."""
+    shapes = {True: 0, False: 0}
+    for seed in range(block * 30, block * 30 + 30):
+        rng = np.random.default_rng(50000 + seed)
+        C, k, m = int(rng.integers(1, 33)), int(rng.integers(1, 17)), int(rng.integers(0, 5))
+        N = int(rng.choice([1, 2, 5, 31, 32, 33, 64, 97, 129, 256, 385, 512, int(rng.integers(1, 513))]))
+        B = int(rng.integers(1, 7))
+        drafts, dl, strict, dx = _random_candidates(rng, B, C, k, m, int(rng.choice([1, 2, 3, 6, 50, 5000])))
+        _build_both(drafts, dl, strict if rng.random() < 0.7 else None, dx,
+                    np.arange(B, dtype=np.int32) if rng.random() < 0.5 else None, N)
+        shapes[C * (1 + m) <= 64] += 1
+    assert shapes[True] > 0 and shapes[False] > 0
+
+
 def test_build_tree_full_and_empty():
     # all candidates identical -> one chain; all different -> C*k nodes; no candidate -> the root alone
     C, k = 16, 8
