@@ -206,6 +206,27 @@ def test_every_compiled_launch_shape(shape, forced_plan):
         np.testing.assert_array_equal(got[name], ref[name], err_msg=name)
 
 
+@pytest.mark.parametrize("dtype,V", [("f32", 1_000_003), ("bf16", 4_000_037)])
+def test_vocabularies_too_large_for_the_chunk_maxima_in_lds(dtype, V):
+    """A row so long that a segment's chunk maxima do not fit LDS even in 16 segments: the alignment sweep then finds
+    a lane's candidate chunks by a second look at its share.  Odd V, so rows start at every alignment; all three
+    extras modes, and verification in both launch forms over rows of the same length."""
+    rng = np.random.default_rng(31)
+    rows = 5
+    z = _random_rows(rng, rows, V, dtype, coarse=(dtype == "bf16"))
+    nt = rng.integers(0, V, size=rows).astype(np.int32)
+    nt[0] = -1
+    tally = bk.Tally()
+    for mode in (oracle.EXTRAS_TOP, oracle.EXTRAS_SAMPLE, oracle.EXTRAS_GUMBEL):
+        got = bk.hip_align(z, nt, 2, 4, mode, seed=9)
+        ref = bk.oracle_align(z, nt, 2, 4, mode, seed=9)
+        bk.compare_align(got, ref, tally, mode)
+    assert ref["misaligned"].sum() >= 2
+    zd, drafts, dl, strict = _verify_case(rng, 1, 2, 2, V, dtype, peaked=True)
+    _verify_both(zd, drafts, dl, strict, 0.1, 0.1, 0, tally)
+    print("large vocabulary", dtype, V, tally)
+
+
 # --------------------------------------------------------------------------- retrieval
 def _retrieve_both(tokens, lens, plens, n_min, n_max, k, C, extras=None, n_extras=None, m=0, xs=0):
     ref = oracle.retrieve_drafts(tokens, lens, plens, n_min, n_max, k, C, extras=extras, n_extras=n_extras, m_x=m,
