@@ -224,6 +224,12 @@ def test_vocabularies_too_large_for_the_chunk_maxima_in_lds(dtype, V):
     assert ref["misaligned"].sum() >= 2
     zd, drafts, dl, strict = _verify_case(rng, 1, 2, 2, V, dtype, peaked=True)
     _verify_both(zd, drafts, dl, strict, 0.1, 0.1, 0, tally)
+    # top-k verification runs the alignment form of the sweep (every row lists its best tokens) over the same rows
+    ref = oracle.verify_topk(synth.to_host_bits(zd), drafts, dl, topk=5)
+    t = lambda a, dt: torch.as_tensor(np.ascontiguousarray(a), device=DEV).to(dt)
+    got = bk.to_np(aasd.verify_topk(zd, t(drafts, torch.int32), t(dl, torch.int32), topk=5))
+    for name in ("accept_len", "best_cand", "next_token", "row_argmax"):
+        np.testing.assert_array_equal(got[name], ref[name], err_msg=name)
     print("large vocabulary", dtype, V, tally)
 
 
